@@ -1,0 +1,140 @@
+/*
+ * fbq.h - C ABI of the MI355X (gfx950) library for FBQuant's inference hot path: the
+ * sub-branched weight-only-quantized linear layer
+ *
+ *     y = x . Wq^T + (x . A) . B          Wq = s * (q - z), q = packed INT3/INT4 codes
+ *
+ * i.e. y = x . W_F^T with the paper's feedback-reconstructed weight
+ * W_F = Q(W - Sigma) + Sigma, Sigma = B.A (Sec. 4.1 definition of W_F; Sec. 4.2 low-rank
+ * parametrisation; Sec. 4.3 kernel fusion: de-quantization, main projection and up-projection
+ * in one kernel sharing one output tensor, the down-projection x.A a separate small kernel).
+ *
+ * Conventions
+ *   N = output features, K = input features, M = tokens, r = rank of the sub-branch,
+ *   g = group size along K (one fp16 scale and one fp16 zero per row n and group), G = K/g,
+ *   b = bits per code (3 or 4), qmax = 2^b - 1.
+ *   The paper writes Sigma = B.A with A [r, d_in] and B [d_out, r]; this library takes the
+ *   transposes A [K, r] and B [r, N] so that y = x.A.B:  Sigma[n,k] = sum_j A[k,j] * B[j,n].
+ *   All matrices are dense row-major.  fp16 is IEEE binary16, passed as uint16_t on the host.
+ *
+ * Device layout (what fbq_pack writes and the kernels read)
+ *   qweight  uint32 words, rows contiguous, K*b/32 words per row.
+ *            b = 4: word k/8 holds code k%8 = i at bits [4i, 4i+4).
+ *            b = 3: the 32 codes k/32 = u live in words 3u..3u+2.  For j = k%32 < 30: word j/10,
+ *                   field i = j%10; fields 0..4 at bits [3i, 3i+3), fields 5..9 at bits
+ *                   [16+3(i-5), 16+3(i-5)+3).  Code 30 is spread over bit 15 of the three words
+ *                   (bit c of the code in word c), code 31 over bit 31.  No code straddles a
+ *                   16-bit half, so a mask yields two codes at once as an fp16 pair.
+ *   scales   [N, G] fp16      zeros  [N, G] fp16 (real-valued zero point, not an integer)
+ *   A        [K, r] fp16      Bt     [N, r] fp16 (B transposed: one output's r taps contiguous)
+ *
+ * Ownership and errors
+ *   The library owns no memory and keeps no mutable state.  Pointers marked "host" are read or
+ *   written by the CPU during the call; pointers marked "device" must be device memory valid on
+ *   the current HIP device, 16-byte aligned, owned by the caller, and are accessed asynchronously
+ *   on `stream` (a hipStream_t passed as void*; NULL is the default stream).  Device entry points
+ *   validate everything on the host first and return an error WITHOUT launching; they never
+ *   allocate and never synchronise.  Outputs are fully overwritten, never accumulated into.
+ */
+#ifndef FBQ_H
+#define FBQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FBQ_OK = 0,
+    FBQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    FBQ_ERR_SHAPE = 2,       /* N, K, M < 1; r < 0; K % group; K % 32; r % 8; a code above qmax */
+    FBQ_ERR_UNSUPPORTED = 3, /* bits not in {3, 4}; group != 128; r > 256; K > 32768 */
+    FBQ_ERR_ALIGN = 4,       /* a device pointer is not 16-byte aligned */
+    FBQ_ERR_WORKSPACE = 5,   /* workspace smaller than fbq_workspace_bytes() */
+    FBQ_ERR_HIP = 6          /* the HIP runtime refused a launch (hipGetLastError) */
+} fbq_status;
+
+/* One quantized layer.  r == 0 is the branch-free layer (A and Bt may then be NULL). */
+typedef struct {
+    int32_t N;      /* output features */
+    int32_t K;      /* input features, multiple of group */
+    int32_t r;      /* rank of the sub-branch, multiple of 8, 0..256 */
+    int32_t bits;   /* 3 or 4 */
+    int32_t group;  /* 128 */
+} fbq_desc;
+
+typedef void *fbq_stream;   /* hipStream_t */
+
+const char *fbq_status_string(fbq_status s);
+
+/* Validates a descriptor (FBQ_OK, FBQ_ERR_NULL, FBQ_ERR_SHAPE or FBQ_ERR_UNSUPPORTED). */
+fbq_status fbq_check_desc(const fbq_desc *d);
+
+/* Bytes of the packed code buffer, N * K * bits / 8.  0 for an invalid descriptor. */
+size_t fbq_packed_bytes(const fbq_desc *d);
+
+/* Bytes of device scratch fbq_linear needs for M tokens: the split-K partial sums of the
+ * down-projection t = x.A in fp32.  0 when r == 0; 0 for an invalid descriptor or M < 1. */
+size_t fbq_workspace_bytes(const fbq_desc *d, int M);
+
+/*
+ * fbq_pack - host side, off the hot path.  Converts canonical tensors into the device layout
+ * above (the caller then copies the outputs to the GPU).  INT3/INT4 storage of the main-path
+ * weights with floating-point inputs and outputs is the paper's setting (Sec. 1); the bit
+ * layout is this library's own.
+ *   codes      host [N, K] uint8, each in 0..qmax        qweight_out host, fbq_packed_bytes()
+ *   scales     host [N, G] fp16                           scales_out  host [N, G] fp16
+ *   zeros      host [N, G] fp16                           zeros_out   host [N, G] fp16
+ *   A          host [K, r] fp16 (NULL if r == 0)          A_out       host [K, r] fp16
+ *   B          host [r, N] fp16 (NULL if r == 0)          Bt_out      host [N, r] fp16
+ * Returns FBQ_ERR_SHAPE if a code exceeds qmax (outputs are then unspecified).
+ */
+fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *scales, const uint16_t *zeros,
+                    const uint16_t *A, const uint16_t *B, uint32_t *qweight_out, uint16_t *scales_out,
+                    uint16_t *zeros_out, uint16_t *A_out, uint16_t *Bt_out);
+
+/*
+ * fbq_linear - the hot path (Sec. 4.3).  y[m,n] = sum_k x[m,k] * s[n,k/g] * (q[n,k] - z[n,k/g])
+ *                                               + sum_j (sum_k x[m,k] * A[k,j]) * Bt[n,j]
+ * in fp32 accumulation, rounded once to fp16.  Two launches when r > 0 (down-projection into
+ * the workspace, then the fused kernel), one when r == 0.  M <= 16 runs the decode GEMV
+ * (packed words streamed once, unpacked in registers); M > 16 runs the fp16 MFMA GEMM.
+ *   x         device [M, K] fp16             qweight, scales, zeros, A, Bt: device, layout above
+ *   y         device [M, N] fp16, overwritten
+ *   workspace device, >= fbq_workspace_bytes(d, M) bytes (may be NULL when that is 0); its
+ *             contents are scratch; concurrent calls must not share it
+ * Errors: FBQ_ERR_NULL, _SHAPE, _UNSUPPORTED, _ALIGN, _WORKSPACE before any launch; FBQ_ERR_HIP.
+ */
+fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
+                      const void *zeros, const void *A, const void *Bt, void *y, void *workspace,
+                      size_t workspace_bytes, fbq_stream stream);
+
+/*
+ * fbq_reconstruct - validation.  W_hat[n,k] = s*(q - z) + sum_j A[k,j]*Bt[n,j], the paper's
+ * W_F = Q(W - Sigma) + Sigma (Sec. 4.1), as fp32.   W_hat device [N, K] fp32, overwritten.
+ */
+fbq_status fbq_reconstruct(const fbq_desc *d, const void *qweight, const void *scales, const void *zeros,
+                           const void *A, const void *Bt, float *W_hat, fbq_stream stream);
+
+/* fbq_unpack_codes - validation.  codes_out device [N, K] uint8 = the integer codes q. */
+fbq_status fbq_unpack_codes(const fbq_desc *d, const void *qweight, uint8_t *codes_out, fbq_stream stream);
+
+/*
+ * fbq_quantize_feedback - the step before the path: the feedback quantizer Q(W - Sigma) of
+ * Sec. 4.1 / Alg. 1 (forward line), group-wise asymmetric round-to-nearest, computed on the GPU
+ * in fp64 and written straight into the device layout.  Per row and group: mn, mx of
+ * R = W - Sigma; s = fp16((mx - mn)/qmax) (1 if the group is constant, never below the smallest
+ * normal fp16); z = fp16(-mn/s); s is stepped to the next fp16 until both ends of the range lie
+ * within half a step of [0, qmax]; q = clamp(round_half_even(R/s + z), 0, qmax).
+ *   W device [N, K] fp16; A device [K, r]; Bt device [N, r] (both NULL if r == 0)
+ *   qweight_out device fbq_packed_bytes(); scales_out, zeros_out device [N, G] fp16
+ */
+fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, const void *A, const void *Bt,
+                                 void *qweight_out, void *scales_out, void *zeros_out, fbq_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FBQ_H */

@@ -1,0 +1,190 @@
+// C ABI of the library: argument validation, host-side packing and kernel dispatch.
+// Every operation is defined in include/fbq.h; nothing here computes on the CPU except fbq_pack
+// (a one-off layout conversion that is off the hot path by definition).
+#include <string.h>
+
+#include "fbq_internal.h"
+
+using namespace fbq;
+
+extern "C" const char *fbq_status_string(fbq_status s)
+{
+    switch (s) {
+    case FBQ_OK: return "ok";
+    case FBQ_ERR_NULL: return "null pointer";
+    case FBQ_ERR_SHAPE: return "bad shape or value";
+    case FBQ_ERR_UNSUPPORTED: return "unsupported configuration";
+    case FBQ_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case FBQ_ERR_WORKSPACE: return "workspace too small";
+    case FBQ_ERR_HIP: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+extern "C" fbq_status fbq_check_desc(const fbq_desc *d)
+{
+    if (!d) return FBQ_ERR_NULL;
+    if (d->bits != 3 && d->bits != 4) return FBQ_ERR_UNSUPPORTED;
+    if (d->group != kGroup) return FBQ_ERR_UNSUPPORTED;
+    if (d->N < 1 || d->K < 1 || d->r < 0) return FBQ_ERR_SHAPE;
+    if (d->K % d->group || d->K % 32 || d->r % 8) return FBQ_ERR_SHAPE;
+    if (d->r > kMaxRank || d->K > kMaxK) return FBQ_ERR_UNSUPPORTED;
+    return FBQ_OK;
+}
+
+extern "C" size_t fbq_packed_bytes(const fbq_desc *d)
+{
+    if (fbq_check_desc(d) != FBQ_OK) return 0;
+    return (size_t)d->N * row_words(d->K, d->bits) * sizeof(uint32_t);
+}
+
+extern "C" size_t fbq_workspace_bytes(const fbq_desc *d, int M)
+{
+    if (fbq_check_desc(d) != FBQ_OK || M < 1 || d->r == 0) return 0;
+    if (M <= kDecodeMaxM) return (size_t)kSplitT * M * d->r * sizeof(float);
+    return prefill_workspace_bytes(M, d->r);
+}
+
+// ------------------------------------------------------------------ host-side packing
+
+// Bit c of code k within a packed row: word index and bit position (layout in fbq.h).
+static inline void code_bit_slot(int bits, int k, int c, size_t *word, int *bit)
+{
+    if (bits == 4) {
+        *word = (size_t)k >> 3;
+        *bit = ((k & 7) << 2) + c;
+        return;
+    }
+    const int unit = k >> 5, j = k & 31;
+    if (j >= 30) {
+        *word = (size_t)unit * 3 + c;
+        *bit = j == 30 ? 15 : 31;
+        return;
+    }
+    const int wd = j / 10, f = j - wd * 10;
+    *word = (size_t)unit * 3 + wd;
+    *bit = (f >= 5 ? 16 + 3 * (f - 5) : 3 * f) + c;
+}
+
+extern "C" fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *scales, const uint16_t *zeros,
+                               const uint16_t *A, const uint16_t *B, uint32_t *qweight_out, uint16_t *scales_out,
+                               uint16_t *zeros_out, uint16_t *A_out, uint16_t *Bt_out)
+{
+    fbq_status st = fbq_check_desc(d);
+    if (st != FBQ_OK) return st;
+    if (!codes || !scales || !zeros || !qweight_out || !scales_out || !zeros_out) return FBQ_ERR_NULL;
+    if (d->r > 0 && (!A || !B || !A_out || !Bt_out)) return FBQ_ERR_NULL;
+
+    const int N = d->N, K = d->K, r = d->r, bits = d->bits;
+    const size_t rw = row_words(K, bits);
+    const unsigned qmax = (1u << bits) - 1u;
+    memset(qweight_out, 0, rw * (size_t)N * sizeof(uint32_t));
+    for (int n = 0; n < N; ++n) {
+        uint32_t *row = qweight_out + rw * (size_t)n;
+        const uint8_t *crow = codes + (size_t)n * K;
+        for (int k = 0; k < K; ++k) {
+            const unsigned q = crow[k];
+            if (q > qmax) return FBQ_ERR_SHAPE;
+            for (int c = 0; c < bits; ++c) {
+                size_t w;
+                int bit;
+                code_bit_slot(bits, k, c, &w, &bit);
+                row[w] |= ((q >> c) & 1u) << bit;
+            }
+        }
+    }
+    const size_t ng = (size_t)N * (K / d->group);
+    memcpy(scales_out, scales, ng * sizeof(uint16_t));
+    memcpy(zeros_out, zeros, ng * sizeof(uint16_t));
+    if (r > 0) {
+        memcpy(A_out, A, (size_t)K * r * sizeof(uint16_t));
+        for (int n = 0; n < N; ++n)
+            for (int j = 0; j < r; ++j) Bt_out[(size_t)n * r + j] = B[(size_t)j * N + n];
+    }
+    return FBQ_OK;
+}
+
+// ------------------------------------------------------------------ device entry points
+
+static inline bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+static fbq_status hip_status(hipError_t e)
+{
+    if (e == hipSuccess) e = hipGetLastError();
+    return e == hipSuccess ? FBQ_OK : FBQ_ERR_HIP;
+}
+
+extern "C" fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
+                                 const void *zeros, const void *A, const void *Bt, void *y, void *workspace,
+                                 size_t workspace_bytes, fbq_stream stream)
+{
+    fbq_status st = fbq_check_desc(d);
+    if (st != FBQ_OK) return st;
+    if (M < 1) return FBQ_ERR_SHAPE;
+    if (!x || !qweight || !scales || !zeros || !y) return FBQ_ERR_NULL;
+    if (d->r > 0 && (!A || !Bt)) return FBQ_ERR_NULL;
+    const size_t need = fbq_workspace_bytes(d, M);
+    if (need > 0 && !workspace) return FBQ_ERR_NULL;
+    if (misaligned(x) || misaligned(qweight) || misaligned(scales) || misaligned(zeros) || misaligned(y)) return FBQ_ERR_ALIGN;
+    if (d->r > 0 && (misaligned(A) || misaligned(Bt))) return FBQ_ERR_ALIGN;
+    if (need > 0 && misaligned(workspace)) return FBQ_ERR_ALIGN;
+    if (workspace_bytes < need) return FBQ_ERR_WORKSPACE;
+
+    LinearArgs a;
+    a.qw = (const uint32_t *)qweight;
+    a.scales = (const uint16_t *)scales;
+    a.zeros = (const uint16_t *)zeros;
+    a.A = (const uint16_t *)A;
+    a.Bt = (const uint16_t *)Bt;
+    a.x = (const uint16_t *)x;
+    a.y = (uint16_t *)y;
+    a.tpart = (float *)workspace;
+    a.M = M; a.N = d->N; a.K = d->K; a.r = d->r; a.bits = d->bits;
+    hipStream_t s = (hipStream_t)stream;
+
+    hipError_t e = hipSuccess;
+    if (M <= kDecodeMaxM) {
+        if (d->r > 0) e = launch_down_proj_decode(a, s);
+        if (e == hipSuccess) e = launch_gemv_decode(a, s);
+    } else {
+        if (d->r > 0) e = launch_down_proj_prefill(a, s);
+        if (e == hipSuccess) e = launch_gemm_prefill(a, s);
+    }
+    return hip_status(e);
+}
+
+extern "C" fbq_status fbq_reconstruct(const fbq_desc *d, const void *qweight, const void *scales, const void *zeros,
+                                      const void *A, const void *Bt, float *W_hat, fbq_stream stream)
+{
+    fbq_status st = fbq_check_desc(d);
+    if (st != FBQ_OK) return st;
+    if (!qweight || !scales || !zeros || !W_hat) return FBQ_ERR_NULL;
+    if (d->r > 0 && (!A || !Bt)) return FBQ_ERR_NULL;
+    if (misaligned(qweight) || misaligned(scales) || misaligned(zeros) || misaligned(W_hat)) return FBQ_ERR_ALIGN;
+    if (d->r > 0 && (misaligned(A) || misaligned(Bt))) return FBQ_ERR_ALIGN;
+    return hip_status(launch_reconstruct(*d, (const uint32_t *)qweight, (const uint16_t *)scales, (const uint16_t *)zeros,
+                                         (const uint16_t *)A, (const uint16_t *)Bt, W_hat, (hipStream_t)stream));
+}
+
+extern "C" fbq_status fbq_unpack_codes(const fbq_desc *d, const void *qweight, uint8_t *codes_out, fbq_stream stream)
+{
+    fbq_status st = fbq_check_desc(d);
+    if (st != FBQ_OK) return st;
+    if (!qweight || !codes_out) return FBQ_ERR_NULL;
+    if (misaligned(qweight) || misaligned(codes_out)) return FBQ_ERR_ALIGN;
+    return hip_status(launch_unpack(*d, (const uint32_t *)qweight, codes_out, (hipStream_t)stream));
+}
+
+extern "C" fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, const void *A, const void *Bt,
+                                            void *qweight_out, void *scales_out, void *zeros_out, fbq_stream stream)
+{
+    fbq_status st = fbq_check_desc(d);
+    if (st != FBQ_OK) return st;
+    if (!W || !qweight_out || !scales_out || !zeros_out) return FBQ_ERR_NULL;
+    if (d->r > 0 && (!A || !Bt)) return FBQ_ERR_NULL;
+    if (misaligned(W) || misaligned(qweight_out) || misaligned(scales_out) || misaligned(zeros_out)) return FBQ_ERR_ALIGN;
+    if (d->r > 0 && (misaligned(A) || misaligned(Bt))) return FBQ_ERR_ALIGN;
+    return hip_status(launch_quantize(*d, (const uint16_t *)W, (const uint16_t *)A, (const uint16_t *)Bt,
+                                      (uint32_t *)qweight_out, (uint16_t *)scales_out, (uint16_t *)zeros_out,
+                                      (hipStream_t)stream));
+}

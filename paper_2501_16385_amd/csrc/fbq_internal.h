@@ -1,0 +1,52 @@
+// Internal declarations shared by the library's own translation units (not part of the ABI).
+#ifndef FBQ_INTERNAL_H
+#define FBQ_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fbq.h"
+
+namespace fbq {
+
+constexpr int kGroup = 128;          // codes per (scale, zero) pair
+constexpr int kLaneCodes = 32;       // codes one lane takes from one wave-wide load
+constexpr int kChunk = 64 * kLaneCodes;   // codes one wave-wide load covers (2048)
+constexpr int kSplitT = 8;           // split-K partial sums of the decode down-projection
+constexpr int kMaxRank = 256;
+constexpr int kMaxK = 16 * kChunk;      // 32768: the decode kernel keeps a wave's activations in registers
+constexpr int kDecodeMaxM = 16;
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Words per packed row.
+inline size_t row_words(int K, int bits) { return (size_t)K * bits / 32; }
+
+struct LinearArgs {
+    const uint32_t *qw;
+    const uint16_t *scales;
+    const uint16_t *zeros;
+    const uint16_t *A;
+    const uint16_t *Bt;
+    const uint16_t *x;
+    uint16_t *y;
+    float *tpart;     // decode: [kSplitT][M][r] fp32 partial sums of x.A; prefill: [M][r] fp16 pairs (see prefill)
+    int M, N, K, r, bits;
+};
+
+// Launchers (validated arguments only).  Each returns the hipError_t of its launches.
+hipError_t launch_down_proj_decode(const LinearArgs &a, hipStream_t stream);
+hipError_t launch_gemv_decode(const LinearArgs &a, hipStream_t stream);
+hipError_t launch_down_proj_prefill(const LinearArgs &a, hipStream_t stream);
+hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream);
+hipError_t launch_unpack(const fbq_desc &d, const uint32_t *qw, uint8_t *codes, hipStream_t stream);
+hipError_t launch_reconstruct(const fbq_desc &d, const uint32_t *qw, const uint16_t *scales, const uint16_t *zeros,
+                              const uint16_t *A, const uint16_t *Bt, float *W_hat, hipStream_t stream);
+hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t *A, const uint16_t *Bt, uint32_t *qw,
+                           uint16_t *scales, uint16_t *zeros, hipStream_t stream);
+
+size_t prefill_workspace_bytes(int M, int r);
+
+}  // namespace fbq
+
+#endif

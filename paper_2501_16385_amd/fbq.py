@@ -1,0 +1,228 @@
+"""ctypes binding of the C ABI in include/fbq.h: argument marshalling only.
+
+Device buffers are torch tensors (torch is used for device memory and streams, nothing else);
+every step of the path runs in the library's own kernels.  There is no CPU fallback: if
+libfbq.so is missing or the GPU is absent the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfbq.so")
+_lib: Optional[ctypes.CDLL] = None
+
+EXPORTED_SYMBOLS = ["fbq_status_string", "fbq_check_desc", "fbq_packed_bytes", "fbq_workspace_bytes", "fbq_pack",
+                    "fbq_linear", "fbq_reconstruct", "fbq_unpack_codes", "fbq_quantize_feedback"]
+
+
+class FbqError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {status_string(code)} (fbq_status {code})")
+
+
+class _CDesc(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int32), ("K", ctypes.c_int32), ("r", ctypes.c_int32), ("bits", ctypes.c_int32),
+                ("group", ctypes.c_int32)]
+
+
+@dataclass(frozen=True)
+class Desc:
+    N: int
+    K: int
+    r: int
+    bits: int
+    group: int = 128
+
+    def c(self) -> _CDesc:
+        return _CDesc(self.N, self.K, self.r, self.bits, self.group)
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Loads libfbq.so (built by paper_2501_16385_amd/build.py); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(f"{_LIB_PATH} not built: run `python -m paper_2501_16385_amd.build`")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        dp = ctypes.POINTER(_CDesc)
+        lib.fbq_status_string.restype = ctypes.c_char_p
+        lib.fbq_status_string.argtypes = [i32]
+        lib.fbq_check_desc.restype = i32
+        lib.fbq_check_desc.argtypes = [dp]
+        lib.fbq_packed_bytes.restype = sz
+        lib.fbq_packed_bytes.argtypes = [dp]
+        lib.fbq_workspace_bytes.restype = sz
+        lib.fbq_workspace_bytes.argtypes = [dp, i32]
+        lib.fbq_pack.restype = i32
+        lib.fbq_pack.argtypes = [dp] + [vp] * 10
+        lib.fbq_linear.restype = i32
+        lib.fbq_linear.argtypes = [dp, i32] + [vp] * 8 + [sz, vp]
+        lib.fbq_reconstruct.restype = i32
+        lib.fbq_reconstruct.argtypes = [dp] + [vp] * 7
+        lib.fbq_unpack_codes.restype = i32
+        lib.fbq_unpack_codes.argtypes = [dp] + [vp] * 3
+        lib.fbq_quantize_feedback.restype = i32
+        lib.fbq_quantize_feedback.argtypes = [dp] + [vp] * 7
+        _lib = lib
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return load().fbq_status_string(int(code)).decode()
+
+
+def _check(code: int, what: str) -> None:
+    if code != 0:
+        raise FbqError(code, what)
+
+
+def packed_bytes(d: Desc) -> int:
+    return int(load().fbq_packed_bytes(ctypes.byref(d.c())))
+
+
+def workspace_bytes(d: Desc, M: int) -> int:
+    return int(load().fbq_workspace_bytes(ctypes.byref(d.c()), int(M)))
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _dev_ptr(t) -> Optional[ctypes.c_void_p]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("expected a device tensor")
+    if not t.is_contiguous():
+        raise ValueError("expected a contiguous tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None) -> ctypes.c_void_p:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+@dataclass
+class PackedLayer:
+    """Host-side arrays in the device layout (outputs of fbq_pack)."""
+    desc: Desc
+    qweight: np.ndarray   # uint32 [N, K*bits/32]
+    scales: np.ndarray    # float16 [N, G]
+    zeros: np.ndarray     # float16 [N, G]
+    A: Optional[np.ndarray]    # float16 [K, r]
+    Bt: Optional[np.ndarray]   # float16 [N, r]
+
+
+def pack(d: Desc, codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray, A: Optional[np.ndarray],
+         B: Optional[np.ndarray]) -> PackedLayer:
+    """fbq_pack: canonical host tensors -> device-layout host tensors."""
+    G = d.K // d.group
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.float16)
+    zeros = np.ascontiguousarray(zeros, dtype=np.float16)
+    if codes.shape != (d.N, d.K) or scales.shape != (d.N, G) or zeros.shape != (d.N, G):
+        raise ValueError("shape mismatch")
+    nbytes = packed_bytes(d)
+    if nbytes == 0:
+        _check(int(load().fbq_check_desc(ctypes.byref(d.c()))), "fbq_pack")
+    qw = np.empty((d.N, nbytes // 4 // d.N), np.uint32)
+    s_out, z_out = np.empty_like(scales), np.empty_like(zeros)
+    if d.r:
+        A = np.ascontiguousarray(A, dtype=np.float16)
+        B = np.ascontiguousarray(B, dtype=np.float16)
+        if A.shape != (d.K, d.r) or B.shape != (d.r, d.N):
+            raise ValueError("shape mismatch")
+        A_out, Bt_out = np.empty((d.K, d.r), np.float16), np.empty((d.N, d.r), np.float16)
+    else:
+        A = B = A_out = Bt_out = None
+    rc = load().fbq_pack(ctypes.byref(d.c()), _np_ptr(codes), _np_ptr(scales), _np_ptr(zeros), _np_ptr(A), _np_ptr(B),
+                         _np_ptr(qw), _np_ptr(s_out), _np_ptr(z_out), _np_ptr(A_out), _np_ptr(Bt_out))
+    _check(rc, "fbq_pack")
+    return PackedLayer(d, qw, s_out, z_out, A_out, Bt_out)
+
+
+@dataclass
+class DeviceLayer:
+    """Device tensors of one layer plus its scratch."""
+    desc: Desc
+    qweight: "object"
+    scales: "object"
+    zeros: "object"
+    A: "object"
+    Bt: "object"
+
+
+def upload_layer(p: PackedLayer, device="cuda") -> DeviceLayer:
+    import torch
+    t = lambda a: None if a is None else torch.from_numpy(a.view(np.int16) if a.dtype == np.float16 else a.view(np.int32)).to(device)
+    return DeviceLayer(p.desc, t(p.qweight), t(p.scales), t(p.zeros), t(p.A), t(p.Bt))
+
+
+def linear(layer: DeviceLayer, x, y=None, workspace=None, stream=None):
+    """fbq_linear: x [M, K] fp16 device tensor -> y [M, N] fp16 device tensor."""
+    import torch
+    d = layer.desc
+    M = int(x.shape[0])
+    if y is None:
+        y = torch.empty((M, d.N), dtype=torch.float16, device=x.device)
+    need = workspace_bytes(d, M)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().fbq_linear(ctypes.byref(d.c()), M, _dev_ptr(x), _dev_ptr(layer.qweight), _dev_ptr(layer.scales),
+                           _dev_ptr(layer.zeros), _dev_ptr(layer.A), _dev_ptr(layer.Bt), _dev_ptr(y), _dev_ptr(workspace),
+                           wbytes, _stream(stream))
+    _check(rc, "fbq_linear")
+    return y
+
+
+def reconstruct(layer: DeviceLayer, stream=None):
+    """fbq_reconstruct: W_F [N, K] fp32 device tensor."""
+    import torch
+    d = layer.desc
+    out = torch.empty((d.N, d.K), dtype=torch.float32, device=layer.qweight.device)
+    rc = load().fbq_reconstruct(ctypes.byref(d.c()), _dev_ptr(layer.qweight), _dev_ptr(layer.scales), _dev_ptr(layer.zeros),
+                                _dev_ptr(layer.A), _dev_ptr(layer.Bt), _dev_ptr(out), _stream(stream))
+    _check(rc, "fbq_reconstruct")
+    return out
+
+
+def unpack_codes(layer: DeviceLayer, stream=None):
+    """fbq_unpack_codes: integer codes [N, K] uint8 device tensor."""
+    import torch
+    d = layer.desc
+    out = torch.empty((d.N, d.K), dtype=torch.uint8, device=layer.qweight.device)
+    rc = load().fbq_unpack_codes(ctypes.byref(d.c()), _dev_ptr(layer.qweight), _dev_ptr(out), _stream(stream))
+    _check(rc, "fbq_unpack_codes")
+    return out
+
+
+def quantize_feedback(d: Desc, W, A=None, Bt=None, stream=None) -> DeviceLayer:
+    """fbq_quantize_feedback: W [N, K] fp16, A [K, r], Bt [N, r] device tensors -> packed device layer."""
+    import torch
+    dev = W.device
+    nbytes = packed_bytes(d)
+    if nbytes == 0:
+        _check(int(load().fbq_check_desc(ctypes.byref(d.c()))), "fbq_quantize_feedback")
+    qw = torch.empty((d.N, nbytes // 4 // d.N), dtype=torch.int32, device=dev)
+    G = d.K // d.group
+    s = torch.empty((d.N, G), dtype=torch.int16, device=dev)
+    z = torch.empty((d.N, G), dtype=torch.int16, device=dev)
+    rc = load().fbq_quantize_feedback(ctypes.byref(d.c()), _dev_ptr(W), _dev_ptr(A), _dev_ptr(Bt), _dev_ptr(qw), _dev_ptr(s),
+                                      _dev_ptr(z), _stream(stream))
+    _check(rc, "fbq_quantize_feedback")
+    return DeviceLayer(d, qw, s, z, A, Bt)

@@ -1,0 +1,158 @@
+"""GPU-vs-oracle parity through the C ABI (needs an MI355X: run with -m gpu).
+
+Bars: integer codes bit-exact; y within 1e-3 relative L2 of the fp64 oracle (fp16 in/out, fp32
+accumulation); W_F within 1e-6 relative; the GPU feedback quantizer reproduces the oracle's codes
+(at most 1e-4 of the elements may differ, by exactly one step, which only near-ties can cause).
+"""
+import numpy as np
+import pytest
+
+import fbq_synth
+from helpers import gpu_y, make_oracle_layer, oracle_y, rel_l2, to_device_layer
+from oracle import fbq_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+Y_TOL = 1e-3
+
+
+def spec_of(N, K, r, bits, **kw):
+    return fbq_synth.LayerSpec(f"t{N}x{K}r{r}b{bits}", N, K, r, bits, **kw)
+
+
+# ------------------------------------------------------------------ integer codes
+
+@pytest.mark.parametrize("bits", [3, 4])
+@pytest.mark.parametrize("N,K", [(37, 1408), (256, 4096)])
+def test_unpacked_codes_are_bit_exact(bits, N, K):
+    import torch
+    import paper_2501_16385_amd as fbq
+    L = make_oracle_layer(spec_of(N, K, 0, bits), config=11)
+    dev = to_device_layer(L)
+    got = fbq.unpack_codes(dev)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), L.codes)
+    assert np.array_equal(got.cpu().numpy(), orc.unpack(L.words, K, bits))
+
+
+# ------------------------------------------------------------------ decode GEMV
+
+DECODE_CASES = [
+    # N, K, r, M          several row tiles, ragged N, partial K chunks, every K-split variant
+    (4096, 4096, 32, 1),
+    (300, 1408, 24, 1),
+    (300, 1408, 24, 5),
+    (515, 2048, 64, 2),
+    (1024, 5120, 128, 1),
+    (768, 8192, 64, 3),
+    (512, 11008, 64, 1),
+    (384, 13824, 128, 4),
+    (256, 28672, 128, 1),
+    (130, 28672, 256, 16),
+    (1000, 4096, 0, 1),
+    (64, 128, 8, 16),
+    (1, 128, 0, 1),
+]
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K,r,M", DECODE_CASES)
+def test_decode_linear_matches_oracle(bits, N, K, r, M):
+    spec = spec_of(N, K, r, bits)
+    L = make_oracle_layer(spec, config=12)
+    x = fbq_synth.make_x(spec, M, 12, 0)
+    want = oracle_y(L, x)
+    dev = to_device_layer(L)
+    got = gpu_y(dev, x)
+    assert got.shape == (M, N) and np.all(np.isfinite(got))
+    err = rel_l2(got, want)
+    assert err <= Y_TOL, f"rel L2 {err:.3e}"
+    # per-token bound too, so that one bad row of a batch cannot hide
+    for m in range(M):
+        assert rel_l2(got[m], want[m]) <= Y_TOL
+    # same launch twice: bit-identical (no races, no uninitialised scratch)
+    assert np.array_equal(gpu_y(dev, x), got)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_decode_exact_on_integer_inputs(bits):
+    """s = 1, z = 0, no branch, x in {-1, 0, 1}: y is an integer below 2048, exact in every precision."""
+    import paper_2501_16385_amd as fbq
+    rng = np.random.Generator(np.random.Philox(70 + bits))
+    N, K = 200, 128
+    codes = rng.integers(0, 2 ** bits, (N, K), dtype=np.uint8)
+    s = np.ones((N, 1), np.float16)
+    z = np.zeros((N, 1), np.float16)
+    x = rng.integers(-1, 2, (3, K)).astype(np.float16)
+    dev = fbq.upload_layer(fbq.pack(fbq.Desc(N, K, 0, bits), codes, s, z, None, None))
+    got = gpu_y(dev, x)
+    want = orc.linear(x, orc.pack(codes, bits), s, z, None, None, bits, 128)
+    assert np.array_equal(got.astype(np.float64), want)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_branch_free_twin_equals_zero_up_projection(bits):
+    """Alg. 1 starts from B = 0: the fused kernel must then agree with its r = 0 twin bit for bit."""
+    import paper_2501_16385_amd as fbq
+    spec = spec_of(512, 4096, 64, bits)
+    L = make_oracle_layer(spec, config=13)
+    x = fbq_synth.make_x(spec, 1, 13, 0)
+    B0 = np.zeros_like(L.B)
+    with_zero_B = fbq.upload_layer(fbq.pack(fbq.Desc(512, 4096, 64, bits), L.codes, L.scales, L.zeros, L.A, B0))
+    twin = fbq.upload_layer(fbq.pack(fbq.Desc(512, 4096, 0, bits), L.codes, L.scales, L.zeros, None, None))
+    assert np.array_equal(gpu_y(with_zero_B, x), gpu_y(twin, x))
+
+
+# ------------------------------------------------------------------ full benchmark shapes
+
+@pytest.mark.parametrize("config", [0, 1])
+def test_benchmark_layers_full_size(config):
+    """The exact shapes bench.py times (configs 0 and 1), every output compared."""
+    specs, Ms = fbq_synth.config_layers(config)
+    seen = set()
+    for li, spec in enumerate(specs):
+        if (spec.N, spec.K) in seen:
+            continue
+        seen.add((spec.N, spec.K))
+        L = make_oracle_layer(spec, config=config, layer_index=li)
+        x = fbq_synth.make_x(spec, Ms[0], config, li)
+        err = rel_l2(gpu_y(to_device_layer(L), x), oracle_y(L, x))
+        assert err <= Y_TOL, f"{spec.name}: rel L2 {err:.3e}"
+
+
+# ------------------------------------------------------------------ reconstruct / quantize
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_reconstruct_matches_oracle(bits):
+    import torch
+    import paper_2501_16385_amd as fbq
+    spec = spec_of(96, 1024, 32, bits)
+    L = make_oracle_layer(spec, config=14)
+    got = fbq.reconstruct(to_device_layer(L))
+    torch.cuda.synchronize()
+    want = orc.reconstruct(L.words, L.scales, L.zeros, L.A, L.B, spec.K, bits, 128)
+    assert rel_l2(got.cpu().numpy(), want) <= 1e-6
+    # Sec. 4.1 bound on the GPU's own reconstruction
+    half = np.repeat(L.scales.astype(np.float64), 128, axis=1) / 2
+    assert np.all(np.abs(L.W.astype(np.float64) - got.cpu().numpy()) <= half * (1 + 1e-3))
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K,r", [(128, 2048, 32), (50, 1408, 0)])
+def test_gpu_feedback_quantizer_matches_oracle(bits, N, K, r):
+    import torch
+    import paper_2501_16385_amd as fbq
+    spec = spec_of(N, K, r, bits)
+    L = make_oracle_layer(spec, config=15)
+    t16 = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+    Wd = t16(L.W)
+    Ad = t16(L.A) if r else None
+    Btd = t16(L.B.T) if r else None
+    dev = fbq.quantize_feedback(fbq.Desc(N, K, r, bits), Wd, Ad, Btd)
+    codes = fbq.unpack_codes(dev).cpu().numpy()
+    torch.cuda.synchronize()
+    assert np.array_equal(dev.scales.cpu().numpy().view(np.float16), L.scales)
+    assert np.array_equal(dev.zeros.cpu().numpy().view(np.float16), L.zeros)
+    diff = codes.astype(np.int16) - L.codes.astype(np.int16)
+    assert np.mean(diff != 0) <= 1e-4 and np.all(np.abs(diff) <= 1)
+    assert np.array_equal(dev.qweight.cpu().numpy().view(np.uint32), L.words) or np.mean(diff != 0) > 0

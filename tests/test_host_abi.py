@@ -1,0 +1,83 @@
+"""CPU-side checks of the C ABI: the library loads, exports what include/fbq.h declares, rejects bad
+arguments before any launch, and its host-side fbq_pack writes the documented device layout."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2501_16385_amd as fbq
+from oracle import fbq_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "fbq.h")).read()
+    declared = sorted(set(re.findall(r"\b(fbq_[a-z_]+)\s*\(", header)))
+    assert declared == sorted(fbq.EXPORTED_SYMBOLS)
+    lib = fbq.load()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_sizes_and_status_strings():
+    d = fbq.Desc(4096, 4096, 64, 4)
+    assert fbq.packed_bytes(d) == 4096 * 4096 // 2
+    assert fbq.packed_bytes(fbq.Desc(4096, 4096, 64, 3)) == 4096 * 4096 * 3 // 8
+    assert fbq.workspace_bytes(d, 1) > 0 and fbq.workspace_bytes(fbq.Desc(4096, 4096, 0, 4), 1) == 0
+    assert fbq.workspace_bytes(d, 16) >= 16 * 64 * 4
+    assert fbq.status_string(0) == "ok"
+    assert all(fbq.status_string(c) for c in range(8))
+
+
+@pytest.mark.parametrize("desc,code", [
+    (fbq.Desc(16, 256, 8, 5), 3), (fbq.Desc(16, 256, 8, 4, 64), 3), (fbq.Desc(16, 200, 8, 4), 2),
+    (fbq.Desc(0, 256, 8, 4), 2), (fbq.Desc(16, 256, 7, 4), 2), (fbq.Desc(16, 256, 264, 4), 3),
+    (fbq.Desc(16, 65536, 8, 4), 3), (fbq.Desc(16, 256, -8, 4), 2)])
+def test_bad_descriptors_are_rejected(desc, code):
+    lib = fbq.load()
+    assert lib.fbq_check_desc(ctypes.byref(desc.c())) == code
+    assert fbq.packed_bytes(desc) == 0 and fbq.workspace_bytes(desc, 1) == 0
+    # fbq_linear refuses before touching the GPU (bogus but aligned pointers are never dereferenced)
+    p = ctypes.c_void_p(0x1000)
+    assert lib.fbq_linear(ctypes.byref(desc.c()), 1, p, p, p, p, p, p, p, p, 1 << 20, None) == code
+
+
+def test_linear_argument_errors_without_launch():
+    lib = fbq.load()
+    d = fbq.Desc(16, 256, 8, 4)
+    ok, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004)
+    call = lambda M, x, ws, wb: lib.fbq_linear(ctypes.byref(d.c()), M, x, ok, ok, ok, ok, ok, ok, ws, wb, None)
+    assert call(0, ok, ok, 1 << 20) == 2            # M < 1
+    assert call(1, None, ok, 1 << 20) == 1          # null x
+    assert call(1, odd, ok, 1 << 20) == 4           # misaligned x
+    assert call(1, ok, None, 1 << 20) == 1          # workspace needed but null
+    assert call(1, ok, ok, 8) == 5                  # workspace too small
+    assert lib.fbq_linear(None, 1, ok, ok, ok, ok, ok, ok, ok, ok, 1 << 20, None) == 1
+    assert lib.fbq_unpack_codes(ctypes.byref(d.c()), None, ok, None) == 1
+    assert lib.fbq_reconstruct(ctypes.byref(d.c()), ok, ok, ok, None, ok, ok, None) == 1
+    assert lib.fbq_quantize_feedback(ctypes.byref(d.c()), ok, ok, ok, odd, ok, ok, None) == 4
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_host_pack_writes_the_documented_layout(bits):
+    rng = np.random.Generator(np.random.Philox(900 + bits))
+    N, K, r = 7, 384, 16
+    d = fbq.Desc(N, K, r, bits)
+    codes = rng.integers(0, 2 ** bits, (N, K), dtype=np.uint8)
+    s = rng.random((N, K // 128)).astype(np.float16)
+    z = (rng.random((N, K // 128)) * 8).astype(np.float16)
+    A = rng.standard_normal((K, r)).astype(np.float16)
+    B = rng.standard_normal((r, N)).astype(np.float16)
+    p = fbq.pack(d, codes, s, z, A, B)
+    assert np.array_equal(p.qweight, orc.pack(codes, bits))           # same words as the oracle's packer
+    assert np.array_equal(orc.unpack(p.qweight, K, bits), codes)      # and the oracle reads them back
+    assert np.array_equal(p.scales, s) and np.array_equal(p.zeros, z)
+    assert np.array_equal(p.A, A) and np.array_equal(p.Bt, B.T)
+    bad = codes.copy()
+    bad[3, 5] = 2 ** bits
+    with pytest.raises(fbq.FbqError) as e:
+        fbq.pack(d, bad, s, z, A, B)
+    assert e.value.code == 2
