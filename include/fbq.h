@@ -26,10 +26,10 @@
  *                   (bit c of the code in word c), code 31 over bit 31.  No code straddles a
  *                   16-bit half, so a mask yields two codes at once as an fp16 pair.
  *   scales   [N, G] fp16      zeros  [N, G] fp16 (real-valued zero point, not an integer)
- *   A        [K, r] fp16      Bt     [N, r] fp16 (B transposed: one output's r taps contiguous)
+ *   At       [r, K] fp16 (A transposed: K contiguous)   Bt  [N, r] fp16 (B transposed: one output's r taps contiguous)
  *
  * Ownership and errors
- *   The library owns no memory and keeps no mutable state.  Pointers marked "host" are read or
+ *   The library owns no memory and keeps no state.  Pointers marked "host" are read or
  *   written by the CPU during the call; pointers marked "device" must be device memory valid on
  *   the current HIP device, 16-byte aligned, owned by the caller, and are accessed asynchronously
  *   on `stream` (a hipStream_t passed as void*; NULL is the default stream).  Device entry points
@@ -75,8 +75,9 @@ fbq_status fbq_check_desc(const fbq_desc *d);
 /* Bytes of the packed code buffer, N * K * bits / 8.  0 for an invalid descriptor. */
 size_t fbq_packed_bytes(const fbq_desc *d);
 
-/* Bytes of device scratch fbq_linear needs for M tokens: the split-K partial sums of the
- * down-projection t = x.A in fp32.  0 when r == 0; 0 for an invalid descriptor or M < 1. */
+/* Bytes of device scratch fbq_linear needs for M tokens: the down-projection t = x.A on its way
+ * from the blocks that compute it to the blocks that use it.  0 when r == 0; 0 for an invalid
+ * descriptor or M < 1. */
 size_t fbq_workspace_bytes(const fbq_desc *d, int M);
 
 /*
@@ -87,36 +88,38 @@ size_t fbq_workspace_bytes(const fbq_desc *d, int M);
  *   codes      host [N, K] uint8, each in 0..qmax        qweight_out host, fbq_packed_bytes()
  *   scales     host [N, G] fp16                           scales_out  host [N, G] fp16
  *   zeros      host [N, G] fp16                           zeros_out   host [N, G] fp16
- *   A          host [K, r] fp16 (NULL if r == 0)          A_out       host [K, r] fp16
+ *   A          host [K, r] fp16 (NULL if r == 0)          At_out      host [r, K] fp16
  *   B          host [r, N] fp16 (NULL if r == 0)          Bt_out      host [N, r] fp16
  * Returns FBQ_ERR_SHAPE if a code exceeds qmax (outputs are then unspecified).
  */
 fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *scales, const uint16_t *zeros,
                     const uint16_t *A, const uint16_t *B, uint32_t *qweight_out, uint16_t *scales_out,
-                    uint16_t *zeros_out, uint16_t *A_out, uint16_t *Bt_out);
+                    uint16_t *zeros_out, uint16_t *At_out, uint16_t *Bt_out);
 
 /*
  * fbq_linear - the hot path (Sec. 4.3).  y[m,n] = sum_k x[m,k] * s[n,k/g] * (q[n,k] - z[n,k/g])
- *                                               + sum_j (sum_k x[m,k] * A[k,j]) * Bt[n,j]
- * in fp32 accumulation, rounded once to fp16.  Two launches when r > 0 (down-projection into
- * the workspace, then the fused kernel), one when r == 0.  M <= 16 runs the decode GEMV
- * (packed words streamed once, unpacked in registers); M > 16 runs the fp16 MFMA GEMM.
- *   x         device [M, K] fp16             qweight, scales, zeros, A, Bt: device, layout above
+ *                                               + sum_j (sum_k x[m,k] * At[j,k]) * Bt[n,j]
+ * in fp32 accumulation, rounded once to fp16.  M <= 16 runs the decode GEMV in ONE launch (packed
+ * words streamed once, unpacked in registers; the down-projection runs in a few producer blocks
+ * of the same launch); M > 16 runs the fp16 MFMA GEMM after a separate down-projection.
+ *   x         device [M, K] fp16             qweight, scales, zeros, At, Bt: device, layout above
  *   y         device [M, N] fp16, overwritten
- *   workspace device, >= fbq_workspace_bytes(d, M) bytes (may be NULL when that is 0); its
- *             contents are scratch; concurrent calls must not share it
+ *   workspace device, >= fbq_workspace_bytes(d, M) bytes (may be NULL when that is 0).  Zero-fill it
+ *             once after allocating it; after that it needs no care between calls, on any stream
+ *             and under graph replay: every launch marks what it writes with its own identity.
+ *             Calls that may run concurrently must not share a workspace.
  * Errors: FBQ_ERR_NULL, _SHAPE, _UNSUPPORTED, _ALIGN, _WORKSPACE before any launch; FBQ_ERR_HIP.
  */
 fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
-                      const void *zeros, const void *A, const void *Bt, void *y, void *workspace,
+                      const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
                       size_t workspace_bytes, fbq_stream stream);
 
 /*
- * fbq_reconstruct - validation.  W_hat[n,k] = s*(q - z) + sum_j A[k,j]*Bt[n,j], the paper's
+ * fbq_reconstruct - validation.  W_hat[n,k] = s*(q - z) + sum_j At[j,k]*Bt[n,j], the paper's
  * W_F = Q(W - Sigma) + Sigma (Sec. 4.1), as fp32.   W_hat device [N, K] fp32, overwritten.
  */
 fbq_status fbq_reconstruct(const fbq_desc *d, const void *qweight, const void *scales, const void *zeros,
-                           const void *A, const void *Bt, float *W_hat, fbq_stream stream);
+                           const void *At, const void *Bt, float *W_hat, fbq_stream stream);
 
 /* fbq_unpack_codes - validation.  codes_out device [N, K] uint8 = the integer codes q. */
 fbq_status fbq_unpack_codes(const fbq_desc *d, const void *qweight, uint8_t *codes_out, fbq_stream stream);
@@ -128,10 +131,10 @@ fbq_status fbq_unpack_codes(const fbq_desc *d, const void *qweight, uint8_t *cod
  * R = W - Sigma; s = fp16((mx - mn)/qmax) (1 if the group is constant, never below the smallest
  * normal fp16); z = fp16(-mn/s); s is stepped to the next fp16 until both ends of the range lie
  * within half a step of [0, qmax]; q = clamp(round_half_even(R/s + z), 0, qmax).
- *   W device [N, K] fp16; A device [K, r]; Bt device [N, r] (both NULL if r == 0)
+ *   W device [N, K] fp16; At device [r, K]; Bt device [N, r] (both NULL if r == 0)
  *   qweight_out device fbq_packed_bytes(); scales_out, zeros_out device [N, G] fp16
  */
-fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, const void *A, const void *Bt,
+fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, const void *At, const void *Bt,
                                  void *qweight_out, void *scales_out, void *zeros_out, fbq_stream stream);
 
 #ifdef __cplusplus

@@ -41,7 +41,7 @@ extern "C" size_t fbq_packed_bytes(const fbq_desc *d)
 extern "C" size_t fbq_workspace_bytes(const fbq_desc *d, int M)
 {
     if (fbq_check_desc(d) != FBQ_OK || M < 1 || d->r == 0) return 0;
-    if (M <= kDecodeMaxM) return (size_t)kSplitT * M * d->r * sizeof(float);
+    if (M <= kDecodeMaxM) return decode_workspace_bytes(M, d->r);
     return prefill_workspace_bytes(M, d->r);
 }
 
@@ -68,12 +68,12 @@ static inline void code_bit_slot(int bits, int k, int c, size_t *word, int *bit)
 
 extern "C" fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *scales, const uint16_t *zeros,
                                const uint16_t *A, const uint16_t *B, uint32_t *qweight_out, uint16_t *scales_out,
-                               uint16_t *zeros_out, uint16_t *A_out, uint16_t *Bt_out)
+                               uint16_t *zeros_out, uint16_t *At_out, uint16_t *Bt_out)
 {
     fbq_status st = fbq_check_desc(d);
     if (st != FBQ_OK) return st;
     if (!codes || !scales || !zeros || !qweight_out || !scales_out || !zeros_out) return FBQ_ERR_NULL;
-    if (d->r > 0 && (!A || !B || !A_out || !Bt_out)) return FBQ_ERR_NULL;
+    if (d->r > 0 && (!A || !B || !At_out || !Bt_out)) return FBQ_ERR_NULL;
 
     const int N = d->N, K = d->K, r = d->r, bits = d->bits;
     const size_t rw = row_words(K, bits);
@@ -97,7 +97,8 @@ extern "C" fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const ui
     memcpy(scales_out, scales, ng * sizeof(uint16_t));
     memcpy(zeros_out, zeros, ng * sizeof(uint16_t));
     if (r > 0) {
-        memcpy(A_out, A, (size_t)K * r * sizeof(uint16_t));
+        for (int k = 0; k < K; ++k)
+            for (int j = 0; j < r; ++j) At_out[(size_t)j * K + k] = A[(size_t)k * r + j];
         for (int n = 0; n < N; ++n)
             for (int j = 0; j < r; ++j) Bt_out[(size_t)n * r + j] = B[(size_t)j * N + n];
     }
@@ -115,18 +116,18 @@ static fbq_status hip_status(hipError_t e)
 }
 
 extern "C" fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
-                                 const void *zeros, const void *A, const void *Bt, void *y, void *workspace,
+                                 const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
                                  size_t workspace_bytes, fbq_stream stream)
 {
     fbq_status st = fbq_check_desc(d);
     if (st != FBQ_OK) return st;
     if (M < 1) return FBQ_ERR_SHAPE;
     if (!x || !qweight || !scales || !zeros || !y) return FBQ_ERR_NULL;
-    if (d->r > 0 && (!A || !Bt)) return FBQ_ERR_NULL;
+    if (d->r > 0 && (!At || !Bt)) return FBQ_ERR_NULL;
     const size_t need = fbq_workspace_bytes(d, M);
     if (need > 0 && !workspace) return FBQ_ERR_NULL;
     if (misaligned(x) || misaligned(qweight) || misaligned(scales) || misaligned(zeros) || misaligned(y)) return FBQ_ERR_ALIGN;
-    if (d->r > 0 && (misaligned(A) || misaligned(Bt))) return FBQ_ERR_ALIGN;
+    if (d->r > 0 && (misaligned(At) || misaligned(Bt))) return FBQ_ERR_ALIGN;
     if (need > 0 && misaligned(workspace)) return FBQ_ERR_ALIGN;
     if (workspace_bytes < need) return FBQ_ERR_WORKSPACE;
 
@@ -134,18 +135,17 @@ extern "C" fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const 
     a.qw = (const uint32_t *)qweight;
     a.scales = (const uint16_t *)scales;
     a.zeros = (const uint16_t *)zeros;
-    a.A = (const uint16_t *)A;
+    a.At = (const uint16_t *)At;
     a.Bt = (const uint16_t *)Bt;
     a.x = (const uint16_t *)x;
     a.y = (uint16_t *)y;
-    a.tpart = (float *)workspace;
+    a.workspace = workspace;
     a.M = M; a.N = d->N; a.K = d->K; a.r = d->r; a.bits = d->bits;
     hipStream_t s = (hipStream_t)stream;
 
     hipError_t e = hipSuccess;
     if (M <= kDecodeMaxM) {
-        if (d->r > 0) e = launch_down_proj_decode(a, s);
-        if (e == hipSuccess) e = launch_gemv_decode(a, s);
+        e = launch_gemv_decode(a, s);
     } else {
         if (d->r > 0) e = launch_down_proj_prefill(a, s);
         if (e == hipSuccess) e = launch_gemm_prefill(a, s);
@@ -154,16 +154,16 @@ extern "C" fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const 
 }
 
 extern "C" fbq_status fbq_reconstruct(const fbq_desc *d, const void *qweight, const void *scales, const void *zeros,
-                                      const void *A, const void *Bt, float *W_hat, fbq_stream stream)
+                                      const void *At, const void *Bt, float *W_hat, fbq_stream stream)
 {
     fbq_status st = fbq_check_desc(d);
     if (st != FBQ_OK) return st;
     if (!qweight || !scales || !zeros || !W_hat) return FBQ_ERR_NULL;
-    if (d->r > 0 && (!A || !Bt)) return FBQ_ERR_NULL;
+    if (d->r > 0 && (!At || !Bt)) return FBQ_ERR_NULL;
     if (misaligned(qweight) || misaligned(scales) || misaligned(zeros) || misaligned(W_hat)) return FBQ_ERR_ALIGN;
-    if (d->r > 0 && (misaligned(A) || misaligned(Bt))) return FBQ_ERR_ALIGN;
+    if (d->r > 0 && (misaligned(At) || misaligned(Bt))) return FBQ_ERR_ALIGN;
     return hip_status(launch_reconstruct(*d, (const uint32_t *)qweight, (const uint16_t *)scales, (const uint16_t *)zeros,
-                                         (const uint16_t *)A, (const uint16_t *)Bt, W_hat, (hipStream_t)stream));
+                                         (const uint16_t *)At, (const uint16_t *)Bt, W_hat, (hipStream_t)stream));
 }
 
 extern "C" fbq_status fbq_unpack_codes(const fbq_desc *d, const void *qweight, uint8_t *codes_out, fbq_stream stream)
@@ -175,16 +175,16 @@ extern "C" fbq_status fbq_unpack_codes(const fbq_desc *d, const void *qweight, u
     return hip_status(launch_unpack(*d, (const uint32_t *)qweight, codes_out, (hipStream_t)stream));
 }
 
-extern "C" fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, const void *A, const void *Bt,
+extern "C" fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, const void *At, const void *Bt,
                                             void *qweight_out, void *scales_out, void *zeros_out, fbq_stream stream)
 {
     fbq_status st = fbq_check_desc(d);
     if (st != FBQ_OK) return st;
     if (!W || !qweight_out || !scales_out || !zeros_out) return FBQ_ERR_NULL;
-    if (d->r > 0 && (!A || !Bt)) return FBQ_ERR_NULL;
+    if (d->r > 0 && (!At || !Bt)) return FBQ_ERR_NULL;
     if (misaligned(W) || misaligned(qweight_out) || misaligned(scales_out) || misaligned(zeros_out)) return FBQ_ERR_ALIGN;
-    if (d->r > 0 && (misaligned(A) || misaligned(Bt))) return FBQ_ERR_ALIGN;
-    return hip_status(launch_quantize(*d, (const uint16_t *)W, (const uint16_t *)A, (const uint16_t *)Bt,
+    if (d->r > 0 && (misaligned(At) || misaligned(Bt))) return FBQ_ERR_ALIGN;
+    return hip_status(launch_quantize(*d, (const uint16_t *)W, (const uint16_t *)At, (const uint16_t *)Bt,
                                       (uint32_t *)qweight_out, (uint16_t *)scales_out, (uint16_t *)zeros_out,
                                       (hipStream_t)stream));
 }

@@ -1,9 +1,21 @@
 // Decode path (M <= 16 tokens): the fused kernel of Sec. 4.3 as a memory-streaming GEMV for gfx950.
 //
-//   down-projection   t = x.A            small split-K kernel, fp32 partial sums in the workspace
+//   down-projection   t = x.A            a few producer blocks at the front of the SAME launch, each
+//                                        owning four columns of A over all of K (the paper keeps
+//                                        it a separate small kernel; on this GPU a launch costs as
+//                                        much as streaming a 4096^2 layer, so it rides along)
 //   fused kernel      y = x.Wq^T + t.B   one pass over the packed codes; de-quantization, main
 //                                        projection and up-projection share one fp32 accumulator
-//                                        and y is written once
+//                                        and y is written once.  t is needed only for the last few
+//                                        instructions of a wave, so waiting for it hides behind
+//                                        the weight stream.
+//
+// Hand-over of t inside one launch.  Every t[j] travels as one 8-byte word {value, tag}; the tag
+// identifies the launch (AQL dispatch id mixed with the queue address: distinct for every launch,
+// also for every replay of a captured graph, identical for all blocks of one launch).  Consumers
+// poll the words they need until the tags match: no flag, no counter, no atomic read-modify-write
+// (each costs microseconds across the eight L2s) and nothing to reset afterwards.  Words are
+// written and read with device-scope (sc1) accesses, which do not linger in a per-XCD L2.
 //
 // Work decomposition of the fused kernel.  A wave owns kRows consecutive output rows and a
 // contiguous K range; its 64 lanes lie along K.  One wave-wide load covers 2048 codes
@@ -33,12 +45,25 @@ __device__ __forceinline__ float dot2(uint32_t codes, half2_t xp, float acc)
     return __builtin_amdgcn_fdot2(as_h2(codes), xp, acc, false);
 }
 
-// Sum over the 64 lanes of a wave; every lane ends with the total.
+// v + (v moved across lanes by a DPP control); lanes the move does not reach add zero.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false);
+    return v + __builtin_bit_cast(float, moved);
+}
+
+// Sum over the 64 lanes of a wave, returned wave-uniform.  Butterfly inside each row of 16 lanes,
+// then row 0 -> 1, 2 -> 3 (row_bcast:15) and rows 0+1 -> 2, 3 (row_bcast:31); lane 63 has the total.
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v = dpp_add<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x141, 0xF>(v);   // row_half_mirror
+    v = dpp_add<0x140, 0xF>(v);   // row_mirror
+    v = dpp_add<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+    v = dpp_add<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 // ------------------------------------------------------------------ activations in registers
@@ -51,25 +76,19 @@ struct XFrag {
     half2_t p[16];
     float sum;
 
-    __device__ __forceinline__ void load(const uint16_t *xrow, int k0, bool valid)
+    // raw: 32 consecutive fp16 activations as loaded; valid == false gives an all-zero fragment
+    __device__ __forceinline__ void arrange(const uint4 (&raw)[4], bool valid)
     {
         half_t v[32];
-        if (valid) {
-            const uint4 *src = reinterpret_cast<const uint4 *>(xrow + k0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                uint4 q = src[i];
-                uint32_t w[4] = {q.x, q.y, q.z, q.w};
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    half2_t h = as_h2(w[j]);
-                    v[i * 8 + j * 2] = h.x;
-                    v[i * 8 + j * 2 + 1] = h.y;
-                }
+            for (int j = 0; j < 4; ++j) {
+                const half2_t h = as_h2(valid ? w[j] : 0u);
+                v[i * 8 + j * 2] = h.x;
+                v[i * 8 + j * 2 + 1] = h.y;
             }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 32; ++i) v[i] = (half_t)0.0f;
         }
         float s = 0.0f;
 #pragma unroll
@@ -132,7 +151,6 @@ struct CodeWords<4> {
         uint4 q = *reinterpret_cast<const uint4 *>(p);
         w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
     }
-    __device__ __forceinline__ void zero() { w[0] = w[1] = w[2] = w[3] = 0; }
     __device__ __forceinline__ float dot(const half2_t (&p)[16]) const { return dot_codes_int4(w, p); }
 };
 template <>
@@ -142,7 +160,6 @@ struct CodeWords<3> {
     {
         w[0] = p[0]; w[1] = p[1]; w[2] = p[2];
     }
-    __device__ __forceinline__ void zero() { w[0] = w[1] = w[2] = 0; }
     __device__ __forceinline__ float dot(const half2_t (&p)[16]) const { return dot_codes_int3(w, p); }
 };
 
@@ -152,14 +169,77 @@ struct GemvParams {
     const uint32_t *qw;
     const uint16_t *scales;
     const uint16_t *zeros;
-    const uint16_t *Bt;
-    const float *tpart;   // [kSplitT][M][r]
+    const uint16_t *At;   // [r][K]
+    const uint16_t *Bt;   // [N][r]
     const uint16_t *x;    // [M][K]
     uint16_t *y;          // [M][N]
+    uint64_t *ttag;       // workspace: [M][r] words {fp32 value (low half), launch tag (high half)}
     int M, N, K, r;
     int row_words;        // words per packed row
     int G;                // groups per row
+    int producers;        // producer blocks at the front of the grid (0 when r == 0)
 };
+
+constexpr int kProdCols = 4;          // columns of A per producer block
+constexpr int kSpinLimit = 1 << 15;   // polls (~0.3 us each) before a wave gives up and computes t itself
+constexpr int kCacheSc1 = 16 | (1 << 31);   // buffer-load policy: device scope (sc1), and volatile so that a poll is never hoisted or merged
+
+extern "C" __device__ unsigned long long fbq_llvm_dispatch_id(void) __asm("llvm.amdgcn.dispatch.id");
+
+// Identity of this launch, the same in every block: never zero, so a zero-filled workspace never matches.
+__device__ __forceinline__ uint32_t launch_tag()
+{
+    const uint64_t id = fbq_llvm_dispatch_id();
+    const uint64_t q = (uint64_t)__builtin_amdgcn_queue_ptr();
+    const uint32_t tag = (uint32_t)id + (uint32_t)(q >> 6) * 0x9E3779B1u;
+    return tag ? tag : 0x80000000u;
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t dev_buffer(const void *p, int bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
+}
+
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+
+// Producer block b of token m: t[j] for its kProdCols columns, lanes along K like the main kernel.
+__device__ void produce_t(const GemvParams &p, int m, int b, uint32_t tag, float *lds)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint16_t *xrow = p.x + (size_t)m * p.K;
+    const int j0 = b * kProdCols;
+    float acc[kProdCols];
+#pragma unroll
+    for (int c = 0; c < kProdCols; ++c) acc[c] = 0.0f;
+#pragma unroll 2
+    for (int k0 = tid * 8; k0 < p.K; k0 += 256 * 8) {
+        const uint4 xv = *reinterpret_cast<const uint4 *>(xrow + k0);
+        uint4 av[kProdCols];
+#pragma unroll
+        for (int c = 0; c < kProdCols; ++c) {
+            const int j = min(j0 + c, p.r - 1);         // r is a multiple of 8: never clamps, keeps loads unconditional
+            av[c] = *reinterpret_cast<const uint4 *>(p.At + (size_t)j * p.K + k0);
+        }
+#pragma unroll
+        for (int c = 0; c < kProdCols; ++c) {
+            acc[c] = dot2(av[c].x, as_h2(xv.x), acc[c]);
+            acc[c] = dot2(av[c].y, as_h2(xv.y), acc[c]);
+            acc[c] = dot2(av[c].z, as_h2(xv.z), acc[c]);
+            acc[c] = dot2(av[c].w, as_h2(xv.w), acc[c]);
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < kProdCols; ++c) {
+        const float s = wave_sum(acc[c]);
+        if (lane == 0) lds[wave * kProdCols + c] = s;
+    }
+    __syncthreads();
+    if (tid < kProdCols && j0 + tid < p.r) {
+        const float s = (lds[tid] + lds[kProdCols + tid]) + (lds[2 * kProdCols + tid] + lds[3 * kProdCols + tid]);
+        const uint64_t word = (uint64_t)__builtin_bit_cast(uint32_t, s) | ((uint64_t)tag << 32);
+        __hip_atomic_store(p.ttag + (size_t)m * p.r + j0 + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
 
 // BITS: 3 or 4.  CPW: chunks (of 2048 codes) per wave.  KS: waves of a block that split K.
 // ROWS: rows per wave.  RI: ceil(r/128), 0 = branch-free twin.
@@ -169,72 +249,146 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvParams p)
     constexpr int kWaves = 4;
     constexpr int kRowSets = kWaves / KS;               // row sets per block
     constexpr int kLaneWords = BITS == 4 ? 4 : 3;
-    __shared__ float red[KS > 1 ? kWaves * ROWS : 1];
+    constexpr int kRI = RI > 0 ? RI : 1;
+    __shared__ float red[kWaves * (ROWS > kProdCols ? ROWS : kProdCols)];   // K-split sums, or the producer's wave sums
+
+    const int m = blockIdx.y;
+    int bx = blockIdx.x;
+    uint32_t tag = 0;
+    if (RI > 0) {
+        tag = launch_tag();
+        if (bx < p.producers) {                         // block-uniform: producer blocks only produce
+            produce_t(p, m, bx, tag, red);
+            return;
+        }
+        bx -= p.producers;
+    }
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int ks = wave % KS;                           // which K slice
     const int rs = wave / KS;                           // which row set of the block
-    const int m = blockIdx.y;
-    const int n0 = (blockIdx.x * kRowSets + rs) * ROWS;
-    const bool wave_active = n0 < p.N;
-    const int chunk0 = ks * CPW;
+    const int n0 = (bx * kRowSets + rs) * ROWS;
 
-    // activations of this wave's K range, kept for all rows
-    XFrag<BITS> xf[CPW];
+    // Every load below is unconditional (addresses clamped into the tensors) so that the whole
+    // wave's traffic is in flight before anything waits; clamped lanes are zeroed afterwards.
+    int kc[CPW];
+    bool kv[CPW];
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+        const int k0 = ((ks * CPW + c) * 64 + lane) * kLaneCodes;
+        kv[c] = k0 < p.K;
+        kc[c] = kv[c] ? k0 : 0;
+    }
+    int jc[kRI];
+    bool jv[kRI];
+#pragma unroll
+    for (int q = 0; q < kRI; ++q) {
+        const int j = (q * 64 + lane) * 2;
+        jv[q] = RI > 0 && j < p.r;
+        jc[q] = jv[q] ? j : 0;
+    }
+
+    uint4 xraw[CPW][4];
     const uint16_t *xrow = p.x + (size_t)m * p.K;
 #pragma unroll
     for (int c = 0; c < CPW; ++c) {
-        const int k0 = (chunk0 + c) * kChunk + lane * kLaneCodes;
-        xf[c].load(xrow, k0, wave_active && k0 < p.K);
-    }
-
-    // down-projection result for this lane's taps: t[j], j = (i*64 + lane)*2 + {0,1}
-    float t0[RI > 0 ? RI : 1], t1[RI > 0 ? RI : 1];
-    if (RI > 0) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(xrow + kc[c]);
 #pragma unroll
-        for (int i = 0; i < RI; ++i) {
-            t0[i] = t1[i] = 0.0f;
-            const int j = (i * 64 + lane) * 2;
-            if (wave_active && ks == 0 && j < p.r) {
-                for (int s = 0; s < kSplitT; ++s) {
-                    const float2 v = *reinterpret_cast<const float2 *>(p.tpart + ((size_t)s * p.M + m) * p.r + j);
-                    t0[i] += v.x;
-                    t1[i] += v.y;
-                }
-            }
-        }
+        for (int i = 0; i < 4; ++i) xraw[c][i] = src[i];
     }
 
-    // issue every load of this wave's rows before using any of them
     CodeWords<BITS> cw[ROWS][CPW];
-    half_t sc[ROWS][CPW], zp[ROWS][CPW];
-    uint32_t bt[ROWS][RI > 0 ? RI : 1];
+    uint16_t sc[ROWS][CPW], zp[ROWS][CPW];
+    uint32_t bt[ROWS][kRI];
 #pragma unroll
     for (int i = 0; i < ROWS; ++i) {
-        const int n = min(n0 + i, p.N - 1);             // clamp: tail rows re-read a valid row, result discarded
+        const int n = min(n0 + i, p.N - 1);             // rows past the end re-read the last row; never stored
         const uint32_t *qrow = p.qw + (size_t)n * p.row_words;
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
-            const int k0 = (chunk0 + c) * kChunk + lane * kLaneCodes;
-            if (wave_active && k0 < p.K) {
-                cw[i][c].load(qrow + (size_t)(k0 / kLaneCodes) * kLaneWords);
-                const int g = k0 / kGroup;
-                sc[i][c] = __builtin_bit_cast(half_t, p.scales[(size_t)n * p.G + g]);
-                zp[i][c] = __builtin_bit_cast(half_t, p.zeros[(size_t)n * p.G + g]);
-            } else {
-                cw[i][c].zero();
-                sc[i][c] = (half_t)0.0f;
-                zp[i][c] = (half_t)0.0f;
-            }
+            cw[i][c].load(qrow + (kc[c] / kLaneCodes) * kLaneWords);
+            sc[i][c] = p.scales[(size_t)n * p.G + kc[c] / kGroup];
+            zp[i][c] = p.zeros[(size_t)n * p.G + kc[c] / kGroup];
         }
         if (RI > 0) {
 #pragma unroll
-            for (int q = 0; q < RI; ++q) {
-                const int j = (q * 64 + lane) * 2;
-                bt[i][q] = (wave_active && ks == 0 && j < p.r)
-                               ? *reinterpret_cast<const uint32_t *>(p.Bt + (size_t)n * p.r + j)
-                               : 0u;
+            for (int q = 0; q < RI; ++q) bt[i][q] = *reinterpret_cast<const uint32_t *>(p.Bt + (size_t)n * p.r + jc[q]);
+        }
+    }
+
+    // One early look at t: if the producers are already done it is in hand before the arithmetic.
+    // A lane needs t[j], t[j+1]: one 16-byte device-scope load {value, tag, value, tag}.
+    const __amdgpu_buffer_rsrc_t tbuf = dev_buffer(p.ttag + (size_t)m * p.r, (RI > 0 ? p.r : 1) * 8);
+    uint4_t tw[kRI];
+    bool ready = false;
+    if (RI > 0 && ks == 0) {
+        bool ok = true;
+#pragma unroll
+        for (int q = 0; q < RI; ++q) {
+            tw[q] = __builtin_amdgcn_raw_buffer_load_b128(tbuf, jc[q] * 8, 0, kCacheSc1);
+            ok = ok && (!jv[q] || (tw[q].y == tag && tw[q].w == tag));
+        }
+        ready = __all(ok);
+    }
+
+    XFrag<BITS> xf[CPW];
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) xf[c].arrange(xraw[c], kv[c]);
+
+    // main path: de-quantize and multiply; clamped lanes hold zero activations and add nothing
+    float acc[ROWS];
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) {
+        float a = 0.0f;
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) {
+            const float qx = cw[i][c].dot(xf[c].p);
+            const float s = (float)__builtin_bit_cast(half_t, sc[i][c]);
+            const float z = (float)__builtin_bit_cast(half_t, zp[i][c]);
+            a = fmaf(s, fmaf(-z, xf[c].sum, qx), a);
+        }
+        acc[i] = a;
+    }
+
+    // up-projection into the same accumulators (the K-slice-0 wave of each row set only)
+    if (RI > 0 && ks == 0) {
+        float t0[kRI], t1[kRI];
+        if (!ready) {
+#pragma unroll
+            for (int i = 0; i < ROWS; ++i) asm volatile("" : "+v"(acc[i]));   // finish the arithmetic before waiting
+            for (int it = 0; it < kSpinLimit && !ready; ++it) {
+                bool ok = true;
+#pragma unroll
+                for (int q = 0; q < RI; ++q) {
+                    tw[q] = __builtin_amdgcn_raw_buffer_load_b128(tbuf, jc[q] * 8, 0, kCacheSc1);
+                    ok = ok && (!jv[q] || (tw[q].y == tag && tw[q].w == tag));
+                }
+                ready = __all(ok);
+                if (!ready) __builtin_amdgcn_s_sleep(2);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < RI; ++q) {
+            if (ready) {
+                const uint32_t v0 = tw[q].x, v1 = tw[q].z;   // scalars first: bit_cast of a vector component reads the wrong lane
+                t0[q] = __builtin_bit_cast(float, v0);
+                t1[q] = __builtin_bit_cast(float, v1);
+            } else {                                    // producers never showed up in time: do it here
+                t0[q] = t1[q] = 0.0f;
+                const uint16_t *a0 = p.At + (size_t)jc[q] * p.K, *a1 = a0 + p.K;
+                for (int k = 0; k < p.K; ++k) {
+                    const float xv = (float)__builtin_bit_cast(half_t, xrow[k]);
+                    t0[q] = fmaf(xv, (float)__builtin_bit_cast(half_t, a0[k]), t0[q]);
+                    t1[q] = fmaf(xv, (float)__builtin_bit_cast(half_t, a1[k]), t1[q]);
+                }
+            }
+            const float u0 = jv[q] ? t0[q] : 0.0f, u1 = jv[q] ? t1[q] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < ROWS; ++i) {
+                const half2_t b = as_h2(bt[i][q]);
+                acc[i] = fmaf(u0, (float)b.x, acc[i]);
+                acc[i] = fmaf(u1, (float)b.y, acc[i]);
             }
         }
     }
@@ -242,25 +396,9 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvParams p)
     float out = 0.0f;   // lane i of the wave ends up holding row n0 + i
 #pragma unroll
     for (int i = 0; i < ROWS; ++i) {
-        float acc = 0.0f;
-#pragma unroll
-        for (int c = 0; c < CPW; ++c) {
-            const float qx = cw[i][c].dot(xf[c].p);
-            const float s = (float)sc[i][c], z = (float)zp[i][c];
-            acc = fmaf(s, fmaf(-z, xf[c].sum, qx), acc);
-        }
-        if (RI > 0) {
-#pragma unroll
-            for (int q = 0; q < RI; ++q) {
-                const half2_t b = as_h2(bt[i][q]);
-                acc = fmaf(t0[q], (float)b.x, acc);
-                acc = fmaf(t1[q], (float)b.y, acc);
-            }
-        }
-        acc = wave_sum(acc);
-        if (lane == i) out = acc;
+        const float tot = wave_sum(acc[i]);
+        if (lane == i) out = tot;
     }
-
     if (KS > 1) {
         if (lane < ROWS) red[wave * ROWS + lane] = out;
         __syncthreads();
@@ -270,77 +408,8 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvParams p)
             for (int q = 0; q < KS; ++q) out += red[(wave + q) * ROWS + lane];
         }
     }
-    if (wave_active && ks == 0 && lane < ROWS && n0 + lane < p.N)
+    if (ks == 0 && lane < ROWS && n0 + lane < p.N)
         p.y[(size_t)m * p.N + n0 + lane] = __builtin_bit_cast(uint16_t, (half_t)out);
-}
-
-// ------------------------------------------------------------------ down-projection (decode)
-
-// t[m][j] = sum_k x[m][k] * A[k][j], split over kSplitT blocks along K; block s writes its
-// partial sums to tpart[s][m][j].  Threads: (r/2) column pairs x (256/(r/2)) K sub-slices.
-template <int MT>
-__global__ __launch_bounds__(256) void fbq_down_proj_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ A,
-                                                            float *__restrict__ tpart, int M, int K, int r, int m_base)
-{
-    extern __shared__ float lds[];                      // [ksub][MT][r]
-    const int pairs = r >> 1;                           // r is a multiple of 8
-    const int ksub_n = 256 / pairs > 0 ? 256 / pairs : 1;
-    const int jp = threadIdx.x % pairs;
-    const int ksub = threadIdx.x / pairs;
-    const int kper = (K + kSplitT - 1) / kSplitT;
-    const int kbeg = blockIdx.x * kper;
-    const int kend = min(K, kbeg + kper);
-
-    float acc0[MT], acc1[MT];
-#pragma unroll
-    for (int m = 0; m < MT; ++m) acc0[m] = acc1[m] = 0.0f;
-
-    if (ksub < ksub_n && threadIdx.x < pairs * ksub_n) {
-        for (int k = kbeg + ksub; k < kend; k += ksub_n) {
-            const half2_t a = as_h2(*reinterpret_cast<const uint32_t *>(A + (size_t)k * r + 2 * jp));
-            const float a0 = (float)a.x, a1 = (float)a.y;
-#pragma unroll
-            for (int m = 0; m < MT; ++m) {
-                if (m_base + m < M) {
-                    const float xv = (float)__builtin_bit_cast(half_t, x[(size_t)(m_base + m) * K + k]);
-                    acc0[m] = fmaf(xv, a0, acc0[m]);
-                    acc1[m] = fmaf(xv, a1, acc1[m]);
-                }
-            }
-        }
-        for (int m = 0; m < MT; ++m) {
-            lds[(ksub * MT + m) * r + 2 * jp] = acc0[m];
-            lds[(ksub * MT + m) * r + 2 * jp + 1] = acc1[m];
-        }
-    }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < MT * r; idx += 256) {
-        const int m = idx / r, j = idx - m * r;
-        if (m_base + m < M) {
-            float s = 0.0f;
-            for (int q = 0; q < ksub_n; ++q) s += lds[(q * MT + m) * r + j];
-            tpart[((size_t)blockIdx.x * M + m_base + m) * r + j] = s;
-        }
-    }
-}
-
-template <int MT>
-static void launch_down_proj_mt(const LinearArgs &a, hipStream_t stream)
-{
-    const int pairs = a.r / 2;
-    const int ksub_n = 256 / pairs > 0 ? 256 / pairs : 1;
-    const size_t lds_bytes = (size_t)ksub_n * MT * a.r * sizeof(float);
-    hipLaunchKernelGGL(fbq_down_proj_kernel<MT>, dim3(kSplitT), dim3(256), lds_bytes, stream, a.x, a.A, a.tpart, a.M, a.K, a.r,
-                       0);
-}
-
-hipError_t launch_down_proj_decode(const LinearArgs &a, hipStream_t stream)
-{
-    if (a.M == 1) launch_down_proj_mt<1>(a, stream);
-    else if (a.M <= 4) launch_down_proj_mt<4>(a, stream);
-    else if (a.M <= 8) launch_down_proj_mt<8>(a, stream);
-    else launch_down_proj_mt<16>(a, stream);
-    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ dispatch
@@ -349,7 +418,7 @@ template <int BITS, int CPW, int KS, int ROWS>
 static hipError_t launch_gemv_ri(const GemvParams &p, hipStream_t stream)
 {
     constexpr int kRowSets = 4 / KS;
-    const dim3 grid(ceil_div(p.N, kRowSets * ROWS), p.M);
+    const dim3 grid(ceil_div(p.N, kRowSets * ROWS) + p.producers, p.M);
     const int ri = ceil_div(p.r, 128);
     switch (ri) {
     case 0: hipLaunchKernelGGL((fbq_gemv_kernel<BITS, CPW, KS, ROWS, 0>), grid, dim3(256), 0, stream, p); break;
@@ -395,13 +464,17 @@ static hipError_t launch_gemv_bits(const GemvParams &p, hipStream_t stream)
     return hipErrorInvalidValue;   // K > 32768: rejected by the caller's shape check
 }
 
+size_t decode_workspace_bytes(int M, int r) { return (size_t)M * r * sizeof(uint64_t); }
+
 hipError_t launch_gemv_decode(const LinearArgs &a, hipStream_t stream)
 {
     GemvParams p;
-    p.qw = a.qw; p.scales = a.scales; p.zeros = a.zeros; p.Bt = a.Bt; p.tpart = a.tpart; p.x = a.x; p.y = a.y;
+    p.qw = a.qw; p.scales = a.scales; p.zeros = a.zeros; p.At = a.At; p.Bt = a.Bt; p.x = a.x; p.y = a.y;
     p.M = a.M; p.N = a.N; p.K = a.K; p.r = a.r;
     p.row_words = (int)row_words(a.K, a.bits);
     p.G = a.K / kGroup;
+    p.producers = ceil_div(a.r, kProdCols);
+    p.ttag = (uint64_t *)a.workspace;
     return a.bits == 4 ? launch_gemv_bits<4>(p, stream) : launch_gemv_bits<3>(p, stream);
 }
 

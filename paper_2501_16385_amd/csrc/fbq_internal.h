@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "fbq.h"
 
 namespace fbq {
@@ -12,7 +14,6 @@ namespace fbq {
 constexpr int kGroup = 128;          // codes per (scale, zero) pair
 constexpr int kLaneCodes = 32;       // codes one lane takes from one wave-wide load
 constexpr int kChunk = 64 * kLaneCodes;   // codes one wave-wide load covers (2048)
-constexpr int kSplitT = 8;           // split-K partial sums of the decode down-projection
 constexpr int kMaxRank = 256;
 constexpr int kMaxK = 16 * kChunk;      // 32768: the decode kernel keeps a wave's activations in registers
 constexpr int kDecodeMaxM = 16;
@@ -26,25 +27,25 @@ struct LinearArgs {
     const uint32_t *qw;
     const uint16_t *scales;
     const uint16_t *zeros;
-    const uint16_t *A;
+    const uint16_t *At;
     const uint16_t *Bt;
     const uint16_t *x;
     uint16_t *y;
-    float *tpart;     // decode: [kSplitT][M][r] fp32 partial sums of x.A; prefill: [M][r] fp16 pairs (see prefill)
+    void *workspace;  // see decode_workspace_bytes / prefill_workspace_bytes
     int M, N, K, r, bits;
 };
 
 // Launchers (validated arguments only).  Each returns the hipError_t of its launches.
-hipError_t launch_down_proj_decode(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_gemv_decode(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_down_proj_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_unpack(const fbq_desc &d, const uint32_t *qw, uint8_t *codes, hipStream_t stream);
 hipError_t launch_reconstruct(const fbq_desc &d, const uint32_t *qw, const uint16_t *scales, const uint16_t *zeros,
-                              const uint16_t *A, const uint16_t *Bt, float *W_hat, hipStream_t stream);
-hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t *A, const uint16_t *Bt, uint32_t *qw,
+                              const uint16_t *At, const uint16_t *Bt, float *W_hat, hipStream_t stream);
+hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t *At, const uint16_t *Bt, uint32_t *qw,
                            uint16_t *scales, uint16_t *zeros, hipStream_t stream);
 
+size_t decode_workspace_bytes(int M, int r);
 size_t prefill_workspace_bytes(int M, int r);
 
 }  // namespace fbq

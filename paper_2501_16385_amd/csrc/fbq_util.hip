@@ -36,9 +36,9 @@ hipError_t launch_unpack(const fbq_desc &d, const uint32_t *qw, uint8_t *codes, 
     return hipGetLastError();
 }
 
-// W_F[n,k] = s*(q - z) + sum_j A[k,j] * Bt[n,j]   (Sec. 4.1: W_F = Q(W - Sigma) + Sigma), fp32.
+// W_F[n,k] = s*(q - z) + sum_j At[j,k] * Bt[n,j]   (Sec. 4.1: W_F = Q(W - Sigma) + Sigma), fp32.
 __global__ __launch_bounds__(256) void fbq_reconstruct_kernel(const uint32_t *__restrict__ qw, const uint16_t *__restrict__ scales,
-                                                              const uint16_t *__restrict__ zeros, const uint16_t *__restrict__ A,
+                                                              const uint16_t *__restrict__ zeros, const uint16_t *__restrict__ At,
                                                               const uint16_t *__restrict__ Bt, float *__restrict__ W_hat, int N,
                                                               int K, int r, int bits, int row_words)
 {
@@ -51,15 +51,15 @@ __global__ __launch_bounds__(256) void fbq_reconstruct_kernel(const uint32_t *__
     const float q = (float)code_of_row(qw + (size_t)n * row_words, bits, k);
     float sigma = 0.0f;
     for (int j = 0; j < r; ++j)
-        sigma = fmaf((float)__builtin_bit_cast(half_t, A[(size_t)k * r + j]),
+        sigma = fmaf((float)__builtin_bit_cast(half_t, At[(size_t)j * K + k]),
                      (float)__builtin_bit_cast(half_t, Bt[(size_t)n * r + j]), sigma);
     W_hat[(size_t)n * K + k] = s * (q - z) + sigma;
 }
 
 hipError_t launch_reconstruct(const fbq_desc &d, const uint32_t *qw, const uint16_t *scales, const uint16_t *zeros,
-                              const uint16_t *A, const uint16_t *Bt, float *W_hat, hipStream_t stream)
+                              const uint16_t *At, const uint16_t *Bt, float *W_hat, hipStream_t stream)
 {
-    hipLaunchKernelGGL(fbq_reconstruct_kernel, dim3(ceil_div(d.K, 256), d.N), dim3(256), 0, stream, qw, scales, zeros, A, Bt,
+    hipLaunchKernelGGL(fbq_reconstruct_kernel, dim3(ceil_div(d.K, 256), d.N), dim3(256), 0, stream, qw, scales, zeros, At, Bt,
                        W_hat, d.N, d.K, d.r, d.bits, (int)row_words(d.K, d.bits));
     return hipGetLastError();
 }
@@ -92,7 +92,7 @@ __device__ uint16_t double_to_half_bits(double d)
 
 // One block of 128 threads per (row, group).  fp64 with no fused multiply-add, so that the result
 // does not depend on contraction choices.
-__global__ __launch_bounds__(128) void fbq_quantize_kernel(const uint16_t *__restrict__ W, const uint16_t *__restrict__ A,
+__global__ __launch_bounds__(128) void fbq_quantize_kernel(const uint16_t *__restrict__ W, const uint16_t *__restrict__ At,
                                                            const uint16_t *__restrict__ Bt, uint32_t *__restrict__ qw,
                                                            uint16_t *__restrict__ scales, uint16_t *__restrict__ zeros, int N,
                                                            int K, int r, int bits, int row_words)
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(128) void fbq_quantize_kernel(const uint16_t *__res
     const int qmax = (1 << bits) - 1;
 
     double sigma = 0.0;
-    for (int j = 0; j < r; ++j) sigma = sigma + half_bits_to_double(A[(size_t)k * r + j]) * half_bits_to_double(Bt[(size_t)n * r + j]);
+    for (int j = 0; j < r; ++j) sigma = sigma + half_bits_to_double(At[(size_t)j * K + k]) * half_bits_to_double(Bt[(size_t)n * r + j]);
     const double R = half_bits_to_double(W[(size_t)n * K + k]) - sigma;       // feedback: quantize W - Sigma
 
     smin[i] = R;
@@ -166,10 +166,10 @@ __global__ __launch_bounds__(128) void fbq_quantize_kernel(const uint16_t *__res
     }
 }
 
-hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t *A, const uint16_t *Bt, uint32_t *qw,
+hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t *At, const uint16_t *Bt, uint32_t *qw,
                            uint16_t *scales, uint16_t *zeros, hipStream_t stream)
 {
-    hipLaunchKernelGGL(fbq_quantize_kernel, dim3(d.K / kGroup, d.N), dim3(128), 0, stream, W, A, Bt, qw, scales, zeros, d.N,
+    hipLaunchKernelGGL(fbq_quantize_kernel, dim3(d.K / kGroup, d.N), dim3(128), 0, stream, W, At, Bt, qw, scales, zeros, d.N,
                        d.K, d.r, d.bits, (int)row_words(d.K, d.bits));
     return hipGetLastError();
 }

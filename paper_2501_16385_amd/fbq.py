@@ -123,7 +123,7 @@ class PackedLayer:
     qweight: np.ndarray   # uint32 [N, K*bits/32]
     scales: np.ndarray    # float16 [N, G]
     zeros: np.ndarray     # float16 [N, G]
-    A: Optional[np.ndarray]    # float16 [K, r]
+    At: Optional[np.ndarray]   # float16 [r, K]
     Bt: Optional[np.ndarray]   # float16 [N, r]
 
 
@@ -146,7 +146,7 @@ def pack(d: Desc, codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray, A: O
         B = np.ascontiguousarray(B, dtype=np.float16)
         if A.shape != (d.K, d.r) or B.shape != (d.r, d.N):
             raise ValueError("shape mismatch")
-        A_out, Bt_out = np.empty((d.K, d.r), np.float16), np.empty((d.N, d.r), np.float16)
+        A_out, Bt_out = np.empty((d.r, d.K), np.float16), np.empty((d.N, d.r), np.float16)
     else:
         A = B = A_out = Bt_out = None
     rc = load().fbq_pack(ctypes.byref(d.c()), _np_ptr(codes), _np_ptr(scales), _np_ptr(zeros), _np_ptr(A), _np_ptr(B),
@@ -162,14 +162,14 @@ class DeviceLayer:
     qweight: "object"
     scales: "object"
     zeros: "object"
-    A: "object"
+    At: "object"
     Bt: "object"
 
 
 def upload_layer(p: PackedLayer, device="cuda") -> DeviceLayer:
     import torch
     t = lambda a: None if a is None else torch.from_numpy(a.view(np.int16) if a.dtype == np.float16 else a.view(np.int32)).to(device)
-    return DeviceLayer(p.desc, t(p.qweight), t(p.scales), t(p.zeros), t(p.A), t(p.Bt))
+    return DeviceLayer(p.desc, t(p.qweight), t(p.scales), t(p.zeros), t(p.At), t(p.Bt))
 
 
 def linear(layer: DeviceLayer, x, y=None, workspace=None, stream=None):
@@ -181,10 +181,10 @@ def linear(layer: DeviceLayer, x, y=None, workspace=None, stream=None):
         y = torch.empty((M, d.N), dtype=torch.float16, device=x.device)
     need = workspace_bytes(d, M)
     if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        workspace = torch.zeros(need, dtype=torch.uint8, device=x.device)
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = load().fbq_linear(ctypes.byref(d.c()), M, _dev_ptr(x), _dev_ptr(layer.qweight), _dev_ptr(layer.scales),
-                           _dev_ptr(layer.zeros), _dev_ptr(layer.A), _dev_ptr(layer.Bt), _dev_ptr(y), _dev_ptr(workspace),
+                           _dev_ptr(layer.zeros), _dev_ptr(layer.At), _dev_ptr(layer.Bt), _dev_ptr(y), _dev_ptr(workspace),
                            wbytes, _stream(stream))
     _check(rc, "fbq_linear")
     return y
@@ -196,7 +196,7 @@ def reconstruct(layer: DeviceLayer, stream=None):
     d = layer.desc
     out = torch.empty((d.N, d.K), dtype=torch.float32, device=layer.qweight.device)
     rc = load().fbq_reconstruct(ctypes.byref(d.c()), _dev_ptr(layer.qweight), _dev_ptr(layer.scales), _dev_ptr(layer.zeros),
-                                _dev_ptr(layer.A), _dev_ptr(layer.Bt), _dev_ptr(out), _stream(stream))
+                                _dev_ptr(layer.At), _dev_ptr(layer.Bt), _dev_ptr(out), _stream(stream))
     _check(rc, "fbq_reconstruct")
     return out
 
@@ -211,8 +211,8 @@ def unpack_codes(layer: DeviceLayer, stream=None):
     return out
 
 
-def quantize_feedback(d: Desc, W, A=None, Bt=None, stream=None) -> DeviceLayer:
-    """fbq_quantize_feedback: W [N, K] fp16, A [K, r], Bt [N, r] device tensors -> packed device layer."""
+def quantize_feedback(d: Desc, W, At=None, Bt=None, stream=None) -> DeviceLayer:
+    """fbq_quantize_feedback: W [N, K] fp16, At [r, K], Bt [N, r] device tensors -> packed device layer."""
     import torch
     dev = W.device
     nbytes = packed_bytes(d)
@@ -222,7 +222,7 @@ def quantize_feedback(d: Desc, W, A=None, Bt=None, stream=None) -> DeviceLayer:
     G = d.K // d.group
     s = torch.empty((d.N, G), dtype=torch.int16, device=dev)
     z = torch.empty((d.N, G), dtype=torch.int16, device=dev)
-    rc = load().fbq_quantize_feedback(ctypes.byref(d.c()), _dev_ptr(W), _dev_ptr(A), _dev_ptr(Bt), _dev_ptr(qw), _dev_ptr(s),
+    rc = load().fbq_quantize_feedback(ctypes.byref(d.c()), _dev_ptr(W), _dev_ptr(At), _dev_ptr(Bt), _dev_ptr(qw), _dev_ptr(s),
                                       _dev_ptr(z), _stream(stream))
     _check(rc, "fbq_quantize_feedback")
-    return DeviceLayer(d, qw, s, z, A, Bt)
+    return DeviceLayer(d, qw, s, z, At, Bt)

@@ -146,7 +146,7 @@ def test_gpu_feedback_quantizer_matches_oracle(bits, N, K, r):
     L = make_oracle_layer(spec, config=15)
     t16 = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
     Wd = t16(L.W)
-    Ad = t16(L.A) if r else None
+    Ad = t16(L.A.T) if r else None
     Btd = t16(L.B.T) if r else None
     dev = fbq.quantize_feedback(fbq.Desc(N, K, r, bits), Wd, Ad, Btd)
     codes = fbq.unpack_codes(dev).cpu().numpy()

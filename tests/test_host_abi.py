@@ -75,7 +75,7 @@ def test_host_pack_writes_the_documented_layout(bits):
     assert np.array_equal(p.qweight, orc.pack(codes, bits))           # same words as the oracle's packer
     assert np.array_equal(orc.unpack(p.qweight, K, bits), codes)      # and the oracle reads them back
     assert np.array_equal(p.scales, s) and np.array_equal(p.zeros, z)
-    assert np.array_equal(p.A, A) and np.array_equal(p.Bt, B.T)
+    assert np.array_equal(p.At, A.T) and np.array_equal(p.Bt, B.T)
     bad = codes.copy()
     bad[3, 5] = 2 ** bits
     with pytest.raises(fbq.FbqError) as e:
