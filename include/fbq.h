@@ -114,6 +114,33 @@ fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweig
                       const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
                       size_t workspace_bytes, fbq_stream stream);
 
+/* One layer of a grouped call: the arguments fbq_linear takes, per layer. */
+typedef struct {
+    fbq_desc desc;
+    const void *x;          /* device [M, K] fp16 (layers may share it: q/k/v, gate/up) */
+    const void *qweight;    /* device, layout above */
+    const void *scales;
+    const void *zeros;
+    const void *At;         /* NULL if desc.r == 0 */
+    const void *Bt;         /* NULL if desc.r == 0 */
+    void *y;                /* device [M, N] fp16, overwritten */
+    void *workspace;        /* as for fbq_linear; one per layer */
+    size_t workspace_bytes;
+} fbq_layer_call;
+
+/*
+ * fbq_linear_group - the hot path for several independent layers at once (Sec. 4.3 lists launch
+ * overhead as part of the sub-branch's cost; on this GPU a launch costs about as much as streaming
+ * a 4096x4096 INT4 layer, so layers that do not depend on each other - q/k/v, gate/up - should share
+ * one).  Every layer gets exactly the result fbq_linear gives it.  For M <= 16, layers with the same
+ * bits, the same K-derived kernel variant and a sub-branch (or all without one) are served by ONE
+ * launch, up to 8 layers per launch, in the order they appear; anything else, and every layer when
+ * M > 16, is launched on its own.
+ *   calls host array of n layers (read during the call only); M tokens, the same for all layers
+ * Errors: those of fbq_linear for any layer, reported before ANY launch.
+ */
+fbq_status fbq_linear_group(const fbq_layer_call *calls, int n, int M, fbq_stream stream);
+
 /*
  * fbq_reconstruct - validation.  W_hat[n,k] = s*(q - z) + sum_j At[j,k]*Bt[n,j], the paper's
  * W_F = Q(W - Sigma) + Sigma (Sec. 4.1), as fp32.   W_hat device [N, K] fp32, overwritten.

@@ -41,7 +41,7 @@ extern "C" size_t fbq_packed_bytes(const fbq_desc *d)
 extern "C" size_t fbq_workspace_bytes(const fbq_desc *d, int M)
 {
     if (fbq_check_desc(d) != FBQ_OK || M < 1 || d->r == 0) return 0;
-    if (M <= kDecodeMaxM) return decode_workspace_bytes(M, d->r);
+    if (M <= kDecodeMaxM) return decode_workspace_bytes(M, d->K, d->r);
     return prefill_workspace_bytes(M, d->r);
 }
 
@@ -115,9 +115,10 @@ static fbq_status hip_status(hipError_t e)
     return e == hipSuccess ? FBQ_OK : FBQ_ERR_HIP;
 }
 
-extern "C" fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
-                                 const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
-                                 size_t workspace_bytes, fbq_stream stream)
+// Validates one layer's arguments and fills the launch record; nothing is launched here.
+static fbq_status check_layer(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
+                              const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
+                              size_t workspace_bytes, LinearArgs *a)
 {
     fbq_status st = fbq_check_desc(d);
     if (st != FBQ_OK) return st;
@@ -130,25 +131,67 @@ extern "C" fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const 
     if (d->r > 0 && (misaligned(At) || misaligned(Bt))) return FBQ_ERR_ALIGN;
     if (need > 0 && misaligned(workspace)) return FBQ_ERR_ALIGN;
     if (workspace_bytes < need) return FBQ_ERR_WORKSPACE;
+    a->qw = (const uint32_t *)qweight;
+    a->scales = (const uint16_t *)scales;
+    a->zeros = (const uint16_t *)zeros;
+    a->At = (const uint16_t *)At;
+    a->Bt = (const uint16_t *)Bt;
+    a->x = (const uint16_t *)x;
+    a->y = (uint16_t *)y;
+    a->workspace = workspace;
+    a->M = M; a->N = d->N; a->K = d->K; a->r = d->r; a->bits = d->bits;
+    return FBQ_OK;
+}
 
-    LinearArgs a;
-    a.qw = (const uint32_t *)qweight;
-    a.scales = (const uint16_t *)scales;
-    a.zeros = (const uint16_t *)zeros;
-    a.At = (const uint16_t *)At;
-    a.Bt = (const uint16_t *)Bt;
-    a.x = (const uint16_t *)x;
-    a.y = (uint16_t *)y;
-    a.workspace = workspace;
-    a.M = M; a.N = d->N; a.K = d->K; a.r = d->r; a.bits = d->bits;
-    hipStream_t s = (hipStream_t)stream;
-
+static hipError_t launch_prefill(const LinearArgs &a, hipStream_t s)
+{
     hipError_t e = hipSuccess;
-    if (M <= kDecodeMaxM) {
-        e = launch_gemv_decode(a, s);
-    } else {
-        if (d->r > 0) e = launch_down_proj_prefill(a, s);
-        if (e == hipSuccess) e = launch_gemm_prefill(a, s);
+    if (a.r > 0) e = launch_down_proj_prefill(a, s);
+    if (e == hipSuccess) e = launch_gemm_prefill(a, s);
+    return e;
+}
+
+extern "C" fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
+                                 const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
+                                 size_t workspace_bytes, fbq_stream stream)
+{
+    LinearArgs a;
+    const fbq_status st = check_layer(d, M, x, qweight, scales, zeros, At, Bt, y, workspace, workspace_bytes, &a);
+    if (st != FBQ_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    return hip_status(M <= kDecodeMaxM ? launch_gemv_decode(&a, 1, s) : launch_prefill(a, s));
+}
+
+extern "C" fbq_status fbq_linear_group(const fbq_layer_call *calls, int n, int M, fbq_stream stream)
+{
+    constexpr int kMaxCalls = 64;
+    if (!calls) return FBQ_ERR_NULL;
+    if (n < 1 || n > kMaxCalls) return FBQ_ERR_SHAPE;
+    LinearArgs args[kMaxCalls];
+    for (int i = 0; i < n; ++i) {
+        const fbq_layer_call &c = calls[i];
+        const fbq_status st = check_layer(&c.desc, M, c.x, c.qweight, c.scales, c.zeros, c.At, c.Bt, c.y, c.workspace,
+                                          c.workspace_bytes, &args[i]);
+        if (st != FBQ_OK) return st;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    if (M > kDecodeMaxM) {
+        for (int i = 0; i < n && e == hipSuccess; ++i) e = launch_prefill(args[i], s);
+        return hip_status(e);
+    }
+    bool done[kMaxCalls] = {false};
+    for (int i = 0; i < n && e == hipSuccess; ++i) {
+        if (done[i]) continue;
+        LinearArgs batch[kMaxGroup];
+        int nb = 0;
+        for (int j = i; j < n && nb < kMaxGroup; ++j) {
+            if (!done[j] && decode_group_compatible(args[i], args[j])) {
+                batch[nb++] = args[j];
+                done[j] = true;
+            }
+        }
+        e = launch_gemv_decode(batch, nb, s);
     }
     return hip_status(e);
 }

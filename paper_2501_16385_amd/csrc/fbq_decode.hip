@@ -17,12 +17,14 @@
 // (each costs microseconds across the eight L2s) and nothing to reset afterwards.  Words are
 // written and read with device-scope (sc1) accesses, which do not linger in a per-XCD L2.
 //
-// Work decomposition of the fused kernel.  A wave owns kRows consecutive output rows and a
-// contiguous K range; its 64 lanes lie along K.  One wave-wide load covers 2048 codes
-// (INT4: 16 B per lane, INT3: 12 B per lane, both fully coalesced), so a lane always holds 32
-// consecutive codes of one quantization group.  The lane's 32 activations stay in registers for
-// the whole kernel (they are the same for every row), pre-arranged as the fp16 pairs that the
-// code extraction produces.
+// Work decomposition of the fused kernel.  Waves are persistent: a wave owns a contiguous K range
+// and walks over tiles of ROWS consecutive output rows with a fixed stride, loading the next tile
+// while it computes the current one.  Its 64 lanes lie along K.  One wave-wide load covers 2048
+// codes (INT4: 16 B per lane, INT3: 12 B per lane, both fully coalesced), so a lane always holds
+// 32 consecutive codes of one quantization group.  The lane's activations are loaded once and
+// stay in registers for every tile (they are the same for every row), pre-arranged as the fp16
+// pairs that the code extraction produces.  One launch can serve several layers with the same K
+// (q/k/v, gate/up): blocks are shared out in proportion to the layers' sizes.
 //
 // Code extraction without conversion instructions.  Masking a packed word with 0x000F000F (INT4)
 // or 0x00070007 (INT3) leaves two codes, one per 16-bit half, each in the low mantissa bits of an
@@ -31,6 +33,7 @@
 // its accumulator scaled by 2^(24-o) once per 32 codes.  The group's scale and zero are applied
 // once per lane and chunk:  s * (sum q.x - z * sum x).
 #include <hip/hip_fp16.h>
+#include <stdlib.h>
 
 #include "fbq_internal.h"
 
@@ -165,7 +168,7 @@ struct CodeWords<3> {
 
 // ------------------------------------------------------------------ fused GEMV kernel
 
-struct GemvParams {
+struct LayerParams {
     const uint32_t *qw;
     const uint16_t *scales;
     const uint16_t *zeros;
@@ -173,14 +176,23 @@ struct GemvParams {
     const uint16_t *Bt;   // [N][r]
     const uint16_t *x;    // [M][K]
     uint16_t *y;          // [M][N]
-    uint64_t *ttag;       // workspace: [M][r] words {fp32 value (low half), launch tag (high half)}
-    int M, N, K, r;
+    uint64_t *ttag;       // workspace: [M][tslices][r] words {fp32 partial sum (low half), launch tag (high half)}
+    int N, K, r;
     int row_words;        // words per packed row
     int G;                // groups per row
-    int producers;        // producer blocks at the front of the grid (0 when r == 0)
+    int tslices;          // K slices of the down-projection (1..kMaxTSlices); consumers add the partial sums
+    int producers;        // producer blocks in front of this layer's consumer blocks (0 when r == 0)
+    int blocks;           // consumer blocks of this layer
+};
+
+struct GemvGroup {
+    int n_layers;
+    int block_begin[kMaxGroup + 1];   // first block of each layer (producers first, then consumers)
+    LayerParams layer[kMaxGroup];
 };
 
 constexpr int kProdCols = 4;          // columns of A per producer block
+constexpr int kProdPasses = 4;        // passes of 2048 activations a producer block makes at most (all loads issued up front)
 constexpr int kSpinLimit = 1 << 15;   // polls (~0.3 us each) before a wave gives up and computes t itself
 constexpr int kCacheSc1 = 16 | (1 << 31);   // buffer-load policy: device scope (sc1), and volatile so that a poll is never hoisted or merged
 
@@ -202,30 +214,45 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t dev_buffer(const void *p, int 
 
 typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
 
-// Producer block b of token m: t[j] for its kProdCols columns, lanes along K like the main kernel.
-__device__ void produce_t(const GemvParams &p, int m, int b, uint32_t tag, float *lds)
+// Producer block b of token m: partial sums of t[j] for kProdCols columns over one K slice of at most
+// kProdPasses * 2048 activations, lanes along K like the main kernel; every load is issued up front.
+__device__ void produce_t(const LayerParams &p, int m, int b, uint32_t tag, float *lds)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint16_t *xrow = p.x + (size_t)m * p.K;
-    const int j0 = b * kProdCols;
+    const int col_blocks = (p.r + kProdCols - 1) / kProdCols;
+    const int slice = b / col_blocks;
+    const int j0 = (b - slice * col_blocks) * kProdCols;
+    const int kbeg = slice * (kProdPasses * 2048);
+    const int kend = min(p.K, kbeg + kProdPasses * 2048);
+
+    uint4 xv[kProdPasses], av[kProdPasses][kProdCols];
+    bool valid[kProdPasses];
+#pragma unroll
+    for (int i = 0; i < kProdPasses; ++i) {
+        const int k0 = kbeg + (i * 256 + tid) * 8;
+        valid[i] = k0 < kend;
+        const int kk = valid[i] ? k0 : kbeg;            // clamped: loaded, then ignored
+        xv[i] = *reinterpret_cast<const uint4 *>(xrow + kk);
+#pragma unroll
+        for (int c = 0; c < kProdCols; ++c) {
+            const int j = min(j0 + c, p.r - 1);         // r is a multiple of 8: never clamps
+            av[i][c] = *reinterpret_cast<const uint4 *>(p.At + (size_t)j * p.K + kk);
+        }
+    }
     float acc[kProdCols];
 #pragma unroll
     for (int c = 0; c < kProdCols; ++c) acc[c] = 0.0f;
-#pragma unroll 2
-    for (int k0 = tid * 8; k0 < p.K; k0 += 256 * 8) {
-        const uint4 xv = *reinterpret_cast<const uint4 *>(xrow + k0);
-        uint4 av[kProdCols];
+#pragma unroll
+    for (int i = 0; i < kProdPasses; ++i) {
+        const uint32_t x0 = valid[i] ? xv[i].x : 0u, x1 = valid[i] ? xv[i].y : 0u, x2 = valid[i] ? xv[i].z : 0u,
+                       x3 = valid[i] ? xv[i].w : 0u;
 #pragma unroll
         for (int c = 0; c < kProdCols; ++c) {
-            const int j = min(j0 + c, p.r - 1);         // r is a multiple of 8: never clamps, keeps loads unconditional
-            av[c] = *reinterpret_cast<const uint4 *>(p.At + (size_t)j * p.K + k0);
-        }
-#pragma unroll
-        for (int c = 0; c < kProdCols; ++c) {
-            acc[c] = dot2(av[c].x, as_h2(xv.x), acc[c]);
-            acc[c] = dot2(av[c].y, as_h2(xv.y), acc[c]);
-            acc[c] = dot2(av[c].z, as_h2(xv.z), acc[c]);
-            acc[c] = dot2(av[c].w, as_h2(xv.w), acc[c]);
+            acc[c] = dot2(av[i][c].x, as_h2(x0), acc[c]);
+            acc[c] = dot2(av[i][c].y, as_h2(x1), acc[c]);
+            acc[c] = dot2(av[i][c].z, as_h2(x2), acc[c]);
+            acc[c] = dot2(av[i][c].w, as_h2(x3), acc[c]);
         }
     }
 #pragma unroll
@@ -237,23 +264,57 @@ __device__ void produce_t(const GemvParams &p, int m, int b, uint32_t tag, float
     if (tid < kProdCols && j0 + tid < p.r) {
         const float s = (lds[tid] + lds[kProdCols + tid]) + (lds[2 * kProdCols + tid] + lds[3 * kProdCols + tid]);
         const uint64_t word = (uint64_t)__builtin_bit_cast(uint32_t, s) | ((uint64_t)tag << 32);
-        __hip_atomic_store(p.ttag + (size_t)m * p.r + j0 + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(p.ttag + ((size_t)m * p.tslices + slice) * p.r + j0 + tid, word, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
+// Everything one wave loads for one tile of ROWS rows.
+template <int BITS, int CPW, int ROWS, int RI>
+struct RowTile {
+    static constexpr int kRI = RI > 0 ? RI : 1;
+    static constexpr int kLaneWords = BITS == 4 ? 4 : 3;
+    CodeWords<BITS> cw[ROWS][CPW];
+    uint32_t sc[ROWS][CPW], zp[ROWS][CPW];   // fp16 bits, one per register: packing two would stall the load stream
+    uint32_t bt[ROWS][kRI];
+
+    // Unconditional loads: rows past the end re-read the last row (never stored), lanes past K re-read
+    // chunk 0 (their activations are zero), taps past r re-read tap 0 (their t is zero).
+    __device__ __forceinline__ void load(const LayerParams &p, int n0, const int (&kc)[CPW], const int (&jc)[kRI])
+    {
+#pragma unroll
+        for (int i = 0; i < ROWS; ++i) {
+            const int n = min(n0 + i, p.N - 1);
+            const uint32_t *qrow = p.qw + (size_t)n * p.row_words;
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) {
+                cw[i][c].load(qrow + (kc[c] / kLaneCodes) * kLaneWords);
+                sc[i][c] = p.scales[(size_t)n * p.G + kc[c] / kGroup];
+                zp[i][c] = p.zeros[(size_t)n * p.G + kc[c] / kGroup];
+            }
+            if (RI > 0) {
+#pragma unroll
+                for (int q = 0; q < RI; ++q) bt[i][q] = *reinterpret_cast<const uint32_t *>(p.Bt + (size_t)n * p.r + jc[q]);
+            }
+        }
+    }
+};
+
 // BITS: 3 or 4.  CPW: chunks (of 2048 codes) per wave.  KS: waves of a block that split K.
-// ROWS: rows per wave.  RI: ceil(r/128), 0 = branch-free twin.
+// ROWS: rows per tile.  RI: ceil(r/128), 0 = branch-free twin.
 template <int BITS, int CPW, int KS, int ROWS, int RI>
-__global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvParams p)
+__global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
 {
     constexpr int kWaves = 4;
     constexpr int kRowSets = kWaves / KS;               // row sets per block
-    constexpr int kLaneWords = BITS == 4 ? 4 : 3;
     constexpr int kRI = RI > 0 ? RI : 1;
     __shared__ float red[kWaves * (ROWS > kProdCols ? ROWS : kProdCols)];   // K-split sums, or the producer's wave sums
 
     const int m = blockIdx.y;
-    int bx = blockIdx.x;
+    int l = 0;
+    while (l + 1 < g.n_layers && (int)blockIdx.x >= g.block_begin[l + 1]) ++l;
+    const LayerParams &p = g.layer[l];
+    int bx = (int)blockIdx.x - g.block_begin[l];
     uint32_t tag = 0;
     if (RI > 0) {
         tag = launch_tag();
@@ -268,10 +329,11 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvParams p)
     const int wave = threadIdx.x >> 6;
     const int ks = wave % KS;                           // which K slice
     const int rs = wave / KS;                           // which row set of the block
-    const int n0 = (bx * kRowSets + rs) * ROWS;
+    const int ntiles = (p.N + ROWS - 1) / ROWS;
+    const int tstride = p.blocks * kRowSets;
+    const int trips = (ntiles - bx * kRowSets + tstride - 1) / tstride;   // block-uniform (>= 1 by construction)
+    int tile = bx * kRowSets + rs;
 
-    // Every load below is unconditional (addresses clamped into the tensors) so that the whole
-    // wave's traffic is in flight before anything waits; clamped lanes are zeroed afterwards.
     int kc[CPW];
     bool kv[CPW];
 #pragma unroll
@@ -289,6 +351,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvParams p)
         jc[q] = jv[q] ? j : 0;
     }
 
+    // activations of this wave's K range: loaded once, used for every tile
     uint4 xraw[CPW][4];
     const uint16_t *xrow = p.x + (size_t)m * p.K;
 #pragma unroll
@@ -298,184 +361,268 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvParams p)
         for (int i = 0; i < 4; ++i) xraw[c][i] = src[i];
     }
 
-    CodeWords<BITS> cw[ROWS][CPW];
-    uint16_t sc[ROWS][CPW], zp[ROWS][CPW];
-    uint32_t bt[ROWS][kRI];
-#pragma unroll
-    for (int i = 0; i < ROWS; ++i) {
-        const int n = min(n0 + i, p.N - 1);             // rows past the end re-read the last row; never stored
-        const uint32_t *qrow = p.qw + (size_t)n * p.row_words;
-#pragma unroll
-        for (int c = 0; c < CPW; ++c) {
-            cw[i][c].load(qrow + (kc[c] / kLaneCodes) * kLaneWords);
-            sc[i][c] = p.scales[(size_t)n * p.G + kc[c] / kGroup];
-            zp[i][c] = p.zeros[(size_t)n * p.G + kc[c] / kGroup];
-        }
-        if (RI > 0) {
-#pragma unroll
-            for (int q = 0; q < RI; ++q) bt[i][q] = *reinterpret_cast<const uint32_t *>(p.Bt + (size_t)n * p.r + jc[q]);
-        }
-    }
+    RowTile<BITS, CPW, ROWS, RI> cur, nxt;
+    cur.load(p, min(tile, ntiles - 1) * ROWS, kc, jc);
 
-    // One early look at t: if the producers are already done it is in hand before the arithmetic.
+    // One early request for t, issued behind the weight loads and looked at only after the first tile's
+    // arithmetic: if the producers were already done by then, no time is spent waiting for it.
     // A lane needs t[j], t[j+1]: one 16-byte device-scope load {value, tag, value, tag}.
-    const __amdgpu_buffer_rsrc_t tbuf = dev_buffer(p.ttag + (size_t)m * p.r, (RI > 0 ? p.r : 1) * 8);
-    uint4_t tw[kRI];
-    bool ready = false;
-    if (RI > 0 && ks == 0) {
+    // With several K slices there is one such word pair per slice, and the lane adds the partial sums.
+    const int tslices = RI > 0 ? p.tslices : 1;
+    const __amdgpu_buffer_rsrc_t tbuf = dev_buffer(p.ttag + (size_t)m * tslices * p.r, (RI > 0 ? tslices * p.r : 1) * 8);
+    uint4_t tw[kRI][kMaxTSlices];
+    float t0[kRI], t1[kRI];
+    bool have_t = false;
+    auto request_t = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < RI; ++q)
+#pragma unroll
+            for (int sl = 0; sl < kMaxTSlices; ++sl)
+                if (sl < tslices) tw[q][sl] = __builtin_amdgcn_raw_buffer_load_b128(tbuf, (sl * p.r + jc[q]) * 8, 0, kCacheSc1);
+    };
+    auto t_arrived = [&]() __attribute__((always_inline)) {
         bool ok = true;
 #pragma unroll
-        for (int q = 0; q < RI; ++q) {
-            tw[q] = __builtin_amdgcn_raw_buffer_load_b128(tbuf, jc[q] * 8, 0, kCacheSc1);
-            ok = ok && (!jv[q] || (tw[q].y == tag && tw[q].w == tag));
-        }
-        ready = __all(ok);
-    }
+        for (int q = 0; q < RI; ++q)
+#pragma unroll
+            for (int sl = 0; sl < kMaxTSlices; ++sl)
+                if (sl < tslices) ok = ok && (!jv[q] || (tw[q][sl].y == tag && tw[q][sl].w == tag));
+        return (bool)__all(ok);
+    };
+    __builtin_amdgcn_sched_barrier(0);
+    if (RI > 0 && ks == 0) request_t();
+    __builtin_amdgcn_sched_barrier(0);
 
     XFrag<BITS> xf[CPW];
 #pragma unroll
     for (int c = 0; c < CPW; ++c) xf[c].arrange(xraw[c], kv[c]);
 
-    // main path: de-quantize and multiply; clamped lanes hold zero activations and add nothing
-    float acc[ROWS];
+    // Two tile buffers used alternately (no copies between them): the loads of one tile are in flight
+    // while the other is worked on.
+    auto process = [&](const RowTile<BITS, CPW, ROWS, RI> &cur, int tile) __attribute__((always_inline)) {
+        // main path: de-quantize and multiply; clamped lanes hold zero activations and add nothing
+        float acc[ROWS];
 #pragma unroll
-    for (int i = 0; i < ROWS; ++i) {
-        float a = 0.0f;
+        for (int i = 0; i < ROWS; ++i) {
+            float a = 0.0f;
 #pragma unroll
-        for (int c = 0; c < CPW; ++c) {
-            const float qx = cw[i][c].dot(xf[c].p);
-            const float s = (float)__builtin_bit_cast(half_t, sc[i][c]);
-            const float z = (float)__builtin_bit_cast(half_t, zp[i][c]);
-            a = fmaf(s, fmaf(-z, xf[c].sum, qx), a);
+            for (int c = 0; c < CPW; ++c) {
+                const float qx = cur.cw[i][c].dot(xf[c].p);
+                const float s = (float)__builtin_bit_cast(half_t, (uint16_t)cur.sc[i][c]);
+                const float z = (float)__builtin_bit_cast(half_t, (uint16_t)cur.zp[i][c]);
+                a = fmaf(s, fmaf(-z, xf[c].sum, qx), a);
+            }
+            acc[i] = a;
         }
-        acc[i] = a;
-    }
 
-    // up-projection into the same accumulators (the K-slice-0 wave of each row set only)
-    if (RI > 0 && ks == 0) {
-        float t0[kRI], t1[kRI];
-        if (!ready) {
+        // up-projection into the same accumulators (the K-slice-0 wave of each row set only)
+        if (RI > 0 && ks == 0) {
+            if (!have_t) {                              // first tile only: take t, waiting if it is not there yet
+                bool ready = t_arrived();
+                if (!ready) {
 #pragma unroll
-            for (int i = 0; i < ROWS; ++i) asm volatile("" : "+v"(acc[i]));   // finish the arithmetic before waiting
-            for (int it = 0; it < kSpinLimit && !ready; ++it) {
-                bool ok = true;
+                    for (int i = 0; i < ROWS; ++i) asm volatile("" : "+v"(acc[i]));   // finish the arithmetic before waiting
+                    for (int spin = 0; spin < kSpinLimit && !ready; ++spin) {
+                        request_t();
+                        ready = t_arrived();
+                        if (!ready) __builtin_amdgcn_s_sleep(2);
+                    }
+                }
 #pragma unroll
                 for (int q = 0; q < RI; ++q) {
-                    tw[q] = __builtin_amdgcn_raw_buffer_load_b128(tbuf, jc[q] * 8, 0, kCacheSc1);
-                    ok = ok && (!jv[q] || (tw[q].y == tag && tw[q].w == tag));
+                    if (ready) {
+                        t0[q] = t1[q] = 0.0f;
+#pragma unroll
+                        for (int sl = 0; sl < kMaxTSlices; ++sl) {
+                            if (sl < tslices) {
+                                const uint32_t v0 = tw[q][sl].x, v1 = tw[q][sl].z;   // scalars first: bit_cast of a vector component reads the wrong lane
+                                t0[q] += __builtin_bit_cast(float, v0);
+                                t1[q] += __builtin_bit_cast(float, v1);
+                            }
+                        }
+                    } else {                            // producers never showed up in time: do it here
+                        t0[q] = t1[q] = 0.0f;
+                        const uint16_t *a0 = p.At + (size_t)jc[q] * p.K, *a1 = a0 + p.K;
+                        for (int k = 0; k < p.K; ++k) {
+                            const float xv = (float)__builtin_bit_cast(half_t, xrow[k]);
+                            t0[q] = fmaf(xv, (float)__builtin_bit_cast(half_t, a0[k]), t0[q]);
+                            t1[q] = fmaf(xv, (float)__builtin_bit_cast(half_t, a1[k]), t1[q]);
+                        }
+                    }
+                    if (!jv[q]) t0[q] = t1[q] = 0.0f;
                 }
-                ready = __all(ok);
-                if (!ready) __builtin_amdgcn_s_sleep(2);
+                have_t = true;
+            }
+#pragma unroll
+            for (int q = 0; q < RI; ++q) {
+#pragma unroll
+                for (int i = 0; i < ROWS; ++i) {
+                    const half2_t b = as_h2(cur.bt[i][q]);
+                    acc[i] = fmaf(t0[q], (float)b.x, acc[i]);
+                    acc[i] = fmaf(t1[q], (float)b.y, acc[i]);
+                }
             }
         }
-#pragma unroll
-        for (int q = 0; q < RI; ++q) {
-            if (ready) {
-                const uint32_t v0 = tw[q].x, v1 = tw[q].z;   // scalars first: bit_cast of a vector component reads the wrong lane
-                t0[q] = __builtin_bit_cast(float, v0);
-                t1[q] = __builtin_bit_cast(float, v1);
-            } else {                                    // producers never showed up in time: do it here
-                t0[q] = t1[q] = 0.0f;
-                const uint16_t *a0 = p.At + (size_t)jc[q] * p.K, *a1 = a0 + p.K;
-                for (int k = 0; k < p.K; ++k) {
-                    const float xv = (float)__builtin_bit_cast(half_t, xrow[k]);
-                    t0[q] = fmaf(xv, (float)__builtin_bit_cast(half_t, a0[k]), t0[q]);
-                    t1[q] = fmaf(xv, (float)__builtin_bit_cast(half_t, a1[k]), t1[q]);
-                }
-            }
-            const float u0 = jv[q] ? t0[q] : 0.0f, u1 = jv[q] ? t1[q] : 0.0f;
-#pragma unroll
-            for (int i = 0; i < ROWS; ++i) {
-                const half2_t b = as_h2(bt[i][q]);
-                acc[i] = fmaf(u0, (float)b.x, acc[i]);
-                acc[i] = fmaf(u1, (float)b.y, acc[i]);
-            }
-        }
-    }
 
-    float out = 0.0f;   // lane i of the wave ends up holding row n0 + i
+        float out = 0.0f;   // lane i of the wave ends up holding row n0 + i
 #pragma unroll
-    for (int i = 0; i < ROWS; ++i) {
-        const float tot = wave_sum(acc[i]);
-        if (lane == i) out = tot;
-    }
-    if (KS > 1) {
-        if (lane < ROWS) red[wave * ROWS + lane] = out;
-        __syncthreads();
-        if (ks == 0 && lane < ROWS) {
-            out = 0.0f;
-#pragma unroll
-            for (int q = 0; q < KS; ++q) out += red[(wave + q) * ROWS + lane];
+        for (int i = 0; i < ROWS; ++i) {
+            const float tot = wave_sum(acc[i]);
+            if (lane == i) out = tot;
         }
+        if (KS > 1) {
+            __syncthreads();                            // previous trip's sums have been read
+            if (lane < ROWS) red[wave * ROWS + lane] = out;
+            __syncthreads();
+            if (ks == 0 && lane < ROWS) {
+                out = 0.0f;
+#pragma unroll
+                for (int q = 0; q < KS; ++q) out += red[(wave + q) * ROWS + lane];
+            }
+        }
+        const int n0 = tile * ROWS;
+        if (ks == 0 && lane < ROWS && tile < ntiles && n0 + lane < p.N)
+            p.y[(size_t)m * p.N + n0 + lane] = __builtin_bit_cast(uint16_t, (half_t)out);
+    };
+
+    // Steady state: both prefetches unconditional, so the compiler can count exactly how many loads
+    // are younger than the tile being used.  trips is block-uniform; the last one or two tiles follow.
+    int it = 0;
+    for (; it + 2 < trips; it += 2) {
+        nxt.load(p, min(tile + tstride, ntiles - 1) * ROWS, kc, jc);
+        process(cur, tile);
+        cur.load(p, min(tile + 2 * tstride, ntiles - 1) * ROWS, kc, jc);
+        process(nxt, tile + tstride);
+        tile += 2 * tstride;
     }
-    if (ks == 0 && lane < ROWS && n0 + lane < p.N)
-        p.y[(size_t)m * p.N + n0 + lane] = __builtin_bit_cast(uint16_t, (half_t)out);
+    if (it + 1 < trips) {
+        nxt.load(p, min(tile + tstride, ntiles - 1) * ROWS, kc, jc);
+        process(cur, tile);
+        process(nxt, tile + tstride);
+    } else {
+        process(cur, tile);
+    }
 }
 
 // ------------------------------------------------------------------ dispatch
 
-template <int BITS, int CPW, int KS, int ROWS>
-static hipError_t launch_gemv_ri(const GemvParams &p, hipStream_t stream)
+static int device_cu_count()
 {
-    constexpr int kRowSets = 4 / KS;
-    const dim3 grid(ceil_div(p.N, kRowSets * ROWS) + p.producers, p.M);
-    const int ri = ceil_div(p.r, 128);
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        return n;
+    }();
+    return cus;
+}
+
+// Variant of the kernel a layer needs: it depends on K (chunks per wave, K split), bits and rank class.
+struct Variant {
+    int bits, cpw, ks, ri;
+    bool operator==(const Variant &o) const { return bits == o.bits && cpw == o.cpw && ks == o.ks; }
+};
+
+static Variant variant_of(int K, int bits, int r)
+{
+    const int chunks = ceil_div(K, kChunk);
+    Variant v{bits, 0, 0, ceil_div(r, 128)};
+    if (chunks <= 4) { v.ks = 1; v.cpw = chunks; }
+    else if (chunks <= 8) { v.ks = 2; v.cpw = ceil_div(chunks, 2); }
+    else { v.ks = 4; v.cpw = ceil_div(chunks, 4) < 3 ? 3 : ceil_div(chunks, 4); }
+    if (v.ks > 1 && v.cpw < 3) v.cpw = 3;
+    return v;
+}
+
+template <int BITS, int CPW, int KS, int ROWS>
+static hipError_t launch_ri(const GemvGroup &g, int ri, dim3 grid, hipStream_t stream)
+{
     switch (ri) {
-    case 0: hipLaunchKernelGGL((fbq_gemv_kernel<BITS, CPW, KS, ROWS, 0>), grid, dim3(256), 0, stream, p); break;
-    case 1: hipLaunchKernelGGL((fbq_gemv_kernel<BITS, CPW, KS, ROWS, 1>), grid, dim3(256), 0, stream, p); break;
-    default: hipLaunchKernelGGL((fbq_gemv_kernel<BITS, CPW, KS, ROWS, 2>), grid, dim3(256), 0, stream, p); break;
+    case 0: hipLaunchKernelGGL((fbq_gemv_kernel<BITS, CPW, KS, ROWS, 0>), grid, dim3(256), 0, stream, g); break;
+    case 1: hipLaunchKernelGGL((fbq_gemv_kernel<BITS, CPW, KS, ROWS, 1>), grid, dim3(256), 0, stream, g); break;
+    default: hipLaunchKernelGGL((fbq_gemv_kernel<BITS, CPW, KS, ROWS, 2>), grid, dim3(256), 0, stream, g); break;
     }
     return hipGetLastError();
 }
 
 template <int BITS, int CPW, int KS>
-static hipError_t launch_gemv_rows(const GemvParams &p, hipStream_t stream)
+static hipError_t launch_rows(const GemvGroup &g, int rows, int ri, dim3 grid, hipStream_t stream)
 {
-    // enough waves to cover the chip several times over, otherwise fewer rows per wave
-    const long waves4 = (long)ceil_div(p.N, 4) * KS * p.M;
-    if (waves4 >= 2048) return launch_gemv_ri<BITS, CPW, KS, 4>(p, stream);
-    return launch_gemv_ri<BITS, CPW, KS, 2>(p, stream);
+    if (rows == 4) return launch_ri<BITS, CPW, KS, 4>(g, ri, grid, stream);
+    return launch_ri<BITS, CPW, KS, 2>(g, ri, grid, stream);
 }
 
 template <int BITS>
-static hipError_t launch_gemv_bits(const GemvParams &p, hipStream_t stream)
+static hipError_t launch_bits(const GemvGroup &g, const Variant &v, int rows, dim3 grid, hipStream_t stream)
 {
-    const int chunks = ceil_div(p.K, kChunk);
-    if (chunks <= 4) {
-        switch (chunks) {
-        case 1: return launch_gemv_rows<BITS, 1, 1>(p, stream);
-        case 2: return launch_gemv_rows<BITS, 2, 1>(p, stream);
-        case 3: return launch_gemv_rows<BITS, 3, 1>(p, stream);
-        default: return launch_gemv_rows<BITS, 4, 1>(p, stream);
-        }
-    }
-    if (chunks <= 8) {
-        switch (ceil_div(chunks, 2)) {
-        case 3: return launch_gemv_rows<BITS, 3, 2>(p, stream);
-        default: return launch_gemv_rows<BITS, 4, 2>(p, stream);
-        }
-    }
-    if (chunks <= 16) {
-        switch (ceil_div(chunks, 4)) {
-        case 3: return launch_gemv_rows<BITS, 3, 4>(p, stream);
-        default: return launch_gemv_rows<BITS, 4, 4>(p, stream);
-        }
+    switch (v.ks * 10 + v.cpw) {
+    case 11: return launch_rows<BITS, 1, 1>(g, rows, v.ri, grid, stream);
+    case 12: return launch_rows<BITS, 2, 1>(g, rows, v.ri, grid, stream);
+    case 13: return launch_rows<BITS, 3, 1>(g, rows, v.ri, grid, stream);
+    case 14: return launch_rows<BITS, 4, 1>(g, rows, v.ri, grid, stream);
+    case 23: return launch_rows<BITS, 3, 2>(g, rows, v.ri, grid, stream);
+    case 24: return launch_rows<BITS, 4, 2>(g, rows, v.ri, grid, stream);
+    case 43: return launch_rows<BITS, 3, 4>(g, rows, v.ri, grid, stream);
+    case 44: return launch_rows<BITS, 4, 4>(g, rows, v.ri, grid, stream);
     }
     return hipErrorInvalidValue;   // K > 32768: rejected by the caller's shape check
 }
 
-size_t decode_workspace_bytes(int M, int r) { return (size_t)M * r * sizeof(uint64_t); }
+static int t_slices_of(int K) { return ceil_div(K, kProdPasses * 2048); }
 
-hipError_t launch_gemv_decode(const LinearArgs &a, hipStream_t stream)
+size_t decode_workspace_bytes(int M, int K, int r) { return (size_t)M * t_slices_of(K) * r * sizeof(uint64_t); }
+
+// Layers may share a launch when they need the same kernel variant.  A branch-free layer never joins
+// layers with a sub-branch: the fused kernel reads Bt unconditionally, and a branch-free layer has none.
+bool decode_group_compatible(const LinearArgs &a, const LinearArgs &b)
 {
-    GemvParams p;
-    p.qw = a.qw; p.scales = a.scales; p.zeros = a.zeros; p.At = a.At; p.Bt = a.Bt; p.x = a.x; p.y = a.y;
-    p.M = a.M; p.N = a.N; p.K = a.K; p.r = a.r;
-    p.row_words = (int)row_words(a.K, a.bits);
-    p.G = a.K / kGroup;
-    p.producers = ceil_div(a.r, kProdCols);
-    p.ttag = (uint64_t *)a.workspace;
-    return a.bits == 4 ? launch_gemv_bits<4>(p, stream) : launch_gemv_bits<3>(p, stream);
+    return variant_of(a.K, a.bits, a.r) == variant_of(b.K, b.bits, b.r) && a.M == b.M && (a.r > 0) == (b.r > 0);
+}
+
+hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_t stream)
+{
+    if (n_layers < 1 || n_layers > kMaxGroup) return hipErrorInvalidValue;
+    Variant v = variant_of(layers[0].K, layers[0].bits, layers[0].r);
+    const int M = layers[0].M;
+    double total_work = 0.0;
+    for (int i = 0; i < n_layers; ++i) {
+        if (!decode_group_compatible(layers[0], layers[i])) return hipErrorInvalidValue;
+        v.ri = std::max(v.ri, ceil_div(layers[i].r, 128));
+        total_work += (double)layers[i].N * layers[i].K;
+    }
+    const int row_sets = 4 / v.ks;
+    // Blocks to share out: two per CU keeps enough bytes in flight; a token dimension multiplies the grid.
+    int per_cu = 2;
+    if (const char *e = getenv("FBQ_TUNE_BLOCKS_PER_CU")) per_cu = std::max(1, atoi(e));   // TEMP tuning hook
+    const int budget = std::max(1, per_cu * device_cu_count() / std::max(1, std::min(M, 2)));
+    // Tiles of 4 rows when that still leaves every wave at least one tile, and registers allow; else 2.
+    long tiles4 = 0;
+    for (int i = 0; i < n_layers; ++i) tiles4 += ceil_div(layers[i].N, 4);
+    int rows = (v.cpw <= 2 && tiles4 >= (long)budget * row_sets) ? 4 : 2;
+    if (const char *e = getenv("FBQ_TUNE_ROWS")) rows = atoi(e) == 4 ? 4 : 2;   // TEMP tuning hook
+
+    GemvGroup g;
+    g.n_layers = n_layers;
+    int next_block = 0;
+    for (int i = 0; i < n_layers; ++i) {
+        const LinearArgs &a = layers[i];
+        LayerParams &p = g.layer[i];
+        p.qw = a.qw; p.scales = a.scales; p.zeros = a.zeros; p.At = a.At; p.Bt = a.Bt; p.x = a.x; p.y = a.y;
+        p.ttag = (uint64_t *)a.workspace;
+        p.N = a.N; p.K = a.K; p.r = a.r;
+        p.row_words = (int)row_words(a.K, a.bits);
+        p.G = a.K / kGroup;
+        p.tslices = t_slices_of(a.K);
+        p.producers = ceil_div(a.r, kProdCols) * p.tslices;
+        const int max_blocks = ceil_div(ceil_div(a.N, rows), row_sets);
+        const int share = (int)(budget * ((double)a.N * a.K / total_work) + 0.5);
+        p.blocks = std::max(1, std::min(max_blocks, share));
+        g.block_begin[i] = next_block;
+        next_block += p.producers + p.blocks;
+    }
+    for (int i = n_layers; i <= kMaxGroup; ++i) g.block_begin[i] = next_block;
+    const dim3 grid(next_block, M);
+    return v.bits == 4 ? launch_bits<4>(g, v, rows, grid, stream) : launch_bits<3>(g, v, rows, grid, stream);
 }
 
 }  // namespace fbq

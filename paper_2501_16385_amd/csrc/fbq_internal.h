@@ -17,6 +17,8 @@ constexpr int kChunk = 64 * kLaneCodes;   // codes one wave-wide load covers (20
 constexpr int kMaxRank = 256;
 constexpr int kMaxK = 16 * kChunk;      // 32768: the decode kernel keeps a wave's activations in registers
 constexpr int kDecodeMaxM = 16;
+constexpr int kMaxTSlices = 4;       // K slices of the decode down-projection: kMaxK / (4 passes * 2048)
+constexpr int kMaxGroup = 8;         // layers one grouped decode launch can serve
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
@@ -36,7 +38,8 @@ struct LinearArgs {
 };
 
 // Launchers (validated arguments only).  Each returns the hipError_t of its launches.
-hipError_t launch_gemv_decode(const LinearArgs &a, hipStream_t stream);
+hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_t stream);
+bool decode_group_compatible(const LinearArgs &a, const LinearArgs &b);
 hipError_t launch_down_proj_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_unpack(const fbq_desc &d, const uint32_t *qw, uint8_t *codes, hipStream_t stream);
@@ -45,7 +48,7 @@ hipError_t launch_reconstruct(const fbq_desc &d, const uint32_t *qw, const uint1
 hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t *At, const uint16_t *Bt, uint32_t *qw,
                            uint16_t *scales, uint16_t *zeros, hipStream_t stream);
 
-size_t decode_workspace_bytes(int M, int r);
+size_t decode_workspace_bytes(int M, int K, int r);
 size_t prefill_workspace_bytes(int M, int r);
 
 }  // namespace fbq

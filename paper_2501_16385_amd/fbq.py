@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libfbq.so")
 _lib: Optional[ctypes.CDLL] = None
 
 EXPORTED_SYMBOLS = ["fbq_status_string", "fbq_check_desc", "fbq_packed_bytes", "fbq_workspace_bytes", "fbq_pack",
-                    "fbq_linear", "fbq_reconstruct", "fbq_unpack_codes", "fbq_quantize_feedback"]
+                    "fbq_linear", "fbq_linear_group", "fbq_reconstruct", "fbq_unpack_codes", "fbq_quantize_feedback"]
 
 
 class FbqError(RuntimeError):
@@ -30,6 +30,12 @@ class FbqError(RuntimeError):
 class _CDesc(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int32), ("K", ctypes.c_int32), ("r", ctypes.c_int32), ("bits", ctypes.c_int32),
                 ("group", ctypes.c_int32)]
+
+
+class _CLayerCall(ctypes.Structure):
+    _fields_ = [("desc", _CDesc), ("x", ctypes.c_void_p), ("qweight", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("zeros", ctypes.c_void_p), ("At", ctypes.c_void_p), ("Bt", ctypes.c_void_p), ("y", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
 @dataclass(frozen=True)
@@ -69,6 +75,8 @@ def load() -> ctypes.CDLL:
         lib.fbq_pack.argtypes = [dp] + [vp] * 10
         lib.fbq_linear.restype = i32
         lib.fbq_linear.argtypes = [dp, i32] + [vp] * 8 + [sz, vp]
+        lib.fbq_linear_group.restype = i32
+        lib.fbq_linear_group.argtypes = [ctypes.POINTER(_CLayerCall), i32, i32, vp]
         lib.fbq_reconstruct.restype = i32
         lib.fbq_reconstruct.argtypes = [dp] + [vp] * 7
         lib.fbq_unpack_codes.restype = i32
@@ -188,6 +196,32 @@ def linear(layer: DeviceLayer, x, y=None, workspace=None, stream=None):
                            wbytes, _stream(stream))
     _check(rc, "fbq_linear")
     return y
+
+
+def make_group(layers, xs, ys, workspaces):
+    """Marshals a list of (layer, x, y, workspace) into the array fbq_linear_group takes (reusable)."""
+    arr = (_CLayerCall * len(layers))()
+    ptr = lambda t: None if t is None else t.data_ptr()
+    for i, (l, x, y, ws) in enumerate(zip(layers, xs, ys, workspaces)):
+        arr[i] = _CLayerCall(l.desc.c(), ptr(x), ptr(l.qweight), ptr(l.scales), ptr(l.zeros), ptr(l.At), ptr(l.Bt), ptr(y),
+                             ptr(ws), 0 if ws is None else ws.numel() * ws.element_size())
+    return arr
+
+
+def linear_group(layers, xs, ys=None, workspaces=None, stream=None):
+    """fbq_linear_group: several independent layers, same token count, as few launches as possible."""
+    import torch
+    M = int(xs[0].shape[0])
+    if ys is None:
+        ys = [torch.empty((M, l.desc.N), dtype=torch.float16, device=x.device) for l, x in zip(layers, xs)]
+    if workspaces is None:
+        workspaces = []
+        for l, x in zip(layers, xs):
+            need = workspace_bytes(l.desc, M)
+            workspaces.append(torch.zeros(need, dtype=torch.uint8, device=x.device) if need else None)
+    arr = make_group(layers, xs, ys, workspaces)
+    _check(load().fbq_linear_group(arr, len(layers), M, _stream(stream)), "fbq_linear_group")
+    return ys
 
 
 def reconstruct(layer: DeviceLayer, stream=None):

@@ -156,3 +156,69 @@ def test_gpu_feedback_quantizer_matches_oracle(bits, N, K, r):
     diff = codes.astype(np.int16) - L.codes.astype(np.int16)
     assert np.mean(diff != 0) <= 1e-4 and np.all(np.abs(diff) <= 1)
     assert np.array_equal(dev.qweight.cpu().numpy().view(np.uint32), L.words) or np.mean(diff != 0) > 0
+
+
+# ------------------------------------------------------------------ grouped launches, graph replay
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("M", [1, 3])
+def test_group_call_equals_single_calls(bits, M):
+    """q/k/v-style layers sharing x, one wider layer, one branch-free layer and one with another K:
+    fbq_linear_group must give every layer bit for bit what fbq_linear gives it, and match the oracle."""
+    import torch
+    import paper_2501_16385_amd as fbq
+    shapes = [(512, 2048, 32), (512, 2048, 32), (256, 2048, 64), (1100, 2048, 128), (300, 2048, 0), (384, 5120, 64)]
+    Ls = [make_oracle_layer(spec_of(N, K, r, bits), config=16, layer_index=i) for i, (N, K, r) in enumerate(shapes)]
+    devs = [to_device_layer(L) for L in Ls]
+    x_by_k = {K: fbq_synth.make_x(spec_of(8, K, 0, bits), M, 16, K) for K in {s[1] for s in shapes}}
+    xs_np = [x_by_k[K] for (_, K, _) in shapes]
+    xs = [torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16) for x in xs_np]
+    ys = fbq.linear_group(devs, xs)
+    torch.cuda.synchronize()
+    for L, dev, x_np, y in zip(Ls, devs, xs_np, ys):
+        single = gpu_y(dev, x_np)
+        assert np.array_equal(y.cpu().numpy(), single)
+        assert rel_l2(y.cpu().numpy(), oracle_y(L, x_np)) <= Y_TOL
+
+
+def test_group_rejects_a_bad_layer_before_launching_any():
+    import torch
+    import paper_2501_16385_amd as fbq
+    L = make_oracle_layer(spec_of(64, 256, 8, 4), config=17)
+    dev = to_device_layer(L)
+    x = torch.zeros((1, 256), dtype=torch.float16, device="cuda")
+    y_ok = torch.full((1, 64), 7.0, dtype=torch.float16, device="cuda")
+    ws = torch.zeros(fbq.workspace_bytes(dev.desc, 1), dtype=torch.uint8, device="cuda")
+    arr = fbq.make_group([dev, dev], [x, x], [y_ok, y_ok], [ws, None])     # second layer lacks its workspace
+    rc = fbq.load().fbq_linear_group(arr, 2, 1, None)
+    torch.cuda.synchronize()
+    assert rc == 1
+    assert torch.all(y_ok == 7.0)                                          # nothing ran
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_replayed_graph_follows_new_activations(bits):
+    """A captured launch replayed with new x must hand over the NEW down-projection: the words that carry
+    t are marked with the identity of the launch that wrote them, and every replay is a new launch."""
+    import torch
+    import paper_2501_16385_amd as fbq
+    spec = spec_of(640, 4096, 64, bits)
+    L = make_oracle_layer(spec, config=18)
+    dev = to_device_layer(L)
+    x = torch.zeros((1, spec.K), dtype=torch.float16, device="cuda")
+    y = torch.empty((1, spec.N), dtype=torch.float16, device="cuda")
+    ws = torch.zeros(fbq.workspace_bytes(dev.desc, 1), dtype=torch.uint8, device="cuda")
+    fbq.linear(dev, x, y=y, workspace=ws)                                  # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fbq.linear(dev, x, y=y, workspace=ws)
+    for rep in range(4):
+        x_np = fbq_synth.make_x(spec, 1, 18, 10 + rep)
+        x.copy_(torch.from_numpy(x_np.view(np.int16)).cuda().view(torch.float16))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        assert rel_l2(got, oracle_y(L, x_np)) <= Y_TOL, f"replay {rep}"
+        assert np.array_equal(got, gpu_y(dev, x_np))                       # and equals an eager launch
