@@ -33,7 +33,8 @@
 // its accumulator scaled by 2^(24-o) once per 32 codes.  The group's scale and zero are applied
 // once per lane and chunk:  s * (sum q.x - z * sum x).
 #include <hip/hip_fp16.h>
-#include <stdlib.h>
+
+
 
 #include "fbq_internal.h"
 
@@ -358,14 +359,16 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     for (int c = 0; c < CPW; ++c) {
         const uint4 *src = reinterpret_cast<const uint4 *>(xrow + kc[c]);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) xraw[c][i] = src[i];
+        for (int i = 0; i < 4; ++i) {
+            xraw[c][i] = src[i];
+        }
     }
 
     RowTile<BITS, CPW, ROWS, RI> cur, nxt;
     cur.load(p, min(tile, ntiles - 1) * ROWS, kc, jc);
 
-    // One early request for t, issued behind the weight loads and looked at only after the first tile's
-    // arithmetic: if the producers were already done by then, no time is spent waiting for it.
+    // t is requested when the first tile's arithmetic starts and looked at when it ends: by then the
+    // producers, which were dispatched first and load far less, have usually delivered.
     // A lane needs t[j], t[j+1]: one 16-byte device-scope load {value, tag, value, tag}.
     // With several K slices there is one such word pair per slice, and the lane adds the partial sums.
     const int tslices = RI > 0 ? p.tslices : 1;
@@ -389,9 +392,6 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
                 if (sl < tslices) ok = ok && (!jv[q] || (tw[q][sl].y == tag && tw[q][sl].w == tag));
         return (bool)__all(ok);
     };
-    __builtin_amdgcn_sched_barrier(0);
-    if (RI > 0 && ks == 0) request_t();
-    __builtin_amdgcn_sched_barrier(0);
 
     XFrag<BITS> xf[CPW];
 #pragma unroll
@@ -400,6 +400,11 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     // Two tile buffers used alternately (no copies between them): the loads of one tile are in flight
     // while the other is worked on.
     auto process = [&](const RowTile<BITS, CPW, ROWS, RI> &cur, int tile) __attribute__((always_inline)) {
+        if (RI > 0 && ks == 0 && !have_t) {
+            __builtin_amdgcn_sched_barrier(0);
+            request_t();
+            __builtin_amdgcn_sched_barrier(0);
+        }
         // main path: de-quantize and multiply; clamped lanes hold zero activations and add nothing
         float acc[ROWS];
 #pragma unroll
@@ -592,14 +597,17 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
     }
     const int row_sets = 4 / v.ks;
     // Blocks to share out: two per CU keeps enough bytes in flight; a token dimension multiplies the grid.
-    int per_cu = 2;
-    if (const char *e = getenv("FBQ_TUNE_BLOCKS_PER_CU")) per_cu = std::max(1, atoi(e));   // TEMP tuning hook
-    const int budget = std::max(1, per_cu * device_cu_count() / std::max(1, std::min(M, 2)));
+    const int budget = std::max(1, 2 * device_cu_count() / std::max(1, std::min(M, 2)));
     // Tiles of 4 rows when that still leaves every wave at least one tile, and registers allow; else 2.
     long tiles4 = 0;
     for (int i = 0; i < n_layers; ++i) tiles4 += ceil_div(layers[i].N, 4);
-    int rows = (v.cpw <= 2 && tiles4 >= (long)budget * row_sets) ? 4 : 2;
-    if (const char *e = getenv("FBQ_TUNE_ROWS")) rows = atoi(e) == 4 ? 4 : 2;   // TEMP tuning hook
+    const int rows = (v.cpw <= 2 && tiles4 >= (long)budget * row_sets) ? 4 : 2;
+
+    // Persistent consumer blocks have fixed tile lists, so every one of them must be resident from the
+    // start: the producers take their block slots out of the same budget.
+    int producers_total = 0;
+    for (int i = 0; i < n_layers; ++i) producers_total += ceil_div(layers[i].r, kProdCols) * t_slices_of(layers[i].K);
+    const int consumer_budget = std::max(budget / 2, budget - producers_total);
 
     GemvGroup g;
     g.n_layers = n_layers;
@@ -615,7 +623,7 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
         p.tslices = t_slices_of(a.K);
         p.producers = ceil_div(a.r, kProdCols) * p.tslices;
         const int max_blocks = ceil_div(ceil_div(a.N, rows), row_sets);
-        const int share = (int)(budget * ((double)a.N * a.K / total_work) + 0.5);
+        const int share = (int)(consumer_budget * ((double)a.N * a.K / total_work));
         p.blocks = std::max(1, std::min(max_blocks, share));
         g.block_begin[i] = next_block;
         next_block += p.producers + p.blocks;
