@@ -310,6 +310,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     constexpr int kRowSets = kWaves / KS;               // row sets per block
     constexpr int kRI = RI > 0 ? RI : 1;
     __shared__ float red[kWaves * (ROWS > kProdCols ? ROWS : kProdCols)];   // K-split sums, or the producer's wave sums
+    __shared__ float t_lds[RI > 0 ? RI * 128 : 1];                          // t as wave 0 received it
 
     const int m = blockIdx.y;
     int l = 0;
@@ -381,7 +382,8 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
         for (int q = 0; q < RI; ++q)
 #pragma unroll
             for (int sl = 0; sl < kMaxTSlices; ++sl)
-                if (sl < tslices) tw[q][sl] = __builtin_amdgcn_raw_buffer_load_b128(tbuf, (sl * p.r + jc[q]) * 8, 0, kCacheSc1);
+                if (sl < tslices)   // lanes without a tap aim past the end: the buffer unit answers zero without touching memory
+                    tw[q][sl] = __builtin_amdgcn_raw_buffer_load_b128(tbuf, jv[q] ? (sl * p.r + jc[q]) * 8 : tslices * p.r * 8, 0, kCacheSc1);
     };
     auto t_arrived = [&]() __attribute__((always_inline)) {
         bool ok = true;
@@ -400,7 +402,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     // Two tile buffers used alternately (no copies between them): the loads of one tile are in flight
     // while the other is worked on.
     auto process = [&](const RowTile<BITS, CPW, ROWS, RI> &cur, int tile) __attribute__((always_inline)) {
-        if (RI > 0 && ks == 0 && !have_t) {
+        if (RI > 0 && wave == 0 && !have_t) {           // one wave per block fetches t for all of them
             __builtin_amdgcn_sched_barrier(0);
             request_t();
             __builtin_amdgcn_sched_barrier(0);
@@ -420,9 +422,10 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
             acc[i] = a;
         }
 
-        // up-projection into the same accumulators (the K-slice-0 wave of each row set only)
-        if (RI > 0 && ks == 0) {
-            if (!have_t) {                              // first tile only: take t, waiting if it is not there yet
+        // First tile only (block-uniform): wave 0 takes t, waiting if it is not there yet, and passes it
+        // to the other waves through LDS.
+        if (RI > 0 && !have_t) {
+            if (wave == 0) {
                 bool ready = t_arrived();
                 if (!ready) {
 #pragma unroll
@@ -430,34 +433,44 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
                     for (int spin = 0; spin < kSpinLimit && !ready; ++spin) {
                         request_t();
                         ready = t_arrived();
-                        if (!ready) __builtin_amdgcn_s_sleep(2);
+                        if (!ready) __builtin_amdgcn_s_sleep(4);
                     }
                 }
 #pragma unroll
                 for (int q = 0; q < RI; ++q) {
+                    float u0 = 0.0f, u1 = 0.0f;
                     if (ready) {
-                        t0[q] = t1[q] = 0.0f;
 #pragma unroll
                         for (int sl = 0; sl < kMaxTSlices; ++sl) {
                             if (sl < tslices) {
                                 const uint32_t v0 = tw[q][sl].x, v1 = tw[q][sl].z;   // scalars first: bit_cast of a vector component reads the wrong lane
-                                t0[q] += __builtin_bit_cast(float, v0);
-                                t1[q] += __builtin_bit_cast(float, v1);
+                                u0 += __builtin_bit_cast(float, v0);
+                                u1 += __builtin_bit_cast(float, v1);
                             }
                         }
                     } else {                            // producers never showed up in time: do it here
-                        t0[q] = t1[q] = 0.0f;
                         const uint16_t *a0 = p.At + (size_t)jc[q] * p.K, *a1 = a0 + p.K;
                         for (int k = 0; k < p.K; ++k) {
                             const float xv = (float)__builtin_bit_cast(half_t, xrow[k]);
-                            t0[q] = fmaf(xv, (float)__builtin_bit_cast(half_t, a0[k]), t0[q]);
-                            t1[q] = fmaf(xv, (float)__builtin_bit_cast(half_t, a1[k]), t1[q]);
+                            u0 = fmaf(xv, (float)__builtin_bit_cast(half_t, a0[k]), u0);
+                            u1 = fmaf(xv, (float)__builtin_bit_cast(half_t, a1[k]), u1);
                         }
                     }
-                    if (!jv[q]) t0[q] = t1[q] = 0.0f;
+                    t_lds[(q * 64 + lane) * 2] = jv[q] ? u0 : 0.0f;
+                    t_lds[(q * 64 + lane) * 2 + 1] = jv[q] ? u1 : 0.0f;
                 }
-                have_t = true;
             }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < RI; ++q) {
+                t0[q] = t_lds[(q * 64 + lane) * 2];
+                t1[q] = t_lds[(q * 64 + lane) * 2 + 1];
+            }
+            have_t = true;
+        }
+
+        // up-projection into the same accumulators (the K-slice-0 wave of each row set only)
+        if (RI > 0 && ks == 0) {
 #pragma unroll
             for (int q = 0; q < RI; ++q) {
 #pragma unroll
