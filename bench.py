@@ -203,6 +203,14 @@ def main():
     ms_dom, _ = timed(schedule([dom]), args.steps, args.warmup)
     dom_gbps = dom_bytes / (ms_dom * 1e-3) / 1e9
 
+    # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (config 1 only)
+    traffic = None
+    prof = os.path.join(ROOT, "profiles", "decode_gemv_llama7b_int4_m1.md")
+    if args.config == 1 and M == 1 and os.path.exists(prof):
+        for line in open(prof):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = int(line.split(":")[1])
+
     n_layers = len(specs)
     gbps = set_bytes / (ms_staged * 1e-3) / 1e9
     floor = sum(2 * s.r * (s.K + s.N) for s in specs) / sum(nbytes_plain)
@@ -230,7 +238,7 @@ def main():
                       "merged": mode(ms_merged, ms_merged_plain, 2)},
         "roofline": {"bound": "hbm", "kernel": "fbq_gemv_kernel, the launch serving {" +
                      ",".join(specs[i].name for i in dom) + "}", "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "avg_launch_us": round(ms_dom * 1e3, 3), "bytes_per_launch": dom_bytes},
     }
     if not args.no_cpu_baseline:
