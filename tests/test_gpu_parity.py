@@ -222,3 +222,67 @@ def test_replayed_graph_follows_new_activations(bits):
         got = y.cpu().numpy()
         assert rel_l2(got, oracle_y(L, x_np)) <= Y_TOL, f"replay {rep}"
         assert np.array_equal(got, gpu_y(dev, x_np))                       # and equals an eager launch
+
+
+# ------------------------------------------------------------------ prefill (fp16 MFMA GEMM, M > 16)
+
+PREFILL_CASES = [
+    # N, K, r, M        ragged M and N tiles, several K super-steps, branch-free, wide rank
+    (300, 1408, 24, 40),
+    (512, 4096, 64, 256),
+    (1000, 2048, 0, 130),
+    (257, 128, 8, 17),
+    (768, 5120, 128, 300),
+    (320, 2304, 256, 129),
+]
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K,r,M", PREFILL_CASES)
+def test_prefill_linear_matches_oracle(bits, N, K, r, M):
+    spec = spec_of(N, K, r, bits)
+    L = make_oracle_layer(spec, config=19)
+    x = fbq_synth.make_x(spec, M, 19, 0)
+    want = oracle_y(L, x)
+    dev = to_device_layer(L)
+    got = gpu_y(dev, x)
+    assert got.shape == (M, N) and np.all(np.isfinite(got))
+    err = rel_l2(got, want)
+    assert err <= Y_TOL, f"rel L2 {err:.3e}"
+    worst = max(rel_l2(got[m], want[m]) for m in range(M))
+    assert worst <= 2 * Y_TOL, f"worst token {worst:.3e}"      # a single token's norm is a noisier yardstick
+    assert np.array_equal(gpu_y(dev, x), got)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_prefill_exact_on_integer_inputs(bits):
+    """s = 1, z = 0, no branch, x in {-1, 0, 1}, K = 128: every product and sum is a small integer."""
+    import paper_2501_16385_amd as fbq
+    rng = np.random.Generator(np.random.Philox(80 + bits))
+    N, K, M = 260, 128, 70
+    codes = rng.integers(0, 2 ** bits, (N, K), dtype=np.uint8)
+    s = np.ones((N, 1), np.float16)
+    z = np.zeros((N, 1), np.float16)
+    x = rng.integers(-1, 2, (M, K)).astype(np.float16)
+    dev = fbq.upload_layer(fbq.pack(fbq.Desc(N, K, 0, bits), codes, s, z, None, None))
+    got = gpu_y(dev, x)
+    want = orc.linear(x, orc.pack(codes, bits), s, z, None, None, bits, 128)
+    assert np.array_equal(got.astype(np.float64), want)
+
+
+def test_prefill_benchmark_shapes_sampled_rows():
+    """Config 3 (M = 1024 through the MLP shapes) at full size on the GPU; the oracle recomputes 192
+    sampled output columns per layer (all 1024 tokens), which it can do one by one."""
+    import paper_2501_16385_amd as fbq
+    specs, Ms = fbq_synth.config_layers(3)
+    rng = np.random.Generator(np.random.Philox(33))
+    for li, spec in enumerate(specs):
+        L = make_oracle_layer(spec, config=3, layer_index=li)
+        x = fbq_synth.make_x(spec, Ms[0], 3, li)
+        got = gpu_y(to_device_layer(L), x)
+        rows = np.sort(rng.choice(spec.N, 192, replace=False))
+        want = orc.linear(x, L.words[rows], L.scales[rows], L.zeros[rows], L.A, np.ascontiguousarray(L.B[:, rows]),
+                          spec.bits, spec.group)
+        err = rel_l2(got[:, rows], want)
+        assert err <= Y_TOL, f"{spec.name}: rel L2 {err:.3e}"
+        assert np.all(np.isfinite(got))
