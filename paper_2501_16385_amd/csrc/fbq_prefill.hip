@@ -132,7 +132,7 @@ __device__ __forceinline__ half8_t pack8(half2_t a, half2_t b, half2_t c, half2_
 }
 
 template <int BITS>
-__global__ __launch_bounds__(256) void fbq_gemm_kernel(const PrefillParams p)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void fbq_gemm_kernel(const PrefillParams p)
 {
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][kBM * kLdsRow];
 
