@@ -40,9 +40,9 @@ extern "C" size_t fbq_packed_bytes(const fbq_desc *d)
 
 extern "C" size_t fbq_workspace_bytes(const fbq_desc *d, int M)
 {
-    if (fbq_check_desc(d) != FBQ_OK || M < 1 || d->r == 0) return 0;
-    if (M <= kDecodeMaxM) return decode_workspace_bytes(M, d->K, d->r);
-    return prefill_workspace_bytes(M, d->r);
+    if (fbq_check_desc(d) != FBQ_OK || M < 1) return 0;
+    if (M <= kDecodeMaxM) return d->r == 0 ? 0 : decode_workspace_bytes(M, d->K, d->r);
+    return prefill_workspace_bytes(M, d->K, d->r);      // holds the re-ordered activations even when r == 0
 }
 
 // ------------------------------------------------------------------ host-side packing
@@ -145,8 +145,8 @@ static fbq_status check_layer(const fbq_desc *d, int M, const void *x, const voi
 
 static hipError_t launch_prefill(const LinearArgs &a, hipStream_t s)
 {
-    hipError_t e = hipSuccess;
-    if (a.r > 0) e = launch_down_proj_prefill(a, s);
+    hipError_t e = launch_arrange_x_prefill(a, s);
+    if (e == hipSuccess && a.r > 0) e = launch_down_proj_prefill(a, s);
     if (e == hipSuccess) e = launch_gemm_prefill(a, s);
     return e;
 }

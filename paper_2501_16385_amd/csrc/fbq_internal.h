@@ -40,6 +40,7 @@ struct LinearArgs {
 // Launchers (validated arguments only).  Each returns the hipError_t of its launches.
 hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_t stream);
 bool decode_group_compatible(const LinearArgs &a, const LinearArgs &b);
+hipError_t launch_arrange_x_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_down_proj_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_unpack(const fbq_desc &d, const uint32_t *qw, uint8_t *codes, hipStream_t stream);
@@ -49,7 +50,7 @@ hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t 
                            uint16_t *scales, uint16_t *zeros, hipStream_t stream);
 
 size_t decode_workspace_bytes(int M, int K, int r);
-size_t prefill_workspace_bytes(int M, int r);
+size_t prefill_workspace_bytes(int M, int K, int r);
 
 }  // namespace fbq
 

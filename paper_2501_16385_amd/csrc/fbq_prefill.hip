@@ -7,19 +7,25 @@
 // matrix cores and folds the up-projection into the same accumulators as 2r extra K columns, so y
 // is written once.
 //
-// Fused kernel.  Block = 4 waves side by side along N; block tile 128 (M) x 256 (N); a wave owns
-// 128 x 64 = 4 x 2 tiles of v_mfma_f32_32x32x16_f16.  K advances in super-steps of 64:
-//   * activations: a 128 x 64 fp16 tile per super-step goes global -> registers -> LDS (double
-//     buffered, rows padded to 144 B so that 128-bit reads are conflict free); every wave reads
-//     all of it (4 fragments per K step of 16);
-//   * weights never touch LDS: lane (n = lane % 32, h = lane / 32) loads the 32 codes
-//     k = 64u + 32h .. +31 of row n (INT4: one 16-byte load, INT3: one 12-byte load) and turns them
-//     into the four 8 x fp16 operands of the super-step's four K steps in registers.  The MFMA only
-//     needs both operands to agree on which k sits in which slot, so the activations are stored in
-//     LDS in the order the code extraction produces (pairs (c, c+4) for INT4, (f, f+5) for INT3).
-//   * de-quantization: mask+OR puts a code into the mantissa of 1024.0 (or 1024 + 16c, 1024 + 8c,
-//     1024 + 64c for fields at higher bit offsets); one exact packed add or fma recovers the integer
-//     code, then (q - z) * s in packed fp16: two roundings per weight, each 2^-11 relative at most.
+// Fused kernel.  Block = 4 waves side by side along N; block tile (32 TM) x 256 (TM = 4, or 2 when
+// that is needed to give every CU a block); a wave owns TM x 2 tiles of v_mfma_f32_32x32x16_f16.
+// K advances in super-steps of 128 (one quantization group):
+//   * activations: a small pre-pass rewrites x once into the order the kernel wants (see below);
+//     from there a (32 TM) x 128 fp16 tile per super-step is copied straight into LDS by
+//     global_load_lds_dwordx4 (no registers, double buffered); every wave reads all of it
+//     (TM fragments per K step of 16);
+//   * weights never touch LDS: lane (n = lane % 32, h = lane / 32) loads, for each half c of the
+//     super-step, the 32 codes k = 128u + 64c + 32h .. +31 of row n (INT4: one 16-byte load, INT3:
+//     one 12-byte load) and turns them into the 8 x fp16 operands of four K steps in registers.  The MFMA only
+//     needs both operands to agree on which k sits in which slot, so the pre-pass puts the
+//     activations in the order the code extraction produces (pairs (c, c+4) for INT4, (f, f+5) for
+//     INT3), and it XORs the position of each 16-byte chunk within its 256-byte row segment with
+//     m % 16, so that the un-padded LDS rows are read without bank conflicts.
+//   * de-quantization: one v_and_or_b32 puts a code into the mantissa of 1024.0 (or 1024 + 16c,
+//     1024 + 8c, 1024 + 64c for fields at higher bit offsets); one exact packed add or fma recovers
+//     the code minus the integer zi nearest to the zero point, d = q - zi; the weight is
+//     fma(d, s, c) with c = fp16((zi - z) s): one rounding of the weight (2^-11 relative) and one of
+//     c, which is at most 2^-12 of a quantization step.
 // The sub-branch enters as t = t_hi + t_lo (two fp16 halves, ~22 bits) against B^T rows.
 #include <hip/hip_fp16.h>
 
@@ -32,13 +38,12 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-constexpr int kBM = 128;             // block tile rows (tokens)
-constexpr int kTM = 4;               // 32-row MFMA tiles per wave along M
 constexpr int kTN = 2;               // 32-column MFMA tiles per wave along N
 constexpr int kWavesN = 4;           // waves per block, side by side along N
 constexpr int kBN = kWavesN * kTN * 32;   // 256
-constexpr int kBK = 64;              // K per super-step
-constexpr int kLdsRow = 144;         // bytes per activation row in LDS (128 + 16 padding)
+constexpr int kBK = 128;             // K per super-step: one quantization group
+constexpr int kLdsRow = 256;         // bytes per activation row in LDS: 16 chunks of 8 fp16, chunk l at l ^ (m % 16)
+constexpr int kRowPad = 128;         // the arranged copy of x has its row count rounded up to this
 
 __device__ __forceinline__ half2_t h2_of(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
 __device__ __forceinline__ half2_t h2_splat(half_t v) { return half2_t{v, v}; }
@@ -48,7 +53,7 @@ struct PrefillParams {
     const uint16_t *scales;
     const uint16_t *zeros;
     const uint16_t *Bt;    // [N][r]
-    const uint16_t *x;     // [M][K]
+    const uint16_t *xp;    // [M rounded up to kRowPad][K], arranged by fbq_arrange_x_kernel
     const uint16_t *thl;   // [M][2r]: t_hi | t_lo
     uint16_t *y;           // [M][N]
     int M, N, K, r;
@@ -75,9 +80,10 @@ struct WeightRegs {
     static constexpr int kWords = BITS == 4 ? 4 : 3;
     uint32_t w[kWords];
 
-    __device__ __forceinline__ void load(const uint32_t *row, int u, int h)
+    // block index b = k / 32 of the row
+    __device__ __forceinline__ void load(const uint32_t *row, int b)
     {
-        const uint32_t *p = row + (2 * u + h) * kWords;
+        const uint32_t *p = row + b * kWords;
         if (BITS == 4) {
             const uint4 q = *reinterpret_cast<const uint4 *>(p);
             w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
@@ -86,43 +92,69 @@ struct WeightRegs {
         }
     }
 
-    __device__ __forceinline__ void dequant(half2_t s2, half2_t nz2, half2_t (&out)[16]) const
+    // (w & mask) | 0x6400 in both halves: the masked field lands in the mantissa of 1024.0
+    static __device__ __forceinline__ half2_t field(uint32_t w, uint32_t mask, uint32_t k6400)
     {
-        const half2_t k1024 = h2_splat((half_t)-1024.0f);
-        if (BITS == 4) {
-            const half2_t r16 = h2_splat((half_t)0.0625f), k64 = h2_splat((half_t)-64.0f);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t a = w[j], b = w[j] >> 8;
-                const half2_t q0 = h2_of((a & 0x000F000Fu) | 0x64006400u) + k1024;
-                const half2_t q1 = h2_of((a & 0x00F000F0u) | 0x64006400u) * r16 + k64;
-                const half2_t q2 = h2_of((b & 0x000F000Fu) | 0x64006400u) + k1024;
-                const half2_t q3 = h2_of((b & 0x00F000F0u) | 0x64006400u) * r16 + k64;
-                out[4 * j + 0] = (q0 + nz2) * s2;
-                out[4 * j + 1] = (q1 + nz2) * s2;
-                out[4 * j + 2] = (q2 + nz2) * s2;
-                out[4 * j + 3] = (q3 + nz2) * s2;
-            }
-        } else {
-            const half2_t r8 = h2_splat((half_t)0.125f), k128 = h2_splat((half_t)-128.0f);
-            const half2_t r64 = h2_splat((half_t)0.015625f), k16 = h2_splat((half_t)-16.0f);
-#pragma unroll
-            for (int j = 0; j < 3; ++j) {
-                const uint32_t a = w[j], b = w[j] >> 9;
-                const half2_t q0 = h2_of((a & 0x00070007u) | 0x64006400u) + k1024;
-                const half2_t q1 = h2_of((a & 0x00380038u) | 0x64006400u) * r8 + k128;
-                const half2_t q2 = h2_of((a & 0x01C001C0u) | 0x64006400u) * r64 + k16;
-                const half2_t q3 = h2_of((b & 0x00070007u) | 0x64006400u) + k1024;
-                const half2_t q4 = h2_of((b & 0x00380038u) | 0x64006400u) * r8 + k128;
-                out[5 * j + 0] = (q0 + nz2) * s2;
-                out[5 * j + 1] = (q1 + nz2) * s2;
-                out[5 * j + 2] = (q2 + nz2) * s2;
-                out[5 * j + 3] = (q3 + nz2) * s2;
-                out[5 * j + 4] = (q4 + nz2) * s2;
-            }
-            const uint32_t e = ((w[0] >> 15) & 0x00010001u) | ((w[1] >> 14) & 0x00020002u) | ((w[2] >> 13) & 0x00040004u);
-            out[15] = (h2_of(e | 0x64006400u) + k1024 + nz2) * s2;
+        uint32_t v;
+        asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(v) : "v"(w), "s"(mask), "v"(k6400));
+        return h2_of(v);
+    }
+
+    // Per-group constants: with zi = the integer nearest to z, the code minus zi is an exact small
+    // integer d, and the weight is fma(d, s, c) with c = fp16((zi - z) s), |zi - z| <= 1/2.
+    struct Affine {
+        half2_t s, c;
+        half2_t k0;   // -(1024 + zi): field at bit 0
+        half2_t k1;   // INT4: -(64 + zi), field at bit 4;  INT3: -(128 + zi), field at bit 3
+        half2_t k2;   // INT3: -(16 + zi), field at bit 6
+        __device__ __forceinline__ Affine(uint32_t s_bits, uint32_t z_bits)
+        {
+            const float sf = (float)__builtin_bit_cast(half_t, (uint16_t)s_bits);
+            const float zf = (float)__builtin_bit_cast(half_t, (uint16_t)z_bits);
+            const float zi = __builtin_rintf(zf);
+            s = h2_splat((half_t)sf);
+            c = h2_splat((half_t)((zi - zf) * sf));
+            k0 = h2_splat((half_t)(-1024.0f - zi));
+            k1 = h2_splat((half_t)((BITS == 4 ? -64.0f : -128.0f) - zi));
+            k2 = h2_splat((half_t)(-16.0f - zi));
         }
+    };
+
+    // INT4: word j alone gives the four pairs of K step j.
+    __device__ __forceinline__ void dequant_word(int j, const Affine &f, uint32_t k6400, half2_t (&out)[4]) const
+    {
+        const half2_t r16 = h2_splat((half_t)0.0625f);
+        const uint32_t a = w[j], b = w[j] >> 8;
+        const half2_t d0 = field(a, 0x000F000Fu, k6400) + f.k0;
+        const half2_t d1 = field(a, 0x00F000F0u, k6400) * r16 + f.k1;
+        const half2_t d2 = field(b, 0x000F000Fu, k6400) + f.k0;
+        const half2_t d3 = field(b, 0x00F000F0u, k6400) * r16 + f.k1;
+        out[0] = d0 * f.s + f.c;
+        out[1] = d1 * f.s + f.c;
+        out[2] = d2 * f.s + f.c;
+        out[3] = d3 * f.s + f.c;
+    }
+
+    // INT3: all 32 codes of the block, 16 pairs in slot order.
+    __device__ __forceinline__ void dequant(const Affine &f, uint32_t k6400, half2_t (&out)[16]) const
+    {
+        const half2_t r8 = h2_splat((half_t)0.125f), r64 = h2_splat((half_t)0.015625f);
+#pragma unroll
+        for (int j = 0; j < 3; ++j) {
+            const uint32_t a = w[j], b = w[j] >> 9;
+            const half2_t d0 = field(a, 0x00070007u, k6400) + f.k0;
+            const half2_t d1 = field(a, 0x00380038u, k6400) * r8 + f.k1;
+            const half2_t d2 = field(a, 0x01C001C0u, k6400) * r64 + f.k2;
+            const half2_t d3 = field(b, 0x00070007u, k6400) + f.k0;
+            const half2_t d4 = field(b, 0x00380038u, k6400) * r8 + f.k1;
+            out[5 * j + 0] = d0 * f.s + f.c;
+            out[5 * j + 1] = d1 * f.s + f.c;
+            out[5 * j + 2] = d2 * f.s + f.c;
+            out[5 * j + 3] = d3 * f.s + f.c;
+            out[5 * j + 4] = d4 * f.s + f.c;
+        }
+        const uint32_t e = ((w[0] >> 15) & 0x00010001u) | ((w[1] >> 14) & 0x00020002u) | ((w[2] >> 13) & 0x00040004u);
+        out[15] = (h2_of(e | 0x64006400u) + f.k0) * f.s + f.c;
     }
 };
 
@@ -131,16 +163,18 @@ __device__ __forceinline__ half8_t pack8(half2_t a, half2_t b, half2_t c, half2_
     return half8_t{a.x, a.y, b.x, b.y, c.x, c.y, d.x, d.y};
 }
 
-template <int BITS>
+template <int BITS, int TM>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void fbq_gemm_kernel(const PrefillParams p)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][kBM * kLdsRow];
+    constexpr int kBM = 32 * TM;
+    constexpr int kCopies = kBM / 16;                   // 1 KiB wave copies (4 rows each) per wave and super-step
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2][kBM * kLdsRow];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, h = lane >> 5;
     const int m0 = blockIdx.y * kBM;
     const int nw = blockIdx.x * kBN + wave * (kTN * 32);
-    const int U = p.K / kBK;         // even: K is a multiple of 128
+    const int U = p.K / kBK;
 
     // this lane's weight rows (clamped: columns past N are computed on a valid row and never stored)
     const uint32_t *wrow[kTN];
@@ -151,103 +185,115 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         wrow[tn] = p.qw + (size_t)nrow[tn] * p.row_words;
     }
 
-    // this thread's share of the activation tile: row tid/2, 32 activations (64 B) of block tid%2
-    const int xr = tid >> 1, xb = tid & 1;
-    const uint16_t *xsrc = p.x + (size_t)min(m0 + xr, p.M - 1) * p.K + xb * 32;
-    uint4 xreg[4];
-    auto x_fetch = [&](int u) __attribute__((always_inline)) {
-        const uint4 *s = reinterpret_cast<const uint4 *>(xsrc + u * kBK);
+    // activation tile: wave w copies rows [w kBM/4, (w+1) kBM/4) of the tile, four rows (1 KiB) per
+    // instruction; lane l moves chunk l % 16 of row l / 16 and the hardware puts it at LDS base + 16 l.
+    const uint16_t *xsrc = p.xp + (size_t)(m0 + wave * (kBM / 4) + (lane >> 4)) * p.K + (lane & 15) * 8;
+    auto x_copy = [&](int u, int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) xreg[i] = s[i];
+        for (int j = 0; j < kCopies; ++j)
+            __builtin_amdgcn_global_load_lds(xsrc + (size_t)(4 * j) * p.K + u * kBK,
+                                             (__attribute__((address_space(3))) void *)&lds[buf][(wave * (kBM / 4) + 4 * j) * kLdsRow],
+                                             16, 0, 0);
     };
-    auto x_store = [&](int buf) __attribute__((always_inline)) {
-        half_t v[32];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t wds[4] = {xreg[i].x, xreg[i].y, xreg[i].z, xreg[i].w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const half2_t hh = h2_of(wds[j]);
-                v[i * 8 + j * 2] = hh.x;
-                v[i * 8 + j * 2 + 1] = hh.y;
-            }
-        }
-        uint4 *dst = reinterpret_cast<uint4 *>(&lds[buf][xr * kLdsRow + xb * 64]);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            half2_t o[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) o[j] = half2_t{v[slot_source<BITS>(i * 8 + 2 * j)], v[slot_source<BITS>(i * 8 + 2 * j + 1)]};
-            dst[i] = make_uint4(__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]),
-                                __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3]));
-        }
-    };
+    // this lane's fragment address within a tile for K step 0 of row block 0; K step s = 4 c + i is
+    // logical chunk 8 c + 4 h + i, stored at that index ^ (row % 16)
+    const uint32_t a_lane = col * kLdsRow + (((4 * h) ^ (col & 15)) << 4);
 
-    float16_t acc[kTM][kTN];
+    float16_t acc[TM][kTN];
 #pragma unroll
-    for (int tm = 0; tm < kTM; ++tm)
+    for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
         for (int tn = 0; tn < kTN; ++tn)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.0f;
 
-    half2_t s2[kTN], nz2[kTN];
-    auto load_sz = [&](int g) __attribute__((always_inline)) {
+    // weights, scale and zero of one super-step: two code blocks (k halves) per N tile
+    struct StepRegs {
+        WeightRegs<BITS> w[kTN][2];
+        uint32_t s[kTN], z[kTN];                        // fp16 bits
+    };
+    auto step_load = [&](StepRegs &sr, int u) __attribute__((always_inline)) {
 #pragma unroll
         for (int tn = 0; tn < kTN; ++tn) {
-            const half_t s = __builtin_bit_cast(half_t, p.scales[(size_t)nrow[tn] * p.G + g]);
-            const half_t z = __builtin_bit_cast(half_t, p.zeros[(size_t)nrow[tn] * p.G + g]);
-            s2[tn] = h2_splat(s);
-            nz2[tn] = h2_splat(-z);
+#pragma unroll
+            for (int c = 0; c < 2; ++c) sr.w[tn][c].load(wrow[tn], 4 * u + 2 * c + h);
+            sr.s[tn] = p.scales[(size_t)nrow[tn] * p.G + u];
+            sr.z[tn] = p.zeros[(size_t)nrow[tn] * p.G + u];
         }
     };
 
-    // one super-step: four K steps of 16 on the tile in lds[buf]
-    auto compute = [&](const WeightRegs<BITS> (&wr)[kTN], int buf) __attribute__((always_inline)) {
-        half2_t wv[kTN][16];
+    uint32_t k6400 = 0x64006400u;
+    asm volatile("" : "+v"(k6400));                     // keep the constant in a VGPR for v_and_or_b32
+
+    // one super-step: eight K steps of 16 on the tile in lds[buf].  The activation fragments of K step
+    // i + 1 are fetched from LDS before the matrix instructions of step i are issued.
+    auto compute = [&](const StepRegs &sr, int buf) __attribute__((always_inline)) {
+        const typename WeightRegs<BITS>::Affine aff[kTN] = {{sr.s[0], sr.z[0]}, {sr.s[1], sr.z[1]}};
+        auto a_frag = [&](int tm, int step) __attribute__((always_inline)) {
+            const uint32_t off = a_lane ^ (uint32_t)((8 * (step / 4) + (step % 4)) << 4);
+            return *reinterpret_cast<const half8_t *>(&lds[buf][off + tm * (32 * kLdsRow)]);
+        };
+        half8_t af[TM];
 #pragma unroll
-        for (int tn = 0; tn < kTN; ++tn) wr[tn].dequant(s2[tn], nz2[tn], wv[tn]);
+        for (int tm = 0; tm < TM; ++tm) af[tm] = a_frag(tm, 0);
+        half2_t wv3[kTN][16];                           // INT3 only
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int step = 0; step < 8; ++step) {
+            const int c = step / 4, i = step % 4;
             half8_t bf[kTN];
 #pragma unroll
-            for (int tn = 0; tn < kTN; ++tn) bf[tn] = pack8(wv[tn][4 * i], wv[tn][4 * i + 1], wv[tn][4 * i + 2], wv[tn][4 * i + 3]);
+            for (int tn = 0; tn < kTN; ++tn) {
+                if constexpr (BITS == 4) {
+                    half2_t o[4];
+                    sr.w[tn][c].dequant_word(i, aff[tn], k6400, o);
+                    bf[tn] = pack8(o[0], o[1], o[2], o[3]);
+                } else {
+                    if (i == 0) sr.w[tn][c].dequant(aff[tn], k6400, wv3[tn]);
+                    bf[tn] = pack8(wv3[tn][4 * i], wv3[tn][4 * i + 1], wv3[tn][4 * i + 2], wv3[tn][4 * i + 3]);
+                }
+            }
+            half8_t an[TM];
+            if (step < 7) {
 #pragma unroll
-            for (int tm = 0; tm < kTM; ++tm) {
-                const half8_t af = *reinterpret_cast<const half8_t *>(&lds[buf][(tm * 32 + col) * kLdsRow + h * 64 + i * 16]);
+                for (int tm = 0; tm < TM; ++tm) an[tm] = a_frag(tm, step + 1);
+            }
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < kTN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf[tn], acc[tm][tn], 0, 0, 0);
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[tm], bf[tn], acc[tm][tn], 0, 0, 0);
+            if (step < 7) {
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) af[tm] = an[tm];
             }
+        }
+        // Issue order for the scheduler: every matrix instruction is followed by its share of the
+        // de-quantization arithmetic of the next K step, and every other one by an LDS read, so that
+        // the three pipes run side by side instead of in phases.
+        constexpr int kValuPerMfma = BITS == 4 ? (TM == 4 ? 3 : 6) : (TM == 4 ? 3 : 7);
+#pragma unroll
+        for (int k = 0; k < 8 * TM * kTN; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                  // one MFMA
+            if (k % kTN == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+            __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);       // VALU
         }
     };
 
-    WeightRegs<BITS> wa[kTN], wb[kTN];
-#pragma unroll
-    for (int tn = 0; tn < kTN; ++tn) wa[tn].load(wrow[tn], 0, h);
-    load_sz(0);
-    x_fetch(0);
-    x_store(0);
+    StepRegs cur, nxt;
+    step_load(cur, 0);
+    x_copy(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wave's LDS copies have landed
     __syncthreads();
 
-    for (int u = 0; u < U; u += 2) {                    // one quantization group (128 k) per iteration
-#pragma unroll
-        for (int tn = 0; tn < kTN; ++tn) wb[tn].load(wrow[tn], u + 1, h);
-        x_fetch(u + 1);
-        compute(wa, 0);
-        x_store(1);
-        __syncthreads();
-        const bool more = u + 2 < U;                    // block-uniform
+    for (int u = 0; u < U; ++u) {
+        const bool more = u + 1 < U;                    // block-uniform
         if (more) {
-#pragma unroll
-            for (int tn = 0; tn < kTN; ++tn) wa[tn].load(wrow[tn], u + 2, h);
-            x_fetch(u + 2);
+            step_load(nxt, u + 1);
+            x_copy(u + 1, (u + 1) & 1);
         }
-        compute(wb, 1);
-        if (more) {
-            load_sz((u + 2) / 2);
-            x_store(0);
-        }
+        compute(cur, u & 1);
+        if (more) cur = nxt;
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
     }
 
@@ -261,7 +307,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
             for (int tn = 0; tn < kTN; ++tn) bf[tn] = *reinterpret_cast<const half8_t *>(p.Bt + (size_t)nrow[tn] * p.r + jb);
 #pragma unroll
-            for (int tm = 0; tm < kTM; ++tm) {
+            for (int tm = 0; tm < TM; ++tm) {
                 const int m = min(m0 + tm * 32 + col, p.M - 1);
                 const half8_t af = *reinterpret_cast<const half8_t *>(p.thl + (size_t)m * (2 * p.r) + jj);
 #pragma unroll
@@ -277,7 +323,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const int n = nw + tn * 32 + col;
         if (n >= p.N) continue;
 #pragma unroll
-        for (int tm = 0; tm < kTM; ++tm) {
+        for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = m0 + tm * 32 + 8 * (v / 4) + 4 * h + (v % 4);
@@ -287,24 +333,67 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
 }
 
+// ------------------------------------------------------------------ activation pre-pass
+
+// xp[m][128 u + 8 (l ^ (m % 16)) + e] = x[m][128 u + 32 (l / 4) + slot_source(8 (l % 4) + e)]
+// for chunk l = 0..15 of every 128-wide block u; one thread per 32 activations.
+template <int BITS>
+__global__ __launch_bounds__(256) void fbq_arrange_x_kernel(const uint16_t *__restrict__ x, uint16_t *__restrict__ xp, int M, int K)
+{
+    const int per_row = K / 32;
+    const size_t total = (size_t)M * per_row;
+    for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (size_t)gridDim.x * 256) {
+        const int m = (int)(idx / per_row), b = (int)(idx - (size_t)m * per_row);
+        const uint4 *src = reinterpret_cast<const uint4 *>(x + (size_t)m * K + b * 32);
+        half_t v[32];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint4 q = src[i];
+            const uint32_t wds[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const half2_t hh = h2_of(wds[j]);
+                v[i * 8 + j * 2] = hh.x;
+                v[i * 8 + j * 2 + 1] = hh.y;
+            }
+        }
+        uint16_t *dst = xp + (size_t)m * K + (b / 4) * 128;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            half2_t o[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                o[j] = half2_t{v[slot_source<BITS>(i * 8 + 2 * j)], v[slot_source<BITS>(i * 8 + 2 * j + 1)]};
+            const int l = 4 * (b % 4) + i;
+            *reinterpret_cast<uint4 *>(dst + 8 * (l ^ (m & 15))) =
+                make_uint4(__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]),
+                           __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3]));
+        }
+    }
+}
+
 // ------------------------------------------------------------------ down-projection (prefill)
 
-// t[m][j] = sum_k x[m][k] * At[j][k] for one 32-row tile of tokens and all r columns; the block's
-// four waves take a quarter of K each and add their tiles up through LDS in wave order.  Written as
-// t_hi = fp16(t), t_lo = fp16(t - t_hi).  RT = 32-column tiles (r <= 32 * RT).
+constexpr int kDownSlices = 8;       // K slices of the prefill down-projection (one block each)
+
+// Stage 1: partial[s][m][j] = sum over K slice s of x[m][k] * At[j][k], for one 32-row tile of tokens
+// and all r columns; the block's four waves take a quarter of the slice each and add their tiles up
+// through LDS in wave order.  RT = 32-column tiles (r <= 32 * RT).
 template <int RT>
 __global__ __launch_bounds__(256) void fbq_down_proj_prefill_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ At,
-                                                                    uint16_t *__restrict__ thl, int M, int K, int r)
+                                                                    float *__restrict__ partial, int M, int K, int r, int kslice)
 {
     extern __shared__ float sum[];                      // [32][32 * RT]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, h = lane >> 5;
     const int m0 = blockIdx.x * 32;
-    const int kq = K / 4;                               // K is a multiple of 128
-    const uint16_t *xrow = x + (size_t)min(m0 + col, M - 1) * K + wave * kq + h * 8;
+    const int kq = kslice / 4;                          // a multiple of 16
+    const int kbeg = blockIdx.y * kslice + wave * kq;
+    const int kend = min(K, kbeg + kq);
+    const uint16_t *xrow = x + (size_t)min(m0 + col, M - 1) * K + h * 8;
     const uint16_t *arow[RT];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) arow[rt] = At + (size_t)min(rt * 32 + col, r - 1) * K + wave * kq + h * 8;
+    for (int rt = 0; rt < RT; ++rt) arow[rt] = At + (size_t)min(rt * 32 + col, r - 1) * K + h * 8;
 
     float16_t acc[RT];
 #pragma unroll
@@ -312,8 +401,7 @@ __global__ __launch_bounds__(256) void fbq_down_proj_prefill_kernel(const uint16
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[rt][v] = 0.0f;
 
-#pragma unroll 4
-    for (int kk = 0; kk < kq; kk += 16) {
+    for (int kk = kbeg; kk < kend; kk += 16) {
         const half8_t af = *reinterpret_cast<const half8_t *>(xrow + kk);
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
@@ -336,43 +424,100 @@ __global__ __launch_bounds__(256) void fbq_down_proj_prefill_kernel(const uint16
         }
         __syncthreads();
     }
+    float *out = partial + (size_t)blockIdx.y * M * r;
     for (int idx = tid; idx < 32 * r; idx += 256) {
         const int i = idx / r, j = idx - i * r;
-        if (m0 + i < M) {
-            const float t = sum[i * ld + j];
-            const half_t hi = (half_t)t;
-            const half_t lo = (half_t)(t - (float)hi);
-            thl[(size_t)(m0 + i) * (2 * r) + j] = __builtin_bit_cast(uint16_t, hi);
-            thl[(size_t)(m0 + i) * (2 * r) + r + j] = __builtin_bit_cast(uint16_t, lo);
-        }
+        if (m0 + i < M) out[(size_t)(m0 + i) * r + j] = sum[i * ld + j];
     }
 }
 
-size_t prefill_workspace_bytes(int M, int r) { return (size_t)M * 2 * r * sizeof(uint16_t); }
+// Stage 2: t = sum of the slices in slice order, written as t_hi = fp16(t), t_lo = fp16(t - t_hi).
+__global__ __launch_bounds__(256) void fbq_down_proj_finish_kernel(const float *__restrict__ partial, uint16_t *__restrict__ thl,
+                                                                   int M, int r, int slices)
+{
+    const size_t total = (size_t)M * r;
+    for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (size_t)gridDim.x * 256) {
+        float t = 0.0f;
+        for (int s = 0; s < slices; ++s) t += partial[(size_t)s * total + idx];
+        const size_t m = idx / r, j = idx - m * r;
+        const half_t hi = (half_t)t;
+        const half_t lo = (half_t)(t - (float)hi);
+        thl[m * (2 * r) + j] = __builtin_bit_cast(uint16_t, hi);
+        thl[m * (2 * r) + r + j] = __builtin_bit_cast(uint16_t, lo);
+    }
+}
+
+// workspace: the arranged copy of x ([M rounded up to kRowPad][K] fp16; rows past M are never
+// written and only feed output rows that are never stored), then [M][2r] fp16 (t_hi | t_lo), then
+// kDownSlices x [M][r] fp32 partial sums
+static size_t xp_bytes(int M, int K) { return (size_t)ceil_div(M, kRowPad) * kRowPad * K * sizeof(uint16_t); }
+static size_t thl_bytes(int M, int r) { return ((size_t)M * 2 * r * sizeof(uint16_t) + 255) & ~(size_t)255; }
+
+size_t prefill_workspace_bytes(int M, int K, int r)
+{
+    return xp_bytes(M, K) + thl_bytes(M, r) + (size_t)kDownSlices * M * r * sizeof(float);
+}
+
+hipError_t launch_arrange_x_prefill(const LinearArgs &a, hipStream_t stream)
+{
+    const size_t items = (size_t)a.M * (a.K / 32);
+    const int blocks = (int)std::min<size_t>(4096, (items + 255) / 256);
+    if (a.bits == 4) hipLaunchKernelGGL(fbq_arrange_x_kernel<4>, dim3(blocks), dim3(256), 0, stream, a.x, (uint16_t *)a.workspace, a.M, a.K);
+    else hipLaunchKernelGGL(fbq_arrange_x_kernel<3>, dim3(blocks), dim3(256), 0, stream, a.x, (uint16_t *)a.workspace, a.M, a.K);
+    return hipGetLastError();
+}
 
 hipError_t launch_down_proj_prefill(const LinearArgs &a, hipStream_t stream)
 {
-    const dim3 grid(ceil_div(a.M, 32));
+    // K slices: multiples of 64 so that each wave's quarter is a whole number of 16-wide K steps
+    const int kslice = ceil_div(ceil_div(a.K, kDownSlices), 64) * 64;
+    const int slices = ceil_div(a.K, kslice);
+    const dim3 grid(ceil_div(a.M, 32), slices);
     const int rt = ceil_div(a.r, 32);
-    uint16_t *thl = (uint16_t *)a.workspace;
-    if (rt <= 1) hipLaunchKernelGGL(fbq_down_proj_prefill_kernel<1>, grid, dim3(256), 32 * 32 * sizeof(float), stream, a.x, a.At, thl, a.M, a.K, a.r);
-    else if (rt <= 2) hipLaunchKernelGGL(fbq_down_proj_prefill_kernel<2>, grid, dim3(256), 32 * 64 * sizeof(float), stream, a.x, a.At, thl, a.M, a.K, a.r);
-    else if (rt <= 4) hipLaunchKernelGGL(fbq_down_proj_prefill_kernel<4>, grid, dim3(256), 32 * 128 * sizeof(float), stream, a.x, a.At, thl, a.M, a.K, a.r);
-    else hipLaunchKernelGGL(fbq_down_proj_prefill_kernel<8>, grid, dim3(256), 32 * 256 * sizeof(float), stream, a.x, a.At, thl, a.M, a.K, a.r);
+    uint16_t *thl = (uint16_t *)((char *)a.workspace + xp_bytes(a.M, a.K));
+    float *partial = (float *)((char *)thl + thl_bytes(a.M, a.r));
+    if (rt <= 1) hipLaunchKernelGGL(fbq_down_proj_prefill_kernel<1>, grid, dim3(256), 32 * 32 * sizeof(float), stream, a.x, a.At, partial, a.M, a.K, a.r, kslice);
+    else if (rt <= 2) hipLaunchKernelGGL(fbq_down_proj_prefill_kernel<2>, grid, dim3(256), 32 * 64 * sizeof(float), stream, a.x, a.At, partial, a.M, a.K, a.r, kslice);
+    else if (rt <= 4) hipLaunchKernelGGL(fbq_down_proj_prefill_kernel<4>, grid, dim3(256), 32 * 128 * sizeof(float), stream, a.x, a.At, partial, a.M, a.K, a.r, kslice);
+    else hipLaunchKernelGGL(fbq_down_proj_prefill_kernel<8>, grid, dim3(256), 32 * 256 * sizeof(float), stream, a.x, a.At, partial, a.M, a.K, a.r, kslice);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int blocks = std::min(1024, ceil_div(a.M * a.r, 256));
+    hipLaunchKernelGGL(fbq_down_proj_finish_kernel, dim3(blocks), dim3(256), 0, stream, partial, thl, a.M, a.r, slices);
     return hipGetLastError();
+}
+
+static int prefill_cu_count()
+{
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        return n;
+    }();
+    return cus;
 }
 
 hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream)
 {
     PrefillParams p;
-    p.qw = a.qw; p.scales = a.scales; p.zeros = a.zeros; p.Bt = a.Bt; p.x = a.x; p.y = a.y;
-    p.thl = (const uint16_t *)a.workspace;
+    p.qw = a.qw; p.scales = a.scales; p.zeros = a.zeros; p.Bt = a.Bt; p.y = a.y;
+    p.xp = (const uint16_t *)a.workspace;
+    p.thl = (const uint16_t *)((const char *)a.workspace + xp_bytes(a.M, a.K));
     p.M = a.M; p.N = a.N; p.K = a.K; p.r = a.r;
     p.row_words = (int)row_words(a.K, a.bits);
     p.G = a.K / kGroup;
-    const dim3 grid(ceil_div(a.N, kBN), ceil_div(a.M, kBM));
-    if (a.bits == 4) hipLaunchKernelGGL(fbq_gemm_kernel<4>, grid, dim3(256), 0, stream, p);
-    else hipLaunchKernelGGL(fbq_gemm_kernel<3>, grid, dim3(256), 0, stream, p);
+    // 128-row tiles amortise the de-quantization best; 64-row tiles when 128 would leave CUs without a block
+    const int nb = ceil_div(a.N, kBN);
+    const bool tall = (long)nb * ceil_div(a.M, 128) >= prefill_cu_count() || a.M <= 64;
+    const dim3 grid(nb, ceil_div(a.M, tall ? 128 : 64));
+    if (a.bits == 4) {
+        if (tall) hipLaunchKernelGGL((fbq_gemm_kernel<4, 4>), grid, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((fbq_gemm_kernel<4, 2>), grid, dim3(256), 0, stream, p);
+    } else {
+        if (tall) hipLaunchKernelGGL((fbq_gemm_kernel<3, 4>), grid, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((fbq_gemm_kernel<3, 2>), grid, dim3(256), 0, stream, p);
+    }
     return hipGetLastError();
 }
 
