@@ -43,6 +43,7 @@ constexpr int kWavesN = 4;           // waves per block, side by side along N
 constexpr int kBN = kWavesN * kTN * 32;   // 256
 constexpr int kBK = 128;             // K per super-step: one quantization group
 constexpr int kLdsRow = 256;         // bytes per activation row in LDS: 16 chunks of 8 fp16, chunk l at l ^ (m % 16)
+constexpr int kXcds = 8;             // accelerator dies, each with its own L2
 constexpr int kRowPad = 128;         // the arranged copy of x has its row count rounded up to this
 
 __device__ __forceinline__ half2_t h2_of(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
@@ -58,6 +59,7 @@ struct PrefillParams {
     uint16_t *y;           // [M][N]
     int M, N, K, r;
     int row_words, G;
+    int row_blocks;        // ceil(M / block tile rows)
 };
 
 // Order in which the 32 activations of a lane's code block must sit so that slot s of K step i
@@ -172,8 +174,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, h = lane >> 5;
-    const int m0 = blockIdx.y * kBM;
-    const int nw = blockIdx.x * kBN + wave * (kTN * 32);
+    // Workgroups go to the eight XCDs round-robin by linear id, and each XCD has its own L2.  Give
+    // every XCD its own column blocks (all row blocks of one column block run on the same XCD, one
+    // after the other in id order), so that a weight tile is fetched into one L2 only.
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int bm = slot % p.row_blocks, bn = (slot / p.row_blocks) * kXcds + xcd;
+    if (bn * kBN >= p.N) return;                        // block-uniform
+    const int m0 = bm * kBM;
+    const int nw = bn * kBN + wave * (kTN * 32);
     const int U = p.K / kBK;
 
     // this lane's weight rows (clamped: columns past N are computed on a valid row and never stored)
@@ -266,16 +274,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm) af[tm] = an[tm];
             }
-        }
-        // Issue order for the scheduler: every matrix instruction is followed by its share of the
-        // de-quantization arithmetic of the next K step, and every other one by an LDS read, so that
-        // the three pipes run side by side instead of in phases.
-        constexpr int kValuPerMfma = BITS == 4 ? (TM == 4 ? 3 : 6) : (TM == 4 ? 3 : 7);
-#pragma unroll
-        for (int k = 0; k < 8 * TM * kTN; ++k) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                  // one MFMA
-            if (k % kTN == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-            __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMfma, 0);       // VALU
         }
     };
 
@@ -510,7 +508,8 @@ hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream)
     // 128-row tiles amortise the de-quantization best; 64-row tiles when 128 would leave CUs without a block
     const int nb = ceil_div(a.N, kBN);
     const bool tall = (long)nb * ceil_div(a.M, 128) >= prefill_cu_count() || a.M <= 64;
-    const dim3 grid(nb, ceil_div(a.M, tall ? 128 : 64));
+    p.row_blocks = ceil_div(a.M, tall ? 128 : 64);
+    const dim3 grid(kXcds * ceil_div(nb, kXcds) * p.row_blocks);
     if (a.bits == 4) {
         if (tall) hipLaunchKernelGGL((fbq_gemm_kernel<4, 4>), grid, dim3(256), 0, stream, p);
         else hipLaunchKernelGGL((fbq_gemm_kernel<4, 2>), grid, dim3(256), 0, stream, p);
