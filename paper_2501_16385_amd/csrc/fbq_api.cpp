@@ -41,7 +41,8 @@ extern "C" size_t fbq_packed_bytes(const fbq_desc *d)
 extern "C" size_t fbq_workspace_bytes(const fbq_desc *d, int M)
 {
     if (fbq_check_desc(d) != FBQ_OK || M < 1) return 0;
-    if (M <= kDecodeMaxM) return d->r == 0 ? 0 : decode_workspace_bytes(M, d->K, d->r);
+    if (M <= kPerTokenMaxM) return d->r == 0 ? 0 : decode_workspace_bytes(M, d->K, d->r);
+    if (M <= kDecodeMaxM) return d->r == 0 ? 0 : small_m_workspace_bytes(d->r);
     return prefill_workspace_bytes(M, d->K, d->r);      // holds the re-ordered activations even when r == 0
 }
 
@@ -151,6 +152,16 @@ static hipError_t launch_prefill(const LinearArgs &a, hipStream_t s)
     return e;
 }
 
+// Up to four tokens: streaming GEMV, one pass per token, with the down-projection inside the launch.
+// 5..16 tokens: one pass over the packed words against a matrix-core tile of tokens.  More: the
+// prefill GEMM.
+static hipError_t launch_one(const LinearArgs &a, hipStream_t s)
+{
+    if (a.M <= kPerTokenMaxM) return launch_gemv_decode(&a, 1, s);
+    if (a.M <= kDecodeMaxM) return launch_gemv_small_m(a, s);
+    return launch_prefill(a, s);
+}
+
 extern "C" fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
                                  const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
                                  size_t workspace_bytes, fbq_stream stream)
@@ -159,7 +170,7 @@ extern "C" fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const 
     const fbq_status st = check_layer(d, M, x, qweight, scales, zeros, At, Bt, y, workspace, workspace_bytes, &a);
     if (st != FBQ_OK) return st;
     hipStream_t s = (hipStream_t)stream;
-    return hip_status(M <= kDecodeMaxM ? launch_gemv_decode(&a, 1, s) : launch_prefill(a, s));
+    return hip_status(launch_one(a, s));
 }
 
 extern "C" fbq_status fbq_linear_group(const fbq_layer_call *calls, int n, int M, fbq_stream stream)
@@ -176,8 +187,8 @@ extern "C" fbq_status fbq_linear_group(const fbq_layer_call *calls, int n, int M
     }
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
-    if (M > kDecodeMaxM) {
-        for (int i = 0; i < n && e == hipSuccess; ++i) e = launch_prefill(args[i], s);
+    if (M > kPerTokenMaxM) {
+        for (int i = 0; i < n && e == hipSuccess; ++i) e = launch_one(args[i], s);
         return hip_status(e);
     }
     bool done[kMaxCalls] = {false};

@@ -17,6 +17,7 @@ constexpr int kChunk = 64 * kLaneCodes;   // codes one wave-wide load covers (20
 constexpr int kMaxRank = 256;
 constexpr int kMaxK = 16 * kChunk;      // 32768: the decode kernel keeps a wave's activations in registers
 constexpr int kDecodeMaxM = 16;
+constexpr int kPerTokenMaxM = 4;     // up to here the GEMV streams the weights once per token; above, the matrix-core tile wins
 constexpr int kMaxTSlices = 4;       // K slices of the decode down-projection: kMaxK / (4 passes * 2048)
 constexpr int kMaxGroup = 8;         // layers one grouped decode launch can serve
 
@@ -33,13 +34,14 @@ struct LinearArgs {
     const uint16_t *Bt;
     const uint16_t *x;
     uint16_t *y;
-    void *workspace;  // see decode_workspace_bytes / prefill_workspace_bytes
+    void *workspace;  // see decode_workspace_bytes / small_m_workspace_bytes / prefill_workspace_bytes
     int M, N, K, r, bits;
 };
 
 // Launchers (validated arguments only).  Each returns the hipError_t of its launches.
 hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_t stream);
 bool decode_group_compatible(const LinearArgs &a, const LinearArgs &b);
+hipError_t launch_gemv_small_m(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_arrange_x_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_down_proj_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream);
@@ -50,6 +52,7 @@ hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t 
                            uint16_t *scales, uint16_t *zeros, hipStream_t stream);
 
 size_t decode_workspace_bytes(int M, int K, int r);
+size_t small_m_workspace_bytes(int r);
 size_t prefill_workspace_bytes(int M, int K, int r);
 
 }  // namespace fbq
