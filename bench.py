@@ -184,12 +184,42 @@ def main():
         wall = time.perf_counter() - t0
         return e0.elapsed_time(e1) / n, wall / n * 1e3      # ms per step: device events, host wall clock
 
+    def timed_graphs(sched, n, warm, steps_per_graph):
+        """The same launches replayed from HIP graphs of steps_per_graph consecutive steps each."""
+        graphs = []
+        side = torch.cuda.Stream()
+        gsp = ctypes.c_void_p(side.cuda_stream)
+        for g0 in range(0, len(sched), steps_per_graph):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for calls in sched[g0:g0 + steps_per_graph]:
+                    for call in calls:
+                        rc = call.fn(call.arr, call.args[1], call.args[2], gsp)
+                        if rc:
+                            raise RuntimeError(f"fbq_linear_group failed with status {rc} during capture")
+            graphs.append((g, len(sched[g0:g0 + steps_per_graph])))
+        for i in range(max(1, warm // steps_per_graph)):
+            graphs[i % len(graphs)][0].replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        done, i = 0, 0
+        while done < n:
+            g, k = graphs[i % len(graphs)]
+            g.replay()
+            done += k
+            i += 1
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / done, done
+
     staged = stages_of(specs)
     per_layer = [[i] for i in range(len(specs))]
     merged = [list(range(len(specs)))]                       # the library splits it by kernel variant itself
 
     ms_staged, wall_staged = timed(schedule(staged), args.steps, args.warmup)
     ms_staged_plain, _ = timed(schedule(staged, plain=True), args.steps, args.warmup)
+    ms_graph_all, graph_steps = timed_graphs(schedule(staged), args.steps, args.warmup, copies)
     ms_layer, _ = timed(schedule(per_layer), args.steps, args.warmup)
     ms_layer_plain, _ = timed(schedule(per_layer, plain=True), args.steps, args.warmup)
     ms_merged, _ = timed(schedule(merged), args.steps, args.warmup)
@@ -234,6 +264,8 @@ def main():
         "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBS, 4),
         "wall_ms_per_step": round(wall_staged, 6),
         "schedules": {"staged": mode(ms_staged, ms_staged_plain, len(staged)),
+                      "staged_graph_of_all_copies": {"us_per_step": round(ms_graph_all * 1e3, 3), "steps_timed": graph_steps,
+                                                     "GBps": round(set_bytes / ms_graph_all / 1e6, 1)},
                       "per_layer": mode(ms_layer, ms_layer_plain, len(per_layer)),
                       "merged": mode(ms_merged, ms_merged_plain, 2)},
         "roofline": {"bound": "hbm", "kernel": "fbq_gemv_kernel, the launch serving {" +

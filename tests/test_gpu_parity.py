@@ -52,6 +52,10 @@ DECODE_CASES = [
     (1000, 4096, 0, 1),
     (64, 128, 8, 16),
     (1, 128, 0, 1),
+    # wide enough for the 64-column blocks of the matrix-core GEMV with K split over blocks
+    (1290, 32768, 64, 16),
+    (3500, 12288, 32, 7),
+    (3500, 12288, 0, 9),
 ]
 
 
