@@ -75,10 +75,11 @@ fbq_status fbq_check_desc(const fbq_desc *d);
 /* Bytes of the packed code buffer, N * K * bits / 8.  0 for an invalid descriptor. */
 size_t fbq_packed_bytes(const fbq_desc *d);
 
-/* Bytes of device scratch fbq_linear needs for M tokens.  M <= 16: the down-projection t = x.A on
- * its way from the blocks that compute it to the blocks that use it (0 when r == 0).  M > 16: the
- * activations re-ordered for the matrix cores (M rounded up to 128 rows of K fp16), t as two fp16
- * halves and its partial sums; not 0 even when r == 0.  0 for an invalid descriptor or M < 1. */
+/* Bytes of device scratch fbq_linear needs for M tokens.  M <= 4: the down-projection t = x.A on its
+ * way from the blocks that compute it to the blocks that use it, as tagged 8-byte words.  5 <= M <= 16:
+ * fp32 partial sums of t.  Both are 0 when r == 0.  M > 16: the activations re-ordered for the matrix
+ * cores (M rounded up to 128 rows of K fp16), t as two fp16 halves and its partial sums; not 0 even
+ * when r == 0.  0 for an invalid descriptor or M < 1. */
 size_t fbq_workspace_bytes(const fbq_desc *d, int M);
 
 /*
@@ -100,10 +101,11 @@ fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *sca
 /*
  * fbq_linear - the hot path (Sec. 4.3).  y[m,n] = sum_k x[m,k] * s[n,k/g] * (q[n,k] - z[n,k/g])
  *                                               + sum_j (sum_k x[m,k] * At[j,k]) * Bt[n,j]
- * in fp32 accumulation, rounded once to fp16.  M <= 16 runs the decode GEMV in ONE launch (packed
- * words streamed once, unpacked in registers; the down-projection runs in a few producer blocks
- * of the same launch); M > 16 runs the fp16 MFMA GEMM after a pass that re-orders x and a separate
- * down-projection.
+ * in fp32 accumulation, rounded once to fp16.  M <= 4 runs the decode GEMV in ONE launch per token
+ * count (packed words streamed once per token, unpacked in registers; the down-projection runs in a
+ * few producer blocks of the same launch).  5 <= M <= 16 streams the packed words once for all
+ * tokens against a 16-token matrix-core tile, after a small down-projection launch.  M > 16 runs
+ * the fp16 MFMA GEMM after a pass that re-orders x and a separate down-projection.
  *   x         device [M, K] fp16             qweight, scales, zeros, At, Bt: device, layout above
  *   y         device [M, N] fp16, overwritten
  *   workspace device, >= fbq_workspace_bytes(d, M) bytes (may be NULL when that is 0).  Zero-fill it
