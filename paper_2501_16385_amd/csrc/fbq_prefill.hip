@@ -241,40 +241,57 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             const uint32_t off = a_lane ^ (uint32_t)((8 * (step / 4) + (step % 4)) << 4);
             return *reinterpret_cast<const half8_t *>(&lds[buf][off + tm * (32 * kLdsRow)]);
         };
-        half8_t af[TM];
+        half2_t wv3[kTN][16];                           // INT3 only
+        auto b_frag = [&](int tn, int step) __attribute__((always_inline)) {
+            const int c = step / 4, i = step % 4;
+            if constexpr (BITS == 4) {
+                half2_t o[4];
+                sr.w[tn][c].dequant_word(i, aff[tn], k6400, o);
+                return pack8(o[0], o[1], o[2], o[3]);
+            } else {
+                if (i == 0) sr.w[tn][c].dequant(aff[tn], k6400, wv3[tn]);
+                return pack8(wv3[tn][4 * i], wv3[tn][4 * i + 1], wv3[tn][4 * i + 2], wv3[tn][4 * i + 3]);
+            }
+        };
+        // Order of issue, fixed with scheduling fences and groups.  A K step is two phases of TM matrix
+        // instructions, one per column tile.  While the first phase's instructions run, the second
+        // tile's weights of this step are de-quantized; during the second phase the first tile's
+        // weights of the NEXT step are, and each activation fragment is re-read from LDS for the
+        // next step right after its last use.  Vector, LDS and matrix instructions alternate, so
+        // the matrix pipe stays fed whatever the other wave of the SIMD is doing, and no operand
+        // needs a second register set.
+        static_assert(kTN == 2, "the issue order below is written for two column tiles per wave");
+        constexpr int kValu = BITS == 4 ? (TM == 4 ? 4 : 7) : (TM == 4 ? 5 : 9);   // vector ops per matrix instruction
+        half8_t af[TM], b0, b1;
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) af[tm] = a_frag(tm, 0);
-        half2_t wv3[kTN][16];                           // INT3 only
+        b0 = b_frag(0, 0);
 #pragma unroll
         for (int step = 0; step < 8; ++step) {
-            const int c = step / 4, i = step % 4;
-            half8_t bf[kTN];
+            __builtin_amdgcn_sched_barrier(0);
+            b1 = b_frag(1, step);
 #pragma unroll
-            for (int tn = 0; tn < kTN; ++tn) {
-                if constexpr (BITS == 4) {
-                    half2_t o[4];
-                    sr.w[tn][c].dequant_word(i, aff[tn], k6400, o);
-                    bf[tn] = pack8(o[0], o[1], o[2], o[3]);
-                } else {
-                    if (i == 0) sr.w[tn][c].dequant(aff[tn], k6400, wv3[tn]);
-                    bf[tn] = pack8(wv3[tn][4 * i], wv3[tn][4 * i + 1], wv3[tn][4 * i + 2], wv3[tn][4 * i + 3]);
-                }
+            for (int tm = 0; tm < TM; ++tm) acc[tm][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[tm], b0, acc[tm][0], 0, 0, 0);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, kValu, 0);
             }
-            half8_t an[TM];
-            if (step < 7) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (step < 7) b0 = b_frag(0, step + 1);
 #pragma unroll
-                for (int tm = 0; tm < TM; ++tm) an[tm] = a_frag(tm, step + 1);
+            for (int tm = 0; tm < TM; ++tm) {
+                acc[tm][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[tm], b1, acc[tm][1], 0, 0, 0);
+                if (step < 7) af[tm] = a_frag(tm, step + 1);
             }
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < kTN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[tm], bf[tn], acc[tm][tn], 0, 0, 0);
-            if (step < 7) {
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) af[tm] = an[tm];
+            for (int tm = 0; tm < TM; ++tm) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, kValu, 0);
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     StepRegs cur, nxt;
