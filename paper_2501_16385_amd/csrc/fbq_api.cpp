@@ -42,7 +42,7 @@ extern "C" size_t fbq_workspace_bytes(const fbq_desc *d, int M)
 {
     if (fbq_check_desc(d) != FBQ_OK || M < 1) return 0;
     if (M <= kPerTokenMaxM) return d->r == 0 ? 0 : decode_workspace_bytes(M, d->K, d->r);
-    if (M <= kDecodeMaxM) return d->r == 0 ? 0 : small_m_workspace_bytes(d->r);
+    if (M <= kDecodeMaxM) return small_m_workspace_bytes(d->K, d->r);   // holds the activations in operand order even when r == 0
     return prefill_workspace_bytes(M, d->K, d->r);      // holds the re-ordered activations even when r == 0
 }
 

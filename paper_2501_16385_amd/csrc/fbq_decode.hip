@@ -33,15 +33,30 @@
 // its accumulator scaled by 2^(24-o) once per 32 codes.  The group's scale and zero are applied
 // once per lane and chunk:  s * (sum q.x - z * sum x).
 #include <hip/hip_fp16.h>
+#include <stdlib.h>
 
 
 
 #include "fbq_internal.h"
 
+// Timing builds only (never defined for the library): per-wave wall-clock stamps (100 MHz) into a buffer the
+// timing harness owns.
+#ifndef FBQ_EXP
+#define FBQ_EXP 0
+#endif
+#ifdef FBQ_TRACE
+extern __device__ long long *fbq_trace_buf;
+#define FBQ_STAMP(slot) do { if ((threadIdx.x & 63) == 0) fbq_trace_buf[((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 8 + (slot)] = wall_clock64(); } while (0)
+#else
+#define FBQ_STAMP(slot) do { } while (0)
+#endif
+
 namespace fbq {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half_t;
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t uint3_t __attribute__((ext_vector_type(3)));
 
 __device__ __forceinline__ half2_t as_h2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
 __device__ __forceinline__ float dot2(uint32_t codes, half2_t xp, float acc)
@@ -150,9 +165,9 @@ struct CodeWords;
 template <>
 struct CodeWords<4> {
     uint32_t w[4];
-    __device__ __forceinline__ void load(const uint32_t *p)
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t buf, int lane_off, int row_off)
     {
-        uint4 q = *reinterpret_cast<const uint4 *>(p);
+        const uint4_t q = __builtin_amdgcn_raw_buffer_load_b128(buf, lane_off, row_off, 0);
         w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
     }
     __device__ __forceinline__ float dot(const half2_t (&p)[16]) const { return dot_codes_int4(w, p); }
@@ -160,9 +175,10 @@ struct CodeWords<4> {
 template <>
 struct CodeWords<3> {
     uint32_t w[3];
-    __device__ __forceinline__ void load(const uint32_t *p)
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t buf, int lane_off, int row_off)
     {
-        w[0] = p[0]; w[1] = p[1]; w[2] = p[2];
+        const uint3_t q = __builtin_amdgcn_raw_buffer_load_b96(buf, lane_off, row_off, 0);
+        w[0] = q.x; w[1] = q.y; w[2] = q.z;
     }
     __device__ __forceinline__ float dot(const half2_t (&p)[16]) const { return dot_codes_int3(w, p); }
 };
@@ -212,8 +228,6 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t dev_buffer(const void *p, int 
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
 }
-
-typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
 
 // Producer block b of token m: partial sums of t[j] for kProdCols columns over one K slice of at most
 // kProdPasses * 2048 activations, lanes along K like the main kernel; every load is issued up front.
@@ -270,36 +284,62 @@ __device__ void produce_t(const LayerParams &p, int m, int b, uint32_t tag, floa
     }
 }
 
-// Everything one wave loads for one tile of ROWS rows.
-template <int BITS, int CPW, int ROWS, int RI>
+// Everything one wave loads for one tile of ROWS rows.  All loads are buffer loads: the row base is a
+// scalar offset (the rows of a tile are the same for every lane), the lane's position inside a row is
+// a byte offset computed once, and a tile that is not wanted is "loaded" through descriptors of size
+// zero, which answer zero without touching memory - so every wave issues the same number of loads
+// on every trip and the compiler can count exactly how many loads are younger than the data it
+// waits for.
+struct TileBuffers {
+    __amdgpu_buffer_rsrc_t qw, scales, zeros, bt;
+};
+
+__device__ __forceinline__ TileBuffers tile_buffers(const LayerParams &p, bool enabled)
+{
+    TileBuffers b;
+    const int on = enabled ? 1 : 0;   // sizes fit 32 bits: K <= 32768 and the rows of one layer stay far below 2^31 bytes
+    b.qw = dev_buffer(p.qw, on * (int)((size_t)p.N * p.row_words * 4));
+    b.scales = dev_buffer(p.scales, on * p.N * p.G * 2);
+    b.zeros = dev_buffer(p.zeros, on * p.N * p.G * 2);
+    b.bt = dev_buffer(p.Bt, on * p.N * p.r * 2);
+    return b;
+}
+
+template <int BITS, int CPW, int ROWS>
 struct RowTile {
-    static constexpr int kRI = RI > 0 ? RI : 1;
     static constexpr int kLaneWords = BITS == 4 ? 4 : 3;
     CodeWords<BITS> cw[ROWS][CPW];
     uint32_t sc[ROWS][CPW], zp[ROWS][CPW];   // fp16 bits, one per register: packing two would stall the load stream
-    uint32_t bt[ROWS][kRI];
 
-    // Unconditional loads: rows past the end re-read the last row (never stored), lanes past K re-read
-    // chunk 0 (their activations are zero), taps past r re-read tap 0 (their t is zero).
-    __device__ __forceinline__ void load(const LayerParams &p, int n0, const int (&kc)[CPW], const int (&jc)[kRI])
+    // Rows past the end re-read the last row (never stored); lanes past K re-read chunk 0 (their
+    // activations are zero).  qoff: byte offset of the lane's words inside a packed row, goff: of its
+    // group's scale / zero inside a row of scales.
+    __device__ __forceinline__ void load(const LayerParams &p, const TileBuffers &b, int n0, const int (&qoff)[CPW], const int (&goff)[CPW])
     {
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
             const int n = min(n0 + i, p.N - 1);
-            const uint32_t *qrow = p.qw + (size_t)n * p.row_words;
 #pragma unroll
             for (int c = 0; c < CPW; ++c) {
-                cw[i][c].load(qrow + (kc[c] / kLaneCodes) * kLaneWords);
-                sc[i][c] = p.scales[(size_t)n * p.G + kc[c] / kGroup];
-                zp[i][c] = p.zeros[(size_t)n * p.G + kc[c] / kGroup];
-            }
-            if (RI > 0) {
-#pragma unroll
-                for (int q = 0; q < RI; ++q) bt[i][q] = *reinterpret_cast<const uint32_t *>(p.Bt + (size_t)n * p.r + jc[q]);
+                cw[i][c].load(b.qw, qoff[c], n * p.row_words * 4);
+                sc[i][c] = __builtin_amdgcn_raw_buffer_load_b16(b.scales, goff[c], n * p.G * 2, 0);
+                zp[i][c] = __builtin_amdgcn_raw_buffer_load_b16(b.zeros, goff[c], n * p.G * 2, 0);
             }
         }
     }
 };
+
+// The lane's two taps of each of the tile's ROWS rows of Bt (taps past r re-read tap 0; their t is zero).
+template <int ROWS, int RI>
+__device__ __forceinline__ void load_taps(uint32_t (&bt)[ROWS][RI], const LayerParams &p, const TileBuffers &b, int n0, const int (&joff)[RI])
+{
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) {
+        const int n = min(n0 + i, p.N - 1);
+#pragma unroll
+        for (int q = 0; q < RI; ++q) bt[i][q] = __builtin_amdgcn_raw_buffer_load_b32(b.bt, joff[q], n * p.r * 2, 0);
+    }
+}
 
 // BITS: 3 or 4.  CPW: chunks (of 2048 codes) per wave.  KS: waves of a block that split K.
 // ROWS: rows per tile.  RI: ceil(r/128), 0 = branch-free twin.
@@ -309,26 +349,36 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     constexpr int kWaves = 4;
     constexpr int kRowSets = kWaves / KS;               // row sets per block
     constexpr int kRI = RI > 0 ? RI : 1;
+    constexpr int kXChunks = CPW * KS;                  // chunks of 2048 activations the block covers
     __shared__ float red[kWaves * (ROWS > kProdCols ? ROWS : kProdCols)];   // K-split sums, or the producer's wave sums
     __shared__ float t_lds[RI > 0 ? RI * 128 : 1];                          // t as wave 0 received it
+    __shared__ uint4 x_lds[kXChunks * 256];                                 // the token's activations, 16-byte pieces swizzled
 
+    // Which layer of the group this block serves: block_begin[] is padded with the grid size, so the
+    // comparison is false for entries past the last layer and no loop over loads is needed.
     const int m = blockIdx.y;
     int l = 0;
-    while (l + 1 < g.n_layers && (int)blockIdx.x >= g.block_begin[l + 1]) ++l;
-    const LayerParams &p = g.layer[l];
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i) l += (int)blockIdx.x >= g.block_begin[i] ? 1 : 0;
+    const LayerParams p = g.layer[l];
     int bx = (int)blockIdx.x - g.block_begin[l];
     uint32_t tag = 0;
     if (RI > 0) {
         tag = launch_tag();
         if (bx < p.producers) {                         // block-uniform: producer blocks only produce
+            __builtin_amdgcn_s_setprio(3);              // every consumer waits for them
+            FBQ_STAMP(0);
             produce_t(p, m, bx, tag, red);
+            FBQ_STAMP(6);
             return;
         }
         bx -= p.producers;
     }
 
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    FBQ_STAMP(0);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in all lanes: lets row offsets live in scalar registers
     const int ks = wave % KS;                           // which K slice
     const int rs = wave / KS;                           // which row set of the block
     const int ntiles = (p.N + ROWS - 1) / ROWS;
@@ -336,54 +386,85 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     const int trips = (ntiles - bx * kRowSets + tstride - 1) / tstride;   // block-uniform (>= 1 by construction)
     int tile = bx * kRowSets + rs;
 
-    int kc[CPW];
+    // The token's activations: the block fetches them once (each thread 16 bytes per chunk) ...
+    const uint16_t *xrow = p.x + (size_t)m * p.K;
+    uint4 xin[kXChunks];
+#pragma unroll
+    for (int i = 0; i < kXChunks; ++i) {
+        const int k = (i * 256 + tid) * 8;
+        xin[i] = k < p.K ? *reinterpret_cast<const uint4 *>(xrow + k) : make_uint4(0u, 0u, 0u, 0u);
+    }
+
+    // ... and right behind them the first two tiles go out, before anything waits.
+    int qoff[CPW], goff[CPW];
     bool kv[CPW];
 #pragma unroll
     for (int c = 0; c < CPW; ++c) {
         const int k0 = ((ks * CPW + c) * 64 + lane) * kLaneCodes;
         kv[c] = k0 < p.K;
-        kc[c] = kv[c] ? k0 : 0;
+        const int kc = kv[c] ? k0 : 0;
+        qoff[c] = (kc / kLaneCodes) * RowTile<BITS, CPW, ROWS>::kLaneWords * 4;
+        goff[c] = (kc / kGroup) * 2;
     }
-    int jc[kRI];
+    int joff[kRI];
     bool jv[kRI];
 #pragma unroll
     for (int q = 0; q < kRI; ++q) {
         const int j = (q * 64 + lane) * 2;
         jv[q] = RI > 0 && j < p.r;
-        jc[q] = jv[q] ? j : 0;
+        joff[q] = jv[q] ? j * 2 : 0;
     }
+    RowTile<BITS, CPW, ROWS> cur, nxt;                  // even and odd trips
+    uint32_t bt0[ROWS][kRI], bt1[ROWS][kRI];            // their rows of Bt
+    cur.load(p, tile_buffers(p, true), min(tile, ntiles - 1) * ROWS, qoff, goff);
+    if (RI > 0) load_taps<ROWS, kRI>(bt0, p, tile_buffers(p, true), min(tile, ntiles - 1) * ROWS, joff);
+    FBQ_STAMP(4);
+    __builtin_amdgcn_sched_barrier(0);
 
-    // activations of this wave's K range: loaded once, used for every tile
-    uint4 xraw[CPW][4];
-    const uint16_t *xrow = p.x + (size_t)m * p.K;
+    // Activations into LDS (piece j at j ^ ((j >> 4) & 3): the 16 lanes of a quarter wave then read 16
+    // different bank groups), and from there the wave's K range into registers, used for every tile.
+#pragma unroll
+    for (int i = 0; i < kXChunks; ++i) {
+        const int j = i * 256 + tid;
+        x_lds[j ^ ((j >> 4) & 3)] = xin[i];
+    }
+    __syncthreads();
+    XFrag<BITS> xf[CPW];
 #pragma unroll
     for (int c = 0; c < CPW; ++c) {
-        const uint4 *src = reinterpret_cast<const uint4 *>(xrow + kc[c]);
+        uint4 raw[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            xraw[c][i] = src[i];
+            const int j = ((ks * CPW + c) * 64 + lane) * 4 + i;
+            raw[i] = x_lds[j ^ ((j >> 4) & 3)];
         }
+        xf[c].arrange(raw, kv[c]);
     }
+    // The second tile goes out only now: the memory pipeline serves a compute unit's requests in the
+    // order they were made, and the first tiles of all its waves should come before any second tile.
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) asm volatile("" : "+v"(xf[c].sum));
+    __builtin_amdgcn_sched_barrier(0);
+    nxt.load(p, tile_buffers(p, trips > 1), min(tile + tstride, ntiles - 1) * ROWS, qoff, goff);
+    __builtin_amdgcn_sched_barrier(0);
 
-    RowTile<BITS, CPW, ROWS, RI> cur, nxt;
-    cur.load(p, min(tile, ntiles - 1) * ROWS, kc, jc);
-
-    // t is requested when the first tile's arithmetic starts and looked at when it ends: by then the
-    // producers, which were dispatched first and load far less, have usually delivered.
-    // A lane needs t[j], t[j+1]: one 16-byte device-scope load {value, tag, value, tag}.
-    // With several K slices there is one such word pair per slice, and the lane adds the partial sums.
+    // t: a lane needs t[j], t[j+1]: one 16-byte device-scope load {value, tag, value, tag}.  With several
+    // K slices there is one such word pair per slice, and the lane adds the partial sums.
     const int tslices = RI > 0 ? p.tslices : 1;
     const __amdgpu_buffer_rsrc_t tbuf = dev_buffer(p.ttag + (size_t)m * tslices * p.r, (RI > 0 ? tslices * p.r : 1) * 8);
     uint4_t tw[kRI][kMaxTSlices];
     float t0[kRI], t1[kRI];
     bool have_t = false;
+#ifdef FBQ_TRACE
+    bool traced = false;
+#endif
     auto request_t = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < RI; ++q)
 #pragma unroll
             for (int sl = 0; sl < kMaxTSlices; ++sl)
-                if (sl < tslices)   // lanes without a tap aim past the end: the buffer unit answers zero without touching memory
-                    tw[q][sl] = __builtin_amdgcn_raw_buffer_load_b128(tbuf, jv[q] ? (sl * p.r + jc[q]) * 8 : tslices * p.r * 8, 0, kCacheSc1);
+                // lanes without a tap, and slices the layer does not have, aim past the end: the buffer unit answers zero without touching memory
+                tw[q][sl] = __builtin_amdgcn_raw_buffer_load_b128(tbuf, jv[q] && sl < tslices ? (sl * p.r) * 8 + joff[q] * 4 : tslices * p.r * 8, 0, kCacheSc1);
     };
     auto t_arrived = [&]() __attribute__((always_inline)) {
         bool ok = true;
@@ -395,93 +476,66 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
         return (bool)__all(ok);
     };
 
-    XFrag<BITS> xf[CPW];
-#pragma unroll
-    for (int c = 0; c < CPW; ++c) xf[c].arrange(xraw[c], kv[c]);
-
-    // Two tile buffers used alternately (no copies between them): the loads of one tile are in flight
-    // while the other is worked on.
-    auto process = [&](const RowTile<BITS, CPW, ROWS, RI> &cur, int tile) __attribute__((always_inline)) {
-        if (RI > 0 && wave == 0 && !have_t) {           // one wave per block fetches t for all of them
-            __builtin_amdgcn_sched_barrier(0);
-            request_t();
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // main path: de-quantize and multiply; clamped lanes hold zero activations and add nothing
-        float acc[ROWS];
-#pragma unroll
-        for (int i = 0; i < ROWS; ++i) {
-            float a = 0.0f;
-#pragma unroll
-            for (int c = 0; c < CPW; ++c) {
-                const float qx = cur.cw[i][c].dot(xf[c].p);
-                const float s = (float)__builtin_bit_cast(half_t, (uint16_t)cur.sc[i][c]);
-                const float z = (float)__builtin_bit_cast(half_t, (uint16_t)cur.zp[i][c]);
-                a = fmaf(s, fmaf(-z, xf[c].sum, qx), a);
+    // Block-uniform.  Wave 0 takes t (requested one tile earlier, see below), waiting if it is not there
+    // yet, and passes it to the other waves through LDS.
+    auto take_t = [&]() __attribute__((always_inline)) {
+        if (wave == 0) {
+            bool ready = t_arrived();
+            for (int spin = 0; spin < kSpinLimit && !ready; ++spin) {
+                request_t();
+                ready = t_arrived();
+                if (!ready) __builtin_amdgcn_s_sleep(4);
             }
-            acc[i] = a;
-        }
-
-        // First tile only (block-uniform): wave 0 takes t, waiting if it is not there yet, and passes it
-        // to the other waves through LDS.
-        if (RI > 0 && !have_t) {
-            if (wave == 0) {
-                bool ready = t_arrived();
-                if (!ready) {
-#pragma unroll
-                    for (int i = 0; i < ROWS; ++i) asm volatile("" : "+v"(acc[i]));   // finish the arithmetic before waiting
-                    for (int spin = 0; spin < kSpinLimit && !ready; ++spin) {
-                        request_t();
-                        ready = t_arrived();
-                        if (!ready) __builtin_amdgcn_s_sleep(4);
-                    }
-                }
-#pragma unroll
-                for (int q = 0; q < RI; ++q) {
-                    float u0 = 0.0f, u1 = 0.0f;
-                    if (ready) {
-#pragma unroll
-                        for (int sl = 0; sl < kMaxTSlices; ++sl) {
-                            if (sl < tslices) {
-                                const uint32_t v0 = tw[q][sl].x, v1 = tw[q][sl].z;   // scalars first: bit_cast of a vector component reads the wrong lane
-                                u0 += __builtin_bit_cast(float, v0);
-                                u1 += __builtin_bit_cast(float, v1);
-                            }
-                        }
-                    } else {                            // producers never showed up in time: do it here
-                        const uint16_t *a0 = p.At + (size_t)jc[q] * p.K, *a1 = a0 + p.K;
-                        for (int k = 0; k < p.K; ++k) {
-                            const float xv = (float)__builtin_bit_cast(half_t, xrow[k]);
-                            u0 = fmaf(xv, (float)__builtin_bit_cast(half_t, a0[k]), u0);
-                            u1 = fmaf(xv, (float)__builtin_bit_cast(half_t, a1[k]), u1);
-                        }
-                    }
-                    t_lds[(q * 64 + lane) * 2] = jv[q] ? u0 : 0.0f;
-                    t_lds[(q * 64 + lane) * 2 + 1] = jv[q] ? u1 : 0.0f;
-                }
-            }
-            __syncthreads();
 #pragma unroll
             for (int q = 0; q < RI; ++q) {
-                t0[q] = t_lds[(q * 64 + lane) * 2];
-                t1[q] = t_lds[(q * 64 + lane) * 2 + 1];
+                float u0 = 0.0f, u1 = 0.0f;
+                if (ready) {
+#pragma unroll
+                    for (int sl = 0; sl < kMaxTSlices; ++sl) {
+                        if (sl < tslices) {
+                            const uint32_t v0 = tw[q][sl].x, v1 = tw[q][sl].z;   // scalars first: bit_cast of a vector component reads the wrong lane
+                            u0 += __builtin_bit_cast(float, v0);
+                            u1 += __builtin_bit_cast(float, v1);
+                        }
+                    }
+                } else {                            // producers never showed up in time: do it here
+                    const uint16_t *a0 = p.At + (size_t)(joff[q] / 2) * p.K, *a1 = a0 + p.K;
+                    for (int k = 0; k < p.K; ++k) {
+                        const float xv = (float)__builtin_bit_cast(half_t, xrow[k]);
+                        u0 = fmaf(xv, (float)__builtin_bit_cast(half_t, a0[k]), u0);
+                        u1 = fmaf(xv, (float)__builtin_bit_cast(half_t, a1[k]), u1);
+                    }
+                }
+                t_lds[(q * 64 + lane) * 2] = jv[q] ? u0 : 0.0f;
+                t_lds[(q * 64 + lane) * 2 + 1] = jv[q] ? u1 : 0.0f;
             }
-            have_t = true;
         }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < RI; ++q) {
+            t0[q] = t_lds[(q * 64 + lane) * 2];
+            t1[q] = t_lds[(q * 64 + lane) * 2 + 1];
+        }
+        have_t = true;
+#ifdef FBQ_TRACE
+        asm volatile("" : "+v"(t0[0])); FBQ_STAMP(2);
+#endif
+    };
 
-        // up-projection into the same accumulators (the K-slice-0 wave of each row set only)
+    // Second half of a tile: up-projection into the same accumulators (the K-slice-0 wave of each row
+    // set only), sum over the wave (and over the K slices), one store per row.
+    auto finish = [&](float (&acc)[ROWS], const uint32_t (&bt)[ROWS][kRI], int tile) __attribute__((always_inline)) {
         if (RI > 0 && ks == 0) {
 #pragma unroll
             for (int q = 0; q < RI; ++q) {
 #pragma unroll
                 for (int i = 0; i < ROWS; ++i) {
-                    const half2_t b = as_h2(cur.bt[i][q]);
+                    const half2_t b = as_h2(bt[i][q]);
                     acc[i] = fmaf(t0[q], (float)b.x, acc[i]);
                     acc[i] = fmaf(t1[q], (float)b.y, acc[i]);
                 }
             }
         }
-
         float out = 0.0f;   // lane i of the wave ends up holding row n0 + i
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
@@ -501,25 +555,83 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
         const int n0 = tile * ROWS;
         if (ks == 0 && lane < ROWS && tile < ntiles && n0 + lane < p.N)
             p.y[(size_t)m * p.N + n0 + lane] = __builtin_bit_cast(uint16_t, (half_t)out);
+#ifdef FBQ_TRACE
+        if (!traced) { FBQ_STAMP(3); traced = true; }
+#endif
     };
 
-    // Steady state: both prefetches unconditional, so the compiler can count exactly how many loads
-    // are younger than the tile being used.  trips is block-uniform; the last one or two tiles follow.
-    int it = 0;
-    for (; it + 2 < trips; it += 2) {
-        nxt.load(p, min(tile + tstride, ntiles - 1) * ROWS, kc, jc);
-        process(cur, tile);
-        cur.load(p, min(tile + 2 * tstride, ntiles - 1) * ROWS, kc, jc);
-        process(nxt, tile + tstride);
+    // One trip.  The tile's registers are refilled (with the tile two trips ahead, or with nothing) as
+    // soon as the arithmetic has consumed them.  With a sub-branch the second half of a tile is
+    // postponed by one trip: t is requested when the next tile's arithmetic starts and taken when it
+    // ends, so waiting for the producers hides behind a whole tile of the weight stream (a wave with a
+    // single trip has nothing to hide behind and waits at once).  Even trips use (cur, bt0, acc0), odd
+    // trips (nxt, bt1, acc1): the rows of Bt for trip j + 1 are fetched in trip j, when the previous
+    // owner of that buffer, trip j - 1, has been finished.
+    float acc0[ROWS], acc1[ROWS];
+    auto step = [&](RowTile<BITS, CPW, ROWS> &T, float (&acc)[ROWS], float (&acc_prev)[ROWS], uint32_t (&bt_mine)[ROWS][kRI],
+                    uint32_t (&bt_prev)[ROWS][kRI], int j, int tile) __attribute__((always_inline)) {
+        if (RI > 0 && wave == 0 && !have_t && (j > 0 || trips == 1)) {
+            __builtin_amdgcn_sched_barrier(0);
+            request_t();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // main path: de-quantize and multiply; clamped lanes hold zero activations and add nothing
+#pragma unroll
+        for (int i = 0; i < ROWS; ++i) {
+            float a = 0.0f;
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) {
+#if FBQ_EXP == 3
+                float qx = 0.0f;
+                for (int w = 0; w < RowTile<BITS, CPW, ROWS>::kLaneWords; ++w) qx += __builtin_bit_cast(float, T.cw[i][c].w[w] & 0x3fffffffu);
+#else
+                const float qx = T.cw[i][c].dot(xf[c].p);
+#endif
+                const float s = (float)__builtin_bit_cast(half_t, (uint16_t)T.sc[i][c]);
+                const float z = (float)__builtin_bit_cast(half_t, (uint16_t)T.zp[i][c]);
+                a = fmaf(s, fmaf(-z, xf[c].sum, qx), a);
+            }
+            acc[i] = a;
+        }
+#pragma unroll
+        for (int i = 0; i < ROWS; ++i) asm volatile("" : "+v"(acc[i]));   // the arithmetic is done before the registers are handed back
+#ifdef FBQ_TRACE
+        if (!traced) { FBQ_STAMP(1); }
+#endif
+        __builtin_amdgcn_sched_barrier(0);
+        T.load(p, tile_buffers(p, j + 2 < trips), min(tile + 2 * tstride, ntiles - 1) * ROWS, qoff, goff);
+        __builtin_amdgcn_sched_barrier(0);
+        if (RI == 0) {
+            finish(acc, bt_mine, tile);
+            return;
+        }
+        if (j > 0) {
+            if (!have_t) take_t();
+            finish(acc_prev, bt_prev, tile - tstride);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        load_taps<ROWS, kRI>(bt_prev, p, tile_buffers(p, j + 1 < trips), min(tile + tstride, ntiles - 1) * ROWS, joff);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // trips is block-uniform; the loop body is straight-line, so the number of loads in flight at every
+    // wait is known at compile time.
+    int j = 0;
+    for (; j + 1 < trips; j += 2) {
+        step(cur, acc0, acc1, bt0, bt1, j, tile);
+        step(nxt, acc1, acc0, bt1, bt0, j + 1, tile + tstride);
         tile += 2 * tstride;
     }
-    if (it + 1 < trips) {
-        nxt.load(p, min(tile + tstride, ntiles - 1) * ROWS, kc, jc);
-        process(cur, tile);
-        process(nxt, tile + tstride);
-    } else {
-        process(cur, tile);
+    if (j < trips) {
+        step(cur, acc0, acc1, bt0, bt1, j, tile);
+        tile += tstride;
     }
+    if (RI > 0) {                                       // the last trip's second half
+        if (!have_t) take_t();
+        if (trips & 1) finish(acc0, bt0, tile - tstride);
+        else finish(acc1, bt1, tile - tstride);
+    }
+    FBQ_STAMP(5);
 }
 
 // ------------------------------------------------------------------ dispatch
@@ -566,7 +678,9 @@ static hipError_t launch_ri(const GemvGroup &g, int ri, dim3 grid, hipStream_t s
 template <int BITS, int CPW, int KS>
 static hipError_t launch_rows(const GemvGroup &g, int rows, int ri, dim3 grid, hipStream_t stream)
 {
-    if (rows == 4) return launch_ri<BITS, CPW, KS, 4>(g, ri, grid, stream);
+    if constexpr (CPW == 1) {                           // wider tiles only where a row is a single chunk
+        if (rows == 4) return launch_ri<BITS, CPW, KS, 4>(g, ri, grid, stream);
+    }
     return launch_ri<BITS, CPW, KS, 2>(g, ri, grid, stream);
 }
 
@@ -574,14 +688,16 @@ template <int BITS>
 static hipError_t launch_bits(const GemvGroup &g, const Variant &v, int rows, dim3 grid, hipStream_t stream)
 {
     switch (v.ks * 10 + v.cpw) {
-    case 11: return launch_rows<BITS, 1, 1>(g, rows, v.ri, grid, stream);
     case 12: return launch_rows<BITS, 2, 1>(g, rows, v.ri, grid, stream);
+    case 23: return launch_rows<BITS, 3, 2>(g, rows, v.ri, grid, stream);
+#ifndef FBQ_FAST_BUILD
+    case 11: return launch_rows<BITS, 1, 1>(g, rows, v.ri, grid, stream);
     case 13: return launch_rows<BITS, 3, 1>(g, rows, v.ri, grid, stream);
     case 14: return launch_rows<BITS, 4, 1>(g, rows, v.ri, grid, stream);
-    case 23: return launch_rows<BITS, 3, 2>(g, rows, v.ri, grid, stream);
     case 24: return launch_rows<BITS, 4, 2>(g, rows, v.ri, grid, stream);
     case 43: return launch_rows<BITS, 3, 4>(g, rows, v.ri, grid, stream);
     case 44: return launch_rows<BITS, 4, 4>(g, rows, v.ri, grid, stream);
+#endif
     }
     return hipErrorInvalidValue;   // K > 32768: rejected by the caller's shape check
 }
@@ -610,11 +726,14 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
     }
     const int row_sets = 4 / v.ks;
     // Blocks to share out: two per CU keeps enough bytes in flight; a token dimension multiplies the grid.
-    const int budget = std::max(1, 2 * device_cu_count() / std::max(1, std::min(M, 2)));
+    int per_cu = 2;
+    if (const char *e = getenv("FBQ_TUNE_BLOCKS_PER_CU")) per_cu = std::max(1, atoi(e));   // TEMP tuning hook
+    const int budget = std::max(1, per_cu * device_cu_count() / std::max(1, std::min(M, 2)));
     // Tiles of 4 rows when that still leaves every wave at least one tile, and registers allow; else 2.
     long tiles4 = 0;
     for (int i = 0; i < n_layers; ++i) tiles4 += ceil_div(layers[i].N, 4);
-    const int rows = (v.cpw <= 2 && tiles4 >= (long)budget * row_sets) ? 4 : 2;
+    int rows = (v.cpw == 1 && tiles4 >= (long)budget * row_sets) ? 4 : 2;
+    if (const char *e = getenv("FBQ_TUNE_ROWS")) rows = atoi(e) == 4 ? 4 : 2;   // TEMP tuning hook
 
     // Persistent consumer blocks have fixed tile lists, so every one of them must be resident from the
     // start: the producers take their block slots out of the same budget.
@@ -638,12 +757,19 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
         const int max_blocks = ceil_div(ceil_div(a.N, rows), row_sets);
         const int share = (int)(consumer_budget * ((double)a.N * a.K / total_work));
         p.blocks = std::max(1, std::min(max_blocks, share));
+        // the fewest blocks that need no more trips than that: every wave then makes (almost) the same
+        // number of trips, and the last trip is as wide as the others
+        if (getenv("FBQ_TUNE_EVEN")) p.blocks = ceil_div(max_blocks, ceil_div(max_blocks, p.blocks));
         g.block_begin[i] = next_block;
         next_block += p.producers + p.blocks;
     }
     for (int i = n_layers; i <= kMaxGroup; ++i) g.block_begin[i] = next_block;
     const dim3 grid(next_block, M);
+#ifdef FBQ_FAST_BUILD
+    return launch_bits<4>(g, v, rows, grid, stream);
+#else
     return v.bits == 4 ? launch_bits<4>(g, v, rows, grid, stream) : launch_bits<3>(g, v, rows, grid, stream);
+#endif
 }
 
 }  // namespace fbq

@@ -1,30 +1,39 @@
-// Decode path for a few tokens (2 <= M <= 16): the fused kernel of Sec. 4.3 with the packed codes
-// still streamed exactly once, the tokens riding along as the 16 rows of a matrix-core tile.
+// Decode path for a few tokens (5 <= M <= 16): the fused kernel of Sec. 4.3 with the packed codes
+// streamed exactly once, the tokens riding along as the 16 rows of a matrix-core tile.
 //
 //   y[M,N] = x[M,K] . Wq[N,K]^T + t[M,r] . B[r,N],   t = x . A
 //
-// Two launches, as in the paper: a small down-projection, then the fused kernel.
+// Two launches, as in the paper: a small preparation launch (down-projection, and the activations
+// rewritten into operand order), then the fused kernel.
 //
-// Fused kernel.  A block owns 16 TN consecutive output columns and walks over K in chunks of 2048
-// codes.  The packed words go from HBM straight into LDS (global_load_lds), one instruction per row
-// and chunk: 64 lanes x 16 B (INT4) or 12 B (INT3) = one contiguous kilobyte of a single row, the
-// access pattern the memory likes, double buffered so that the next chunk streams in while this one
-// is worked on.  The block's four waves take four quantization groups of the chunk each and add
-// their tiles up through LDS at the end.  v_mfma_f32_16x16x32_f16 multiplies a 16 (token) x 32 (k)
-// activation fragment with a 32 (k) x 16 (column) weight fragment.  Lane (c = lane % 16,
-// q = lane / 16) holds 8 values of k for token c in the first and for column c in the second, and
-// the instruction only needs both operands to agree on which k that is.  So for one group of 128
-// lane (c, q) takes the 32 codes k = 32 q .. 32 q + 31 of its column - one 16- or 12-byte LDS read
-// (rows padded by 16 B: no bank conflicts) - and the same 32 activations of its token, read from
-// L2 and arranged in registers into the pair order the code extraction produces; the four matrix
-// instructions of the group use 8 of the 32 each.
+// v_mfma_f32_16x16x32_f16 multiplies a 16 (token) x 32 (k) activation fragment with a 32 (k) x 16
+// (output row) weight fragment.  Lane (c = lane % 16, q = lane / 16) supplies 8 values of k for
+// token c in the first operand and for output row c in the second, and the instruction only needs
+// both operands to agree on which k that is.
 //
-// De-quantization is split around the matrix instruction so that nothing is rounded on the way:
-// the weight operand carries the plain codes q (small integers, exact in fp16), the group's tile
-// D = sum_k x q comes back in fp32, a fifth matrix instruction against an all-ones operand gives
-// X = sum_k x in the same register layout, and the lane that holds column n adds s (D - z X) to its
-// accumulator in fp32.  The up-projection enters the same accumulators as r more values of k, with
-// t split into two fp16 halves (t_hi + t_lo carries 22 bits of the fp32 sum).
+// Weights.  For one quantization group (128 codes) of 16 consecutive output rows, lane (c, q) loads
+// the 32 codes k = 32 q .. 32 q + 31 of row c: one 16-byte (INT4) or 12-byte (INT3) load straight
+// from the packed row into registers, no LDS in between.  A wave owns four consecutive groups, so
+// the 16 row segments it reads are 256 (192) contiguous bytes each.  Masking a packed word with
+// 0x000F000F and OR-ing 0x64006400 leaves two codes as the fp16 pair (1024 + q, 1024 + q'); fields
+// that sit 4 (3, 6) bits higher come out as 1024 + 16 q (8 q, 64 q).  These go into the matrix
+// instruction as they are: one v_and_or_b32 per two codes is all the de-quantization the inner
+// loop does.
+//
+// Activations.  The preparation launch writes, for every group g, matrix instruction t and lane,
+// the 8 activations that meet those 8 weights - already divided by 16 (8, 64) where the weight
+// field is scaled - as one 16-byte operand; 64 lanes read one contiguous kilobyte.  A wave keeps
+// the operands of its four groups in registers and walks over the block's row tiles with them, so
+// a block reads the activations once, whatever the number of rows it owns.  The same launch
+// stores, per group and token, X = sum x and XS = 1024 sum x' (x' the scaled activations).
+//
+// One group of one row tile then is  D' = sum x' (1024 + m q) = XS + sum x q  (four matrix
+// instructions, fp32, every product exact), and the lane that holds output row n adds
+// s (D' - XS - z X) to its accumulator: the same factorisation as in the one-token kernel.
+//
+// A block's eight waves split K; their partial tiles meet in LDS, and the wave that finishes a tile
+// folds the up-projection in as r more values of k (t split into two fp16 halves: t_hi + t_lo
+// carries 22 bits of the fp32 sum) before y is stored once.
 #include <hip/hip_fp16.h>
 
 #include "fbq_internal.h"
@@ -35,20 +44,29 @@ typedef _Float16 half_t;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t uint2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t uint3_t __attribute__((ext_vector_type(3)));
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kTokens = 16;          // rows of the matrix-core tile; M is padded up to it
 constexpr int kMaxSlices = 4;        // K slices of the down-projection
+constexpr int kMainWaves = 8;        // waves per block of the fused kernel; they split K
+constexpr int kWaveGroups = 4;       // consecutive quantization groups a wave takes per pass over the block's tiles
+constexpr int kPassGroups = kMainWaves * kWaveGroups;   // groups one pass covers (4096 codes)
+constexpr int kMaxTiles = 3;         // 16-row tiles per block (more would not fit the register file next to the activations)
 
 __device__ __forceinline__ half2_t h2_of(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
-__device__ __forceinline__ half2_t h2_splat(half_t v) { return half2_t{v, v}; }
 __device__ __forceinline__ half8_t pack8(half2_t a, half2_t b, half2_t c, half2_t d)
 {
     return half8_t{a.x, a.y, b.x, b.y, c.x, c.y, d.x, d.y};
 }
-__device__ __forceinline__ int ceil_div_dev(int a, int b) { return (a + b - 1) / b; }
 __device__ __forceinline__ float4_t mfma(half8_t a, half8_t b, float4_t c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_of(const void *p, long bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
 }
 
 struct SmallParams {
@@ -60,267 +78,287 @@ struct SmallParams {
     const uint16_t *x;     // [M][K]
     uint16_t *y;           // [M][N]
     float *tpart;          // workspace: [slices][16][r] partial sums of t
+    float *xsum;           // workspace: [G][2][16]: X = sum x and XS = 1024 sum x' per group and token
+    uint4 *xop;            // workspace: [G][4][64] 16-byte activation operands
     int M, N, K, r;
     int row_words, G;
     int slices, kslice;    // down-projection: number of K slices and their length (a multiple of 128)
+    int down_blocks;       // blocks of the preparation launch that do the down-projection; the rest arrange x
+    int tiles_per_block;   // 16-row tiles a block of the fused kernel owns
 };
 
-// (w & mask) | 0x6400 in both halves: the masked field lands in the mantissa of 1024.0
-__device__ __forceinline__ half2_t field(uint32_t w, uint32_t mask, uint32_t k6400)
+// What the weight field of pair p (0..15, in extraction order) is multiplied by; the activation that meets it is divided by it.
+template <int BITS>
+__device__ __forceinline__ constexpr float field_gain(int p)
 {
-    uint32_t v;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(v) : "v"(w), "s"(mask), "v"(k6400));
-    return h2_of(v);
+    if (BITS == 4) return (p & 1) ? 16.0f : 1.0f;
+    if (p == 15) return 1.0f;
+    const int f = p % 5;
+    return f == 1 || f == 4 ? 8.0f : (f == 2 ? 64.0f : 1.0f);
 }
 
-// The lane's 32 codes of one group as 16 exact fp16 pairs, in extraction order:
-// INT4 word j -> pairs (8j+f, 8j+f+4), f = 0..3;  INT3 word j -> pairs (10j+f, 10j+f+5), f = 0..4,
-// and codes (30, 31) last.
+// (w & mask) | 0x6400 in both halves: the masked field lands in the mantissa of 1024.0.  Plain C on
+// purpose (it becomes one v_and_or_b32): the result feeds a matrix instruction directly, and only
+// for instructions it has selected itself does the compiler keep the required distance.
+__device__ __forceinline__ half2_t field(uint32_t w, uint32_t mask, uint32_t k6400)
+{
+    return h2_of((w & mask) | k6400);
+}
+
+// The lane's 32 codes of one group and their four matrix operands.  Pair order (also the order of
+// the prepared activations): INT4 word j -> codes (8j+f, 8j+f+4), f = 0..3;  INT3 word j -> codes
+// (10j+f, 10j+f+5), f = 0..4, and codes (30, 31) last.
 template <int BITS>
 struct SmallCodes {
     static constexpr int kWords = BITS == 4 ? 4 : 3;
     uint32_t w[kWords];
 
-    __device__ __forceinline__ void load(const uint32_t *p)
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t buf, int lane_off, int tile_off)
     {
-        if (BITS == 4) {
-            const uint4 q = *reinterpret_cast<const uint4 *>(p);
-            w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+        if constexpr (BITS == 4) {
+            const uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(buf, lane_off, tile_off, 0);
+            w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
         } else {
-            w[0] = p[0]; w[1] = p[1]; w[2] = p[2];
+            const uint3_t v = __builtin_amdgcn_raw_buffer_load_b96(buf, lane_off, tile_off, 0);
+            w[0] = v.x; w[1] = v.y; w[2] = v.z;
         }
     }
 
-    __device__ __forceinline__ void pairs(uint32_t k6400, half2_t (&out)[16]) const
+    __device__ __forceinline__ void operands(uint32_t k6400, half8_t (&b)[4]) const
     {
-        const half2_t k1024 = h2_splat((half_t)-1024.0f);
-        if (BITS == 4) {
-            const half2_t r16 = h2_splat((half_t)0.0625f), k64 = h2_splat((half_t)-64.0f);
+        if constexpr (BITS == 4) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const uint32_t a = w[j], b = w[j] >> 8;
-                out[4 * j + 0] = field(a, 0x000F000Fu, k6400) + k1024;
-                out[4 * j + 1] = field(a, 0x00F000F0u, k6400) * r16 + k64;
-                out[4 * j + 2] = field(b, 0x000F000Fu, k6400) + k1024;
-                out[4 * j + 3] = field(b, 0x00F000F0u, k6400) * r16 + k64;
+                const uint32_t lo = w[j], hi = w[j] >> 8;
+                b[j] = pack8(field(lo, 0x000F000Fu, k6400), field(lo, 0x00F000F0u, k6400), field(hi, 0x000F000Fu, k6400),
+                             field(hi, 0x00F000F0u, k6400));
             }
         } else {
-            const half2_t r8 = h2_splat((half_t)0.125f), k128 = h2_splat((half_t)-128.0f);
-            const half2_t r64 = h2_splat((half_t)0.015625f), k16 = h2_splat((half_t)-16.0f);
+            half2_t d[16];
 #pragma unroll
             for (int j = 0; j < 3; ++j) {
-                const uint32_t a = w[j], b = w[j] >> 9;
-                out[5 * j + 0] = field(a, 0x00070007u, k6400) + k1024;
-                out[5 * j + 1] = field(a, 0x00380038u, k6400) * r8 + k128;
-                out[5 * j + 2] = field(a, 0x01C001C0u, k6400) * r64 + k16;
-                out[5 * j + 3] = field(b, 0x00070007u, k6400) + k1024;
-                out[5 * j + 4] = field(b, 0x00380038u, k6400) * r8 + k128;
+                const uint32_t lo = w[j], hi = w[j] >> 9;
+                d[5 * j + 0] = field(lo, 0x00070007u, k6400);
+                d[5 * j + 1] = field(lo, 0x00380038u, k6400);
+                d[5 * j + 2] = field(lo, 0x01C001C0u, k6400);
+                d[5 * j + 3] = field(hi, 0x00070007u, k6400);
+                d[5 * j + 4] = field(hi, 0x00380038u, k6400);
             }
             const uint32_t e = ((w[0] >> 15) & 0x00010001u) | ((w[1] >> 14) & 0x00020002u) | ((w[2] >> 13) & 0x00040004u);
-            out[15] = h2_of(e | 0x64006400u) + k1024;
+            d[15] = h2_of(e | 0x64006400u);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) b[t] = pack8(d[4 * t], d[4 * t + 1], d[4 * t + 2], d[4 * t + 3]);
         }
     }
 };
 
-// The lane's 32 activations of one group in the same pair order.
-template <int BITS>
-__device__ __forceinline__ void arrange_x(const uint4 (&raw)[4], half2_t (&p)[16])
+// fp16 number i (0..4) of three consecutive words
+__device__ __forceinline__ half_t half_at(uint3_t w, int i)
 {
-    half_t v[32];
+    const uint32_t lo = i < 2 ? w.x : (i < 4 ? w.y : w.z);
+    return __builtin_bit_cast(half_t, (uint16_t)((i & 1) ? lo >> 16 : lo));
+}
+
+// ------------------------------------------------------------------ preparation launch
+
+constexpr int kPrepWaves = 16;
+
+// Down-projection for up to 16 tokens: block (column tile of 16, K slice); the block's sixteen waves
+// take a sixteenth of the slice each.  partial[slice][token][j] = sum over the slice of
+// x[token][k] At[j][k]; token rows past M repeat the last token.
+__device__ void down_proj_block(const SmallParams &p, int b, float4_t (*red)[64])
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 15, q = lane >> 4;
+    const int col_tiles = (p.r + 15) / 16;
+    const int slice = b / col_tiles, j0 = (b - slice * col_tiles) * 16;
+    const int kw = p.kslice / kPrepWaves;               // a multiple of 32
+    const int kbeg = slice * p.kslice + wave * kw;
+    const int kend = min(p.K, kbeg + kw);
+    const uint16_t *xr = p.x + (size_t)min(c, p.M - 1) * p.K + 8 * q;
+    const uint16_t *ar = p.At + (size_t)min(j0 + c, p.r - 1) * p.K + 8 * q;
+    float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 8
+    for (int k = kbeg; k < kend; k += 32)
+        acc = mfma(*reinterpret_cast<const half8_t *>(xr + k), *reinterpret_cast<const half8_t *>(ar + k), acc);
+    red[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0) {
+        float4_t sum = red[0][lane];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+        for (int w = 1; w < kPrepWaves; ++w) sum += red[w][lane];
+        const int j = j0 + c;                           // lane (c, q) holds column j and tokens 4 q + v
+        if (j < p.r) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const half2_t h = h2_of(w[j]);
-            v[i * 8 + j * 2] = h.x;
-            v[i * 8 + j * 2 + 1] = h.y;
+            for (int v = 0; v < 4; ++v) p.tpart[((size_t)slice * kTokens + 4 * q + v) * p.r + j] = sum[v];
         }
-    }
-    if (BITS == 4) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int f = 0; f < 4; ++f) p[j * 4 + f] = half2_t{v[8 * j + f], v[8 * j + f + 4]};
-    } else {
-#pragma unroll
-        for (int w = 0; w < 3; ++w)
-#pragma unroll
-            for (int f = 0; f < 5; ++f) p[w * 5 + f] = half2_t{v[10 * w + f], v[10 * w + f + 5]};
-        p[15] = half2_t{v[30], v[31]};
     }
 }
 
-// Scales and zeros of the wave's four groups of one chunk for the lane's TN columns (fp16 bits):
-// lane (c, q) loads those of group g0 + q, and group i's are fetched from lane (c, i) when needed.
-template <int TN>
-struct ScaleRegs {
-    uint32_t sc[TN], zp[TN];
-    __device__ __forceinline__ void load(const SmallParams &p, const size_t (&sz)[TN], int g)
-    {
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            sc[tn] = p.scales[sz[tn] + g];
-            zp[tn] = p.zeros[sz[tn] + g];
-        }
-    }
-    // value held by lane (c, i), as a float
-    static __device__ __forceinline__ float from_group(uint32_t v, int src_lane)
-    {
-        const uint32_t u = (uint32_t)__builtin_amdgcn_ds_bpermute(src_lane * 4, (int)v);
-        return (float)__builtin_bit_cast(half_t, (uint16_t)u);
-    }
-};
-
-// The lane's 32 activations of one group as loaded; xl: token row + 32 q.
-struct SmallXRegs {
-    uint4 raw[4];
-    __device__ __forceinline__ void load(const uint16_t *xl, int g)
-    {
-        const uint4 *src = reinterpret_cast<const uint4 *>(xl + (size_t)g * kGroup);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) raw[i] = src[i];
-    }
-};
-
-constexpr int kChunkCodes = 2048;    // codes per row one wave-wide copy brings in: 16 quantization groups
-constexpr int kWaves = 4;            // waves per block; wave w works on groups 4 w .. 4 w + 3 of every chunk
-
+// Activation operands: wave w of arrange block b handles group g = 16 b + w; lane (c, q) turns the 32
+// activations k = 128 g + 32 q .. + 31 of token c (zeros for tokens past M) into the four operands
+// that meet the lane-(., q) weight operands, and the four lanes of a token add up X and XS.
 template <int BITS>
-struct SmallStage {
-    static constexpr int kLaneBytes = BITS == 4 ? 16 : 12;          // 32 codes
-    static constexpr int kRowBytes = 64 * kLaneBytes;               // one chunk of one row
-    static constexpr int kPitch = kRowBytes + 16;                   // LDS row pitch: 4 banks further per row
-};
-
-template <int BITS, int TN>
-constexpr int small_m_lds_bytes() { return 2 * 16 * TN * SmallStage<BITS>::kPitch + kWaves * TN * 64 * (int)sizeof(float4_t); }
-
-// BITS: 3 or 4.  TN: 16-column tiles per block.  BRANCH: r > 0.
-template <int BITS, int TN, bool BRANCH>
-__global__ __launch_bounds__(64 * kWaves) void fbq_gemv_mfma_kernel(const SmallParams p)
+__device__ void arrange_block(const SmallParams &p, int b)
 {
-    typedef SmallStage<BITS> St;
-    constexpr int kRows = 16 * TN;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int kStageBytes = kRows * St::kPitch;    // stage s of the packed words starts at smem + s * kStageBytes
-    float4_t *red = reinterpret_cast<float4_t *>(smem + 2 * kStageBytes);   // [kWaves][TN][64]
-
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, q = lane >> 4;
-    const int n0 = blockIdx.x * kRows;
-    const int chunks = ceil_div_dev(p.K, kChunkCodes);
-
-    // columns past N re-read the last row and tokens past M the last token: computed, never stored
-    size_t sz[TN];
+    const int g = b * kPrepWaves + wave;
+    if (g >= p.G) return;                               // wave-uniform
+    half_t v[32];
+    if (c < p.M) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(p.x + (size_t)c * p.K + (size_t)g * kGroup + 32 * q);
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) sz[tn] = (size_t)min(n0 + 16 * tn + c, p.N - 1) * p.G;
-    const uint16_t *xl = p.x + (size_t)min(c, p.M - 1) * p.K + 32 * q;
-
-    // copies of this wave: rows wave, wave + 4, ... of the block, one chunk of 2048 codes each.  INT4:
-    // one instruction of 64 x 16 B.  INT3: three of 64 x 4 B, each a contiguous 256 B piece of the 768.
-    // Lanes past the end of a row (last chunk only) re-read the row's start, which nobody uses.
-    auto copy_chunk = [&](int ch, int stage) __attribute__((always_inline)) {
+        for (int i = 0; i < 4; ++i) {
+            const uint4 raw = src[i];
+            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-        for (int i = 0; i < kRows / kWaves; ++i) {
-            const int row = wave + kWaves * i;
-            const uint32_t *src = p.qw + (size_t)min(n0 + row, p.N - 1) * p.row_words;
-            unsigned char *dst = &smem[stage * kStageBytes + row * St::kPitch];
-            if constexpr (BITS == 4) {                  // the size argument must be a literal
-                const int w = (ch * 64 + lane) * 4;
-                __builtin_amdgcn_global_load_lds(src + (w < p.row_words ? w : 0), (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 3; ++j) {
-                    const int w = ch * 192 + j * 64 + lane;
-                    __builtin_amdgcn_global_load_lds(src + (w < p.row_words ? w : 0),
-                                                     (__attribute__((address_space(3))) void *)(dst + j * 256), 4, 0, 0);
-                }
+            for (int j = 0; j < 4; ++j) {
+                const half2_t h = h2_of(w[j]);
+                v[i * 8 + j * 2] = h.x;
+                v[i * 8 + j * 2 + 1] = h.y;
             }
         }
-    };
+    } else {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) v[i] = (half_t)0.0f;
+    }
+    int first[16], second[16];                          // the two codes of pair p
+#pragma unroll
+    for (int pi = 0; pi < 16; ++pi) {
+        if (BITS == 4) { first[pi] = 8 * (pi / 4) + pi % 4; second[pi] = first[pi] + 4; }
+        else if (pi == 15) { first[pi] = 30; second[pi] = 31; }
+        else { first[pi] = 10 * (pi / 5) + pi % 5; second[pi] = first[pi] + 5; }
+    }
+    float X = 0.0f, XS = 0.0f;
+    half2_t pr[16];
+#pragma unroll
+    for (int pi = 0; pi < 16; ++pi) {
+        const half_t inv = (half_t)(1.0f / field_gain<BITS>(pi));
+        const half_t a = v[first[pi]] * inv, d = v[second[pi]] * inv;   // exact unless the quotient is subnormal
+        pr[pi] = half2_t{a, d};
+        X += (float)v[first[pi]] + (float)v[second[pi]];
+        XS += (float)a + (float)d;
+    }
+    uint4 *dst = p.xop + ((size_t)g * 4) * 64 + lane;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) dst[t * 64] = __builtin_bit_cast(uint4, pack8(pr[4 * t], pr[4 * t + 1], pr[4 * t + 2], pr[4 * t + 3]));
+    X += __shfl_xor(X, 16); X += __shfl_xor(X, 32);
+    XS += __shfl_xor(XS, 16); XS += __shfl_xor(XS, 32);
+    if (q == 0) {
+        p.xsum[((size_t)g * 2 + 0) * kTokens + c] = X;
+        p.xsum[((size_t)g * 2 + 1) * kTokens + c] = 1024.0f * XS;
+    }
+}
+
+template <int BITS>
+__global__ __launch_bounds__(64 * kPrepWaves) void fbq_small_m_prepare_kernel(const SmallParams p)
+{
+    __shared__ float4_t red[kPrepWaves][64];
+    if ((int)blockIdx.x < p.down_blocks) down_proj_block(p, blockIdx.x, red);
+    else arrange_block<BITS>(p, (int)blockIdx.x - p.down_blocks);
+}
+
+// ------------------------------------------------------------------ fused kernel
+
+// BITS: 3 or 4.  T: 16-row tiles per block.  BRANCH: r > 0.
+template <int BITS, int T, bool BRANCH>
+__global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const SmallParams p)
+{
+    constexpr int kPiece = BITS == 4 ? 16 : 12;         // bytes of 32 codes
+    __shared__ float4_t red[kMainWaves][T][64];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int c = lane & 15, q = lane >> 4;
+    const int ntiles = (p.N + 15) / 16;
+    const int tile0 = blockIdx.x * p.tiles_per_block;
+    const int row_bytes = p.row_words * 4;
+
+    const __amdgpu_buffer_rsrc_t qbuf = buffer_of(p.qw, (long)p.N * row_bytes);
+    const __amdgpu_buffer_rsrc_t sbuf = buffer_of(p.scales, (long)p.N * p.G * 2);
+    const __amdgpu_buffer_rsrc_t zbuf = buffer_of(p.zeros, (long)p.N * p.G * 2);
+    const __amdgpu_buffer_rsrc_t xbuf = buffer_of(p.xop, (long)p.G * 4 * 64 * 16);
+    const __amdgpu_buffer_rsrc_t ubuf = buffer_of(p.xsum, (long)p.G * 2 * kTokens * 4);
+
+    // rows past N re-read the last row: computed, never stored
+    int qrow[T], srow[T], odd[T];
+#pragma unroll
+    for (int ti = 0; ti < T; ++ti) {
+        const int n = min((tile0 + ti) * 16 + c, p.N - 1);
+        qrow[ti] = n * row_bytes + q * kPiece;
+        srow[ti] = n * p.G * 2;
+        odd[ti] = (n * p.G) & 1;                        // the wave's first group is a multiple of four
+    }
 
     uint32_t k6400 = 0x64006400u;
     asm volatile("" : "+v"(k6400));                     // keep the constant in a VGPR for v_and_or_b32
-    const half2_t one2 = h2_splat((half_t)1.0f);
-    const half8_t ones = pack8(one2, one2, one2, one2);
     const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    float4_t acc[T];
+#pragma unroll
+    for (int ti = 0; ti < T; ++ti) acc[ti] = zero4;
 
-    float4_t acc[TN];
+    // One pass: the wave's four groups g0 .. g0 + 3 against every tile of the block.  Everything the
+    // pass needs is requested up front.  Every offset that depends on the group is part of the
+    // bounds-checked per-lane offset of its buffer load: groups past the end of K read activation
+    // operands and sums beyond their buffers, i.e. zeros without a memory access, and add nothing
+    // (their weights and scales are whatever follows in the row, or zero behind the last row: finite
+    // either way).
+    const int passes = (p.G + kPassGroups - 1) / kPassGroups;
+    for (int pass = 0; pass < passes; ++pass) {
+        const int g0 = pass * kPassGroups + wave * kWaveGroups;
+        half8_t xa[kWaveGroups][4];
+        float4_t X[kWaveGroups], XS[kWaveGroups];
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) acc[tn] = zero4;
-
-    // one quantization group: block index blk = 4 (group within the chunk) + q of this lane's row segment
-    auto process = [&](const unsigned char *stage, int i, const ScaleRegs<TN> &sr, const SmallXRegs &xr) __attribute__((always_inline)) {
-        const int blk = 4 * (4 * wave + i) + q;         // the lane's 32-code block of the row's chunk
-        half2_t xp[16];
-        arrange_x<BITS>(xr.raw, xp);
-        half8_t a[4];
+        for (int gi = 0; gi < kWaveGroups; ++gi) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) a[i] = pack8(xp[4 * i], xp[4 * i + 1], xp[4 * i + 2], xp[4 * i + 3]);
-        float4_t X = zero4;                             // sum of the group's activations, per token
-#pragma unroll
-        for (int i = 0; i < 4; ++i) X = mfma(a[i], ones, X);
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            SmallCodes<BITS> cw;
-            cw.load(reinterpret_cast<const uint32_t *>(stage + (16 * tn + c) * St::kPitch + blk * St::kLaneBytes));
-            half2_t d[16];
-            cw.pairs(k6400, d);
-            float4_t D = zero4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) D = mfma(a[i], pack8(d[4 * i], d[4 * i + 1], d[4 * i + 2], d[4 * i + 3]), D);
-            const float s = ScaleRegs<TN>::from_group(sr.sc[tn], 16 * i + c);
-            const float nzs = -ScaleRegs<TN>::from_group(sr.zp[tn], 16 * i + c) * s;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) acc[tn][v] = fmaf(s, D[v], fmaf(nzs, X[v], acc[tn][v]));
+            for (int t = 0; t < 4; ++t)
+                xa[gi][t] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(xbuf, ((g0 + gi) * 4 + t) * 1024 + lane * 16, 0, 0));
+            X[gi] = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(ubuf, ((g0 + gi) * 2 + 0) * kTokens * 4 + q * 16, 0, 0));
+            XS[gi] = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(ubuf, ((g0 + gi) * 2 + 1) * kTokens * 4 + q * 16, 0, 0));
         }
-    };
-
-    // Activations come from L2 one group ahead, scales and zeros one chunk ahead, each in two register
-    // sets used alternately; loads past the last group re-read it and are dropped.
-    const int g_last = p.G - 1;
-    ScaleRegs<TN> sr[2];
-    SmallXRegs xr[2];
-    sr[0].load(p, sz, min(4 * wave + q, g_last));
-    xr[0].load(xl, min(4 * wave, g_last));
-    copy_chunk(0, 0);
-
-    auto chunk = [&](int ch, const ScaleRegs<TN> &sc_cur, ScaleRegs<TN> &sc_nxt) __attribute__((always_inline)) {
-        const unsigned char *cur = smem + (ch & 1) * kStageBytes;
-        __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this wave's copies of chunk ch have landed
-        __syncthreads();                                // ... and everybody's; everybody is done with the other stage
-        if (ch + 1 < chunks) copy_chunk(ch + 1, (ch + 1) & 1);   // block-uniform
-        const int g0 = ch * 16 + 4 * wave;              // this wave's four groups of the chunk
-        sc_nxt.load(p, sz, min(g0 + 16 + q, g_last));
+        SmallCodes<BITS> cw[T][kWaveGroups];
+        // Four fp16 scales / zeros, groups g0 .. g0 + 3 of the lane's row: they start at an even or an odd
+        // fp16 index, so three aligned words are loaded and shifted by a half where needed.
+        uint3_t sc[T], zp[T];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            // next group of this wave: the following one of the chunk, or the first of the next chunk
-            const int gn = i < 3 ? g0 + i + 1 : g0 + 16;
-            xr[(i + 1) & 1].load(xl, min(gn, g_last));
-            if (g0 + i < p.G) process(cur, i, sc_cur, xr[i & 1]);   // wave-uniform
+        for (int ti = 0; ti < T; ++ti) {
+#pragma unroll
+            for (int gi = 0; gi < kWaveGroups; ++gi) cw[ti][gi].load(qbuf, qrow[ti] + (g0 + gi) * 4 * kPiece, 0);
+            sc[ti] = __builtin_amdgcn_raw_buffer_load_b96(sbuf, (srow[ti] + g0 * 2) & ~3, 0, 0);
+            zp[ti] = __builtin_amdgcn_raw_buffer_load_b96(zbuf, (srow[ti] + g0 * 2) & ~3, 0, 0);
         }
-    };
-    int ch = 0;
-    for (; ch + 1 < chunks; ch += 2) {
-        chunk(ch, sr[0], sr[1]);
-        chunk(ch + 1, sr[1], sr[0]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ti = 0; ti < T; ++ti) {
+#pragma unroll
+            for (int gi = 0; gi < kWaveGroups; ++gi) {
+                half8_t b[4];
+                cw[ti][gi].operands(k6400, b);
+                float4_t D = zero4;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) D = mfma(xa[gi][t], b[t], D);
+                const float s = (float)half_at(sc[ti], gi + odd[ti]), z = (float)half_at(zp[ti], gi + odd[ti]);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[ti][v] = fmaf(s, D[v] - fmaf(z, X[gi][v], XS[gi][v]), acc[ti][v]);
+            }
+        }
     }
-    if (ch < chunks) chunk(ch, sr[0], sr[1]);
 
-    // K split: every wave leaves its tiles in LDS; wave tn adds them up for tile tn, folds the
+    // K split: every wave leaves its tiles in LDS; wave ti adds them up for tile ti, folds the
     // up-projection in and stores.
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) red[(wave * TN + tn) * 64 + lane] = acc[tn];
+    for (int ti = 0; ti < T; ++ti) red[wave][ti][lane] = acc[ti];
     __syncthreads();
-    for (int tn = wave; tn < TN; tn += kWaves) {        // wave-uniform
-        float4_t sum = red[tn * 64 + lane];
+    for (int ti = wave; ti < T; ti += kMainWaves) {     // wave-uniform
+        if (tile0 + ti >= ntiles) break;
+        float4_t sum = red[0][ti][lane];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) sum += red[(w * TN + tn) * 64 + lane];
+        for (int w = 1; w < kMainWaves; ++w) sum += red[w][ti][lane];
 
-        const int n = n0 + 16 * tn + c;
+        const int n = (tile0 + ti) * 16 + c;
         if (BRANCH) {
-            // t[token c][j], j = 32 js + 8 q .. + 7, from the slices' partial sums; B^T row of column n
+            // t[token c][j], j = 32 js + 8 q .. + 7, from the slices' partial sums; B^T row of output row n
             const uint16_t *brow = p.Bt + (size_t)min(n, p.N - 1) * p.r;
             for (int js = 0; js * 32 < p.r; ++js) {
                 const int j = js * 32 + q * 8;
@@ -348,47 +386,13 @@ __global__ __launch_bounds__(64 * kWaves) void fbq_gemv_mfma_kernel(const SmallP
                 sum = mfma(tlo, bf, sum);
             }
         }
-        // lane (c, q) holds column n and tokens 4 q + v
+        // lane (c, q) holds output row n and tokens 4 q + v
         if (n < p.N) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int m = 4 * q + v;
                 if (m < p.M) p.y[(size_t)m * p.N + n] = __builtin_bit_cast(uint16_t, (half_t)sum[v]);
             }
-        }
-    }
-}
-
-// Down-projection for up to 16 tokens: block (column tile of 16, K slice); the block's sixteen waves
-// take a sixteenth of the slice each.  partial[slice][token][j] = sum over the slice of
-// x[token][k] At[j][k]; token rows past M repeat the last token.
-constexpr int kDownWaves = 16;
-
-__global__ __launch_bounds__(64 * kDownWaves) void fbq_down_proj_small_kernel(const SmallParams p)
-{
-    __shared__ float4_t red[kDownWaves][64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c = lane & 15, q = lane >> 4;
-    const int j0 = blockIdx.x * 16, slice = blockIdx.y;
-    const int kw = p.kslice / kDownWaves;               // a multiple of 32
-    const int kbeg = slice * p.kslice + wave * kw;
-    const int kend = min(p.K, kbeg + kw);
-    const uint16_t *xr = p.x + (size_t)min(c, p.M - 1) * p.K + 8 * q;
-    const uint16_t *ar = p.At + (size_t)min(j0 + c, p.r - 1) * p.K + 8 * q;
-    float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll 8
-    for (int k = kbeg; k < kend; k += 32)
-        acc = mfma(*reinterpret_cast<const half8_t *>(xr + k), *reinterpret_cast<const half8_t *>(ar + k), acc);
-    red[wave][lane] = acc;
-    __syncthreads();
-    if (wave == 0) {
-        float4_t sum = red[0][lane];
-#pragma unroll
-        for (int w = 1; w < kDownWaves; ++w) sum += red[w][lane];
-        const int j = j0 + c;                           // lane (c, q) holds column j and tokens 4 q + v
-        if (j < p.r) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) p.tpart[((size_t)slice * kTokens + 4 * q + v) * p.r + j] = sum[v];
         }
     }
 }
@@ -404,56 +408,51 @@ static int cu_count()
     return cus;
 }
 
-template <int BITS, int TN>
-static hipError_t launch_variant(const SmallParams &p, hipStream_t stream)
+template <int BITS, int T>
+static hipError_t launch_tiles(const SmallParams &p, dim3 grid, hipStream_t stream)
 {
-    constexpr int lds = small_m_lds_bytes<BITS, TN>();
-    // more than 64 KiB of LDS per block has to be asked for, once per kernel (and device)
-    static const hipError_t prepared = [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fbq_gemv_mfma_kernel<BITS, TN, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fbq_gemv_mfma_kernel<BITS, TN, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        return e;
-    }();
-    if (prepared != hipSuccess) return prepared;
-    const dim3 grid(ceil_div(p.N, 16 * TN)), block(64 * kWaves);
-    if (p.r > 0) hipLaunchKernelGGL((fbq_gemv_mfma_kernel<BITS, TN, true>), grid, block, lds, stream, p);
-    else hipLaunchKernelGGL((fbq_gemv_mfma_kernel<BITS, TN, false>), grid, block, lds, stream, p);
+    if (p.r > 0) hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true>), grid, dim3(64 * kMainWaves), 0, stream, p);
+    else hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, false>), grid, dim3(64 * kMainWaves), 0, stream, p);
     return hipGetLastError();
 }
 
 template <int BITS>
 static hipError_t launch_bits(const SmallParams &p, hipStream_t stream)
 {
-    // Wider blocks re-read the activations less often; narrower ones give more blocks.  Take the
-    // widest that still leaves two blocks per CU.
-    const int want = 2 * cu_count();
-    if (ceil_div(p.N, 64) >= want) return launch_variant<BITS, 4>(p, stream);
-    if (ceil_div(p.N, 32) >= want) return launch_variant<BITS, 2>(p, stream);
-    return launch_variant<BITS, 1>(p, stream);
+    const int arrange_blocks = ceil_div(p.G, kPrepWaves);
+    hipLaunchKernelGGL(fbq_small_m_prepare_kernel<BITS>, dim3(p.down_blocks + arrange_blocks), dim3(64 * kPrepWaves), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 grid(ceil_div(ceil_div(p.N, 16), p.tiles_per_block));
+    switch (p.tiles_per_block) {
+    case 1: return launch_tiles<BITS, 1>(p, grid, stream);
+    case 2: return launch_tiles<BITS, 2>(p, grid, stream);
+    default: return launch_tiles<BITS, 3>(p, grid, stream);
+    }
 }
 
-// workspace: [slices][16][r] fp32 partial sums of t
-size_t small_m_workspace_bytes(int r) { return (size_t)kMaxSlices * kTokens * r * sizeof(float); }
+// workspace: [slices][16][r] fp32 partial sums of t, [G][2][16] fp32 sums, [G][4][64] 16-byte operands
+static size_t tpart_bytes(int r) { return (size_t)kMaxSlices * kTokens * r * sizeof(float); }
+static size_t xsum_bytes(int K) { return (size_t)(K / kGroup) * 2 * kTokens * sizeof(float); }
+size_t small_m_workspace_bytes(int K, int r) { return tpart_bytes(r) + xsum_bytes(K) + (size_t)(K / kGroup) * 4 * 64 * 16; }
 
 hipError_t launch_gemv_small_m(const LinearArgs &a, hipStream_t stream)
 {
     if (a.M < 1 || a.M > kTokens) return hipErrorInvalidValue;
     SmallParams p;
     p.qw = a.qw; p.scales = a.scales; p.zeros = a.zeros; p.At = a.At; p.Bt = a.Bt; p.x = a.x; p.y = a.y;
-    p.tpart = (float *)a.workspace;
+    unsigned char *ws = (unsigned char *)a.workspace;
+    p.tpart = (float *)ws;
+    p.xsum = (float *)(ws + tpart_bytes(a.r));
+    p.xop = (uint4 *)(ws + tpart_bytes(a.r) + xsum_bytes(a.K));
     p.M = a.M; p.N = a.N; p.K = a.K; p.r = a.r;
     p.row_words = (int)row_words(a.K, a.bits);
     p.G = a.K / kGroup;
-    p.kslice = ceil_div(ceil_div(a.K, kMaxSlices), 32 * kDownWaves) * (32 * kDownWaves);
+    p.kslice = ceil_div(ceil_div(a.K, kMaxSlices), 32 * kPrepWaves) * (32 * kPrepWaves);
     p.slices = ceil_div(a.K, p.kslice);
-    if (a.r > 0) {
-        hipLaunchKernelGGL(fbq_down_proj_small_kernel, dim3(ceil_div(a.r, 16), p.slices), dim3(64 * kDownWaves), 0, stream, p);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
+    p.down_blocks = a.r > 0 ? ceil_div(a.r, 16) * p.slices : 0;
+    // one block per compute unit where the layer has that many tiles, at most kMaxTiles tiles each
+    p.tiles_per_block = std::min(kMaxTiles, std::max(1, ceil_div(ceil_div(a.N, 16), cu_count())));
     return a.bits == 4 ? launch_bits<4>(p, stream) : launch_bits<3>(p, stream);
 }
 

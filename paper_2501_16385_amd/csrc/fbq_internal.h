@@ -52,7 +52,7 @@ hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t 
                            uint16_t *scales, uint16_t *zeros, hipStream_t stream);
 
 size_t decode_workspace_bytes(int M, int K, int r);
-size_t small_m_workspace_bytes(int r);
+size_t small_m_workspace_bytes(int K, int r);
 size_t prefill_workspace_bytes(int M, int K, int r);
 
 }  // namespace fbq
