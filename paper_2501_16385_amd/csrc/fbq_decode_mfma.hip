@@ -38,6 +38,16 @@
 
 #include "fbq_internal.h"
 
+#ifndef FBQ_EXP
+#define FBQ_EXP 0
+#endif
+#ifdef FBQ_TRACE
+extern __device__ long long *fbq_trace_buf;
+#define FBQ_STAMP(slot) do { if ((threadIdx.x & 63) == 0) fbq_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + (slot)] = wall_clock64(); } while (0)
+#else
+#define FBQ_STAMP(slot) do { } while (0)
+#endif
+
 namespace fbq {
 
 typedef _Float16 half_t;
@@ -49,7 +59,6 @@ typedef uint32_t uint3_t __attribute__((ext_vector_type(3)));
 typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kTokens = 16;          // rows of the matrix-core tile; M is padded up to it
-constexpr int kMaxSlices = 4;        // K slices of the down-projection
 constexpr int kMainWaves = 8;        // waves per block of the fused kernel; they split K
 constexpr int kWaveGroups = 4;       // consecutive quantization groups a wave takes per pass over the block's tiles
 constexpr int kPassGroups = kMainWaves * kWaveGroups;   // groups one pass covers (4096 codes)
@@ -77,12 +86,12 @@ struct SmallParams {
     const uint16_t *Bt;    // [N][r]
     const uint16_t *x;     // [M][K]
     uint16_t *y;           // [M][N]
-    float *tpart;          // workspace: [slices][16][r] partial sums of t
+    float *tpart;          // workspace: [slices][16][r] partial sums of t = x.A, one per K slice of the down-projection
     float *xsum;           // workspace: [G][2][16]: X = sum x and XS = 1024 sum x' per group and token
     uint4 *xop;            // workspace: [G][4][64] 16-byte activation operands
     int M, N, K, r;
     int row_words, G;
-    int slices, kslice;    // down-projection: number of K slices and their length (a multiple of 128)
+    int slices, kslice;    // down-projection: number of K slices and their length (a multiple of 512)
     int down_blocks;       // blocks of the preparation launch that do the down-projection; the rest arrange x
     int tiles_per_block;   // 16-row tiles a block of the fused kernel owns
 };
@@ -163,9 +172,10 @@ __device__ __forceinline__ half_t half_at(uint3_t w, int i)
 
 constexpr int kPrepWaves = 16;
 
-// Down-projection for up to 16 tokens: block (column tile of 16, K slice); the block's sixteen waves
-// take a sixteenth of the slice each.  partial[slice][token][j] = sum over the slice of
-// x[token][k] At[j][k]; token rows past M repeat the last token.
+// Down-projection for up to 16 tokens: block b = (K slice, column tile of 16); the block's sixteen
+// waves take a sixteenth of the slice each.  partial[slice][token][j] = sum over the slice of
+// x[token][k] At[j][k]; token rows past M repeat the last token.  The slices only exist to put more
+// compute units to work on this short, latency-bound step; the fused kernel adds them up.
 __device__ void down_proj_block(const SmallParams &p, int b, float4_t (*red)[64])
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -268,6 +278,7 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
     constexpr int kPiece = BITS == 4 ? 16 : 12;         // bytes of 32 codes
     __shared__ float4_t red[kMainWaves][T][64];
 
+    FBQ_STAMP(0);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 15, q = lane >> 4;
@@ -286,10 +297,33 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
 #pragma unroll
     for (int ti = 0; ti < T; ++ti) {
         const int n = min((tile0 + ti) * 16 + c, p.N - 1);
+#if FBQ_EXP == 4     /* timing only: the same bytes, fetched as contiguous kilobytes */
+        qrow[ti] = (tile0 + ti) * 16 * row_bytes + lane * kPiece - wave * kWaveGroups * 4 * kPiece + wave * kWaveGroups * 64 * kPiece;
+#else
         qrow[ti] = n * row_bytes + q * kPiece;
+#endif
         srow[ti] = n * p.G * 2;
         odd[ti] = (n * p.G) & 1;                        // the wave's first group is a multiple of four
     }
+
+    // Up-projection: r more values of k, in units of (tile, 32 taps) dealt out to the waves.  Lane (c, q)
+    // needs t[token c][j .. j + 7] and Bt[row c of the tile][j .. j + 7], j = 32 js + 8 q; taps past r read
+    // beyond the buffers, i.e. zeros.  The Bt part of the wave's first unit (cold, from HBM) is requested
+    // here with everything else; t (a few KB that every block reads) is fetched when it is needed.
+    const int tap_steps = BRANCH ? (p.r + 31) / 32 : 0;
+    const int units = T * tap_steps;
+    const __amdgpu_buffer_rsrc_t tbuf = buffer_of(p.tpart, BRANCH ? (long)p.slices * kTokens * p.r * 4 : 0);
+    const __amdgpu_buffer_rsrc_t bbuf = buffer_of(p.Bt, BRANCH ? (long)p.N * p.r * 2 : 0);
+    constexpr int kNowhere = 0x7FFFFFF0;                // beyond every buffer
+    half8_t ubf;
+    auto request_taps = [&](int u) __attribute__((always_inline)) {
+        const int ti = u / max(tap_steps, 1), js = u - ti * tap_steps;
+        const int j = js * 32 + q * 8;
+        const bool on = u < units && j < p.r;          // r is a multiple of 8: all eight taps or none
+        const int n = min((tile0 + ti) * 16 + c, p.N - 1);
+        ubf = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(bbuf, on ? (n * p.r + j) * 2 : kNowhere, 0, 0));
+    };
+    if (BRANCH) request_taps(wave);
 
     uint32_t k6400 = 0x64006400u;
     asm volatile("" : "+v"(k6400));                     // keep the constant in a VGPR for v_and_or_b32
@@ -307,8 +341,26 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
     const int passes = (p.G + kPassGroups - 1) / kPassGroups;
     for (int pass = 0; pass < passes; ++pass) {
         const int g0 = pass * kPassGroups + wave * kWaveGroups;
+        // Order of the requests: the first tile's weights, then the activations, then the other tiles -
+        // the weights are the long pole (HBM), so some are under way before the block's share of the
+        // activations (L2) occupies the load path, and the first tile can be worked on while the rest streams.
         half8_t xa[kWaveGroups][4];
         float4_t X[kWaveGroups], XS[kWaveGroups];
+        SmallCodes<BITS> cw[T][kWaveGroups];
+        // Four fp16 scales / zeros, groups g0 .. g0 + 3 of the lane's row: they start at an even or an odd
+        // fp16 index, so three aligned words are loaded and shifted by a half where needed.
+        uint3_t sc[T], zp[T];
+        auto request_tile = [&](int ti) __attribute__((always_inline)) {
+#if FBQ_EXP == 4
+            for (int gi = 0; gi < kWaveGroups; ++gi) cw[ti][gi].load(qbuf, qrow[ti] + g0 * 4 * kPiece + gi * 64 * kPiece, 0);
+#else
+#pragma unroll
+            for (int gi = 0; gi < kWaveGroups; ++gi) cw[ti][gi].load(qbuf, qrow[ti] + (g0 + gi) * 4 * kPiece, 0);
+#endif
+            sc[ti] = __builtin_amdgcn_raw_buffer_load_b96(sbuf, (srow[ti] + g0 * 2) & ~3, 0, 0);
+            zp[ti] = __builtin_amdgcn_raw_buffer_load_b96(zbuf, (srow[ti] + g0 * 2) & ~3, 0, 0);
+        };
+        request_tile(0);
 #pragma unroll
         for (int gi = 0; gi < kWaveGroups; ++gi) {
 #pragma unroll
@@ -317,20 +369,15 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
             X[gi] = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(ubuf, ((g0 + gi) * 2 + 0) * kTokens * 4 + q * 16, 0, 0));
             XS[gi] = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(ubuf, ((g0 + gi) * 2 + 1) * kTokens * 4 + q * 16, 0, 0));
         }
-        SmallCodes<BITS> cw[T][kWaveGroups];
-        // Four fp16 scales / zeros, groups g0 .. g0 + 3 of the lane's row: they start at an even or an odd
-        // fp16 index, so three aligned words are loaded and shifted by a half where needed.
-        uint3_t sc[T], zp[T];
 #pragma unroll
-        for (int ti = 0; ti < T; ++ti) {
-#pragma unroll
-            for (int gi = 0; gi < kWaveGroups; ++gi) cw[ti][gi].load(qbuf, qrow[ti] + (g0 + gi) * 4 * kPiece, 0);
-            sc[ti] = __builtin_amdgcn_raw_buffer_load_b96(sbuf, (srow[ti] + g0 * 2) & ~3, 0, 0);
-            zp[ti] = __builtin_amdgcn_raw_buffer_load_b96(zbuf, (srow[ti] + g0 * 2) & ~3, 0, 0);
-        }
+        for (int ti = 1; ti < T; ++ti) request_tile(ti);
+        FBQ_STAMP(1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ti = 0; ti < T; ++ti) {
+#ifdef FBQ_TRACE
+            if (ti == 1) { asm volatile("" : "+v"(acc[0][0])); FBQ_STAMP(2); }
+#endif
 #pragma unroll
             for (int gi = 0; gi < kWaveGroups; ++gi) {
                 half8_t b[4];
@@ -345,47 +392,50 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
         }
     }
 
-    // K split: every wave leaves its tiles in LDS; wave ti adds them up for tile ti, folds the
-    // up-projection in and stores.
+#ifdef FBQ_TRACE
+    asm volatile("" : "+v"(acc[T - 1][0])); FBQ_STAMP(3);
+#endif
+    if (BRANCH) {
+        for (int u = wave; u < units; u += kMainWaves) {   // wave-uniform; the first unit's Bt operand is already here
+            const int ti = u / tap_steps, js = u - ti * tap_steps;
+            const int j = js * 32 + q * 8;
+            float t[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) t[e] = 0.0f;
+            for (int sl = 0; sl < p.slices; ++sl) {
+                const int off = j < p.r ? ((sl * kTokens + c) * p.r + j) * 4 : kNowhere;
+                const float4_t lo = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(tbuf, off, 0, 0));
+                const float4_t hi = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(tbuf, off + 16, 0, 0));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { t[e] += lo[e]; t[4 + e] += hi[e]; }
+            }
+            half8_t thi, tlo;                           // t_hi + t_lo carries 22 bits of the fp32 sum
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                thi[e] = (half_t)t[e];
+                tlo[e] = (half_t)(t[e] - (float)thi[e]);
+            }
+            float4_t d = mfma(thi, ubf, zero4);
+            d = mfma(tlo, ubf, d);
+#pragma unroll
+            for (int k = 0; k < T; ++k)
+                if (k == ti) acc[k] += d;
+            if (u + kMainWaves < units) request_taps(u + kMainWaves);
+        }
+    }
+
+    // K split: every wave leaves its tiles in LDS; wave ti adds them up for tile ti and stores.
 #pragma unroll
     for (int ti = 0; ti < T; ++ti) red[wave][ti][lane] = acc[ti];
+    FBQ_STAMP(4);
     __syncthreads();
+    FBQ_STAMP(5);
     for (int ti = wave; ti < T; ti += kMainWaves) {     // wave-uniform
         if (tile0 + ti >= ntiles) break;
         float4_t sum = red[0][ti][lane];
 #pragma unroll
         for (int w = 1; w < kMainWaves; ++w) sum += red[w][ti][lane];
-
         const int n = (tile0 + ti) * 16 + c;
-        if (BRANCH) {
-            // t[token c][j], j = 32 js + 8 q .. + 7, from the slices' partial sums; B^T row of output row n
-            const uint16_t *brow = p.Bt + (size_t)min(n, p.N - 1) * p.r;
-            for (int js = 0; js * 32 < p.r; ++js) {
-                const int j = js * 32 + q * 8;
-                half8_t thi, tlo, bf;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) { thi[e] = (half_t)0.0f; tlo[e] = (half_t)0.0f; bf[e] = (half_t)0.0f; }
-                if (j < p.r) {                          // r is a multiple of 8: all eight taps or none
-                    float t[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) t[e] = 0.0f;
-                    for (int sl = 0; sl < p.slices; ++sl) {
-                        const float4 *src = reinterpret_cast<const float4 *>(p.tpart + ((size_t)sl * kTokens + c) * p.r + j);
-                        const float4 lo = src[0], hi = src[1];
-                        t[0] += lo.x; t[1] += lo.y; t[2] += lo.z; t[3] += lo.w;
-                        t[4] += hi.x; t[5] += hi.y; t[6] += hi.z; t[7] += hi.w;
-                    }
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        thi[e] = (half_t)t[e];
-                        tlo[e] = (half_t)(t[e] - (float)thi[e]);
-                    }
-                    bf = *reinterpret_cast<const half8_t *>(brow + j);
-                }
-                sum = mfma(thi, bf, sum);
-                sum = mfma(tlo, bf, sum);
-            }
-        }
         // lane (c, q) holds output row n and tokens 4 q + v
         if (n < p.N) {
 #pragma unroll
@@ -395,6 +445,7 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
             }
         }
     }
+    FBQ_STAMP(6);
 }
 
 static int cu_count()
@@ -432,6 +483,7 @@ static hipError_t launch_bits(const SmallParams &p, hipStream_t stream)
 }
 
 // workspace: [slices][16][r] fp32 partial sums of t, [G][2][16] fp32 sums, [G][4][64] 16-byte operands
+constexpr int kMaxSlices = 4;        // K slices of the down-projection
 static size_t tpart_bytes(int r) { return (size_t)kMaxSlices * kTokens * r * sizeof(float); }
 static size_t xsum_bytes(int K) { return (size_t)(K / kGroup) * 2 * kTokens * sizeof(float); }
 size_t small_m_workspace_bytes(int K, int r) { return tpart_bytes(r) + xsum_bytes(K) + (size_t)(K / kGroup) * 4 * 64 * 16; }
