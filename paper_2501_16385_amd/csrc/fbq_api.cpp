@@ -29,6 +29,8 @@ extern "C" fbq_status fbq_check_desc(const fbq_desc *d)
     if (d->N < 1 || d->K < 1 || d->r < 0) return FBQ_ERR_SHAPE;
     if (d->K % d->group || d->K % 32 || d->r % 8) return FBQ_ERR_SHAPE;
     if (d->r > kMaxRank || d->K > kMaxK) return FBQ_ERR_UNSUPPORTED;
+    // the kernels address a layer's buffers with 32-bit byte offsets and keep 2^30 as "nowhere"
+    if ((size_t)d->N * row_words(d->K, d->bits) * sizeof(uint32_t) >= ((size_t)1 << 30)) return FBQ_ERR_UNSUPPORTED;
     return FBQ_OK;
 }
 

@@ -33,7 +33,6 @@
 // its accumulator scaled by 2^(24-o) once per 32 codes.  The group's scale and zero are applied
 // once per lane and chunk:  s * (sum q.x - z * sum x).
 #include <hip/hip_fp16.h>
-#include <stdlib.h>
 
 
 
@@ -41,9 +40,6 @@
 
 // Timing builds only (never defined for the library): per-wave wall-clock stamps (100 MHz) into a buffer the
 // timing harness owns.
-#ifndef FBQ_EXP
-#define FBQ_EXP 0
-#endif
 #ifdef FBQ_TRACE
 extern __device__ long long *fbq_trace_buf;
 #define FBQ_STAMP(slot) do { if ((threadIdx.x & 63) == 0) fbq_trace_buf[((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 8 + (slot)] = wall_clock64(); } while (0)
@@ -570,23 +566,21 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     float acc0[ROWS], acc1[ROWS];
     auto step = [&](RowTile<BITS, CPW, ROWS> &T, float (&acc)[ROWS], float (&acc_prev)[ROWS], uint32_t (&bt_mine)[ROWS][kRI],
                     uint32_t (&bt_prev)[ROWS][kRI], int j, int tile) __attribute__((always_inline)) {
-        if (RI > 0 && wave == 0 && !have_t && (j > 0 || trips == 1)) {
-            __builtin_amdgcn_sched_barrier(0);
-            request_t();
-            __builtin_amdgcn_sched_barrier(0);
-        }
         // main path: de-quantize and multiply; clamped lanes hold zero activations and add nothing
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) {
+            // t is asked for as late as possible - when the tile's first row has arrived and its arithmetic
+            // is about to start - so that the answer is still fresh when the tile is done
+            if (i == 1 && RI > 0 && wave == 0 && !have_t && (j > 0 || trips == 1)) {
+                asm volatile("" : "+v"(acc[0]));
+                __builtin_amdgcn_sched_barrier(0);
+                request_t();
+                __builtin_amdgcn_sched_barrier(0);
+            }
             float a = 0.0f;
 #pragma unroll
             for (int c = 0; c < CPW; ++c) {
-#if FBQ_EXP == 3
-                float qx = 0.0f;
-                for (int w = 0; w < RowTile<BITS, CPW, ROWS>::kLaneWords; ++w) qx += __builtin_bit_cast(float, T.cw[i][c].w[w] & 0x3fffffffu);
-#else
                 const float qx = T.cw[i][c].dot(xf[c].p);
-#endif
                 const float s = (float)__builtin_bit_cast(half_t, (uint16_t)T.sc[i][c]);
                 const float z = (float)__builtin_bit_cast(half_t, (uint16_t)T.zp[i][c]);
                 a = fmaf(s, fmaf(-z, xf[c].sum, qx), a);
@@ -726,14 +720,11 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
     }
     const int row_sets = 4 / v.ks;
     // Blocks to share out: two per CU keeps enough bytes in flight; a token dimension multiplies the grid.
-    int per_cu = 2;
-    if (const char *e = getenv("FBQ_TUNE_BLOCKS_PER_CU")) per_cu = std::max(1, atoi(e));   // TEMP tuning hook
-    const int budget = std::max(1, per_cu * device_cu_count() / std::max(1, std::min(M, 2)));
+    const int budget = std::max(1, 2 * device_cu_count() / std::max(1, std::min(M, 2)));
     // Tiles of 4 rows when that still leaves every wave at least one tile, and registers allow; else 2.
     long tiles4 = 0;
     for (int i = 0; i < n_layers; ++i) tiles4 += ceil_div(layers[i].N, 4);
-    int rows = (v.cpw == 1 && tiles4 >= (long)budget * row_sets) ? 4 : 2;
-    if (const char *e = getenv("FBQ_TUNE_ROWS")) rows = atoi(e) == 4 ? 4 : 2;   // TEMP tuning hook
+    const int rows = (v.cpw == 1 && tiles4 >= (long)budget * row_sets) ? 4 : 2;
 
     // Persistent consumer blocks have fixed tile lists, so every one of them must be resident from the
     // start: the producers take their block slots out of the same budget.
@@ -757,9 +748,6 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
         const int max_blocks = ceil_div(ceil_div(a.N, rows), row_sets);
         const int share = (int)(consumer_budget * ((double)a.N * a.K / total_work));
         p.blocks = std::max(1, std::min(max_blocks, share));
-        // the fewest blocks that need no more trips than that: every wave then makes (almost) the same
-        // number of trips, and the last trip is as wide as the others
-        if (getenv("FBQ_TUNE_EVEN")) p.blocks = ceil_div(max_blocks, ceil_div(max_blocks, p.blocks));
         g.block_begin[i] = next_block;
         next_block += p.producers + p.blocks;
     }

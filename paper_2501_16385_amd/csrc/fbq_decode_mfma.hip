@@ -38,9 +38,6 @@
 
 #include "fbq_internal.h"
 
-#ifndef FBQ_EXP
-#define FBQ_EXP 0
-#endif
 #ifdef FBQ_TRACE
 extern __device__ long long *fbq_trace_buf;
 #define FBQ_STAMP(slot) do { if ((threadIdx.x & 63) == 0) fbq_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + (slot)] = wall_clock64(); } while (0)
@@ -297,11 +294,7 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
 #pragma unroll
     for (int ti = 0; ti < T; ++ti) {
         const int n = min((tile0 + ti) * 16 + c, p.N - 1);
-#if FBQ_EXP == 4     /* timing only: the same bytes, fetched as contiguous kilobytes */
-        qrow[ti] = (tile0 + ti) * 16 * row_bytes + lane * kPiece - wave * kWaveGroups * 4 * kPiece + wave * kWaveGroups * 64 * kPiece;
-#else
         qrow[ti] = n * row_bytes + q * kPiece;
-#endif
         srow[ti] = n * p.G * 2;
         odd[ti] = (n * p.G) & 1;                        // the wave's first group is a multiple of four
     }
@@ -341,6 +334,7 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
     const int passes = (p.G + kPassGroups - 1) / kPassGroups;
     for (int pass = 0; pass < passes; ++pass) {
         const int g0 = pass * kPassGroups + wave * kWaveGroups;
+        // Token rows past M are all zero and are not fetched (their lanes aim beyond the buffer).
         // Order of the requests: the first tile's weights, then the activations, then the other tiles -
         // the weights are the long pole (HBM), so some are under way before the block's share of the
         // activations (L2) occupies the load path, and the first tile can be worked on while the rest streams.
@@ -351,12 +345,8 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
         // fp16 index, so three aligned words are loaded and shifted by a half where needed.
         uint3_t sc[T], zp[T];
         auto request_tile = [&](int ti) __attribute__((always_inline)) {
-#if FBQ_EXP == 4
-            for (int gi = 0; gi < kWaveGroups; ++gi) cw[ti][gi].load(qbuf, qrow[ti] + g0 * 4 * kPiece + gi * 64 * kPiece, 0);
-#else
 #pragma unroll
             for (int gi = 0; gi < kWaveGroups; ++gi) cw[ti][gi].load(qbuf, qrow[ti] + (g0 + gi) * 4 * kPiece, 0);
-#endif
             sc[ti] = __builtin_amdgcn_raw_buffer_load_b96(sbuf, (srow[ti] + g0 * 2) & ~3, 0, 0);
             zp[ti] = __builtin_amdgcn_raw_buffer_load_b96(zbuf, (srow[ti] + g0 * 2) & ~3, 0, 0);
         };
@@ -365,7 +355,7 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
         for (int gi = 0; gi < kWaveGroups; ++gi) {
 #pragma unroll
             for (int t = 0; t < 4; ++t)
-                xa[gi][t] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(xbuf, ((g0 + gi) * 4 + t) * 1024 + lane * 16, 0, 0));
+                xa[gi][t] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(xbuf, c < p.M ? ((g0 + gi) * 4 + t) * 1024 + lane * 16 : kNowhere, 0, 0));
             X[gi] = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(ubuf, ((g0 + gi) * 2 + 0) * kTokens * 4 + q * 16, 0, 0));
             XS[gi] = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(ubuf, ((g0 + gi) * 2 + 1) * kTokens * 4 + q * 16, 0, 0));
         }
