@@ -91,6 +91,25 @@ def make_x(spec: LayerSpec, M: int, config: int, layer_index: int) -> np.ndarray
     return _normal_f16(_rng(config, layer_index, 3), (M, spec.K), 1.0)
 
 
+def make_random_quantized(spec: LayerSpec, config: int, layer_index: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Stand-in for a quantized layer that is too large to push through the fp64 quantizer in a test:
+    uniformly random codes [N, K] (uint8, 0 .. 2^bits - 1), fp16 scales in the range the quantizer
+    produces for N(0, w_std^2) weights with outliers, fp16 zero points around the middle of the code
+    range.  (The kernels' work does not depend on how the codes came about.)"""
+    qmax = (1 << spec.bits) - 1
+    rng_c, rng_s, rng_z = _rng(config, layer_index, 5), _rng(config, layer_index, 6), _rng(config, layer_index, 7)
+    G = spec.K // spec.group
+    codes = np.empty((spec.N, spec.K), dtype=np.uint8)
+    step = max(1, (1 << 24) // spec.K)
+    for r0 in range(0, spec.N, step):
+        r1 = min(spec.N, r0 + step)
+        codes[r0:r1] = rng_c.integers(0, qmax + 1, (r1 - r0, spec.K), dtype=np.uint8)
+    span = np.float32(spec.w_std) * (5.0 + 25.0 * rng_s.random((spec.N, G), dtype=np.float32) ** 8)   # mostly ~5 sigma, some outlier groups
+    scales = (span / np.float32(qmax)).astype(np.float16)
+    zeros = (np.float32(0.5 * qmax) + (rng_z.random((spec.N, G), dtype=np.float32) - 0.5) * np.float32(0.5 * qmax)).astype(np.float16)
+    return codes, scales, zeros
+
+
 def make_layer(spec: LayerSpec, M: int, config: int = 0, layer_index: int = 0) -> Dict[str, np.ndarray]:
     A, B = make_branch(spec, config, layer_index)
     return {"W": make_weight(spec, config, layer_index), "A": A, "B": B,

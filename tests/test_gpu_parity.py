@@ -124,6 +124,55 @@ def test_benchmark_layers_full_size(config):
         assert err <= Y_TOL, f"{spec.name}: rel L2 {err:.3e}"
 
 
+def test_int3_llama_shapes_every_token_count_sampled_rows():
+    """Config 2 (INT3, rank 64, M in {1, 4, 8, 16}) at full size: the three distinct shapes of the layer
+    set, each token count through the launch configuration it gets in production (per-token GEMV,
+    few-token matrix-core kernel); the oracle recomputes 160 sampled output rows for all 16 tokens."""
+    specs, Ms = fbq_synth.config_layers(2)
+    rng = np.random.Generator(np.random.Philox(35))
+    seen = set()
+    for li, spec in enumerate(specs):
+        if (spec.N, spec.K) in seen:
+            continue
+        seen.add((spec.N, spec.K))
+        L = make_oracle_layer(spec, config=2, layer_index=li)
+        x = fbq_synth.make_x(spec, max(Ms), 2, li)
+        rows = np.sort(rng.choice(spec.N, 160, replace=False))
+        want = orc.linear(x, L.words[rows], L.scales[rows], L.zeros[rows], L.A, np.ascontiguousarray(L.B[:, rows]),
+                          spec.bits, spec.group)
+        dev = to_device_layer(L)
+        for M in Ms:
+            got = gpu_y(dev, np.ascontiguousarray(x[:M]))
+            assert got.shape == (M, spec.N) and np.all(np.isfinite(got))
+            for m in range(M):
+                err = rel_l2(got[m, rows], want[m])
+                assert err <= Y_TOL, f"{spec.name}, M={M}, token {m}: rel L2 {err:.3e}"
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K", [(13824, 5120), (5120, 13824), (28672, 8192), (8192, 28672)])
+def test_large_layer_sweep_sampled_rows(bits, N, K):
+    """Config 4 (rank 128, M in {1, 16, 256}) at full size.  These layers are too large for the fp64
+    quantizer inside a test, so seeded random codes, scales and zeros stand in for a quantized layer;
+    all three kernel families run on them and the oracle recomputes 96 sampled output rows."""
+    import paper_2501_16385_amd as fbq
+    spec = spec_of(N, K, 128, bits, w_std=0.015)
+    codes, s, z = fbq_synth.make_random_quantized(spec, 4, bits)
+    A, B = fbq_synth.make_branch(spec, 4, bits)
+    x = fbq_synth.make_x(spec, 256, 4, bits)
+    rng = np.random.Generator(np.random.Philox(36 + bits))
+    rows = np.sort(rng.choice(N, 96, replace=False))
+    want = orc.linear(x, orc.pack(codes[rows], bits), s[rows], z[rows], A, np.ascontiguousarray(B[:, rows]), bits, spec.group)
+    dev = fbq.upload_layer(fbq.pack(fbq.Desc(N, K, 128, bits), codes, s, z, A, B))
+    for M in (1, 16, 256):
+        got = gpu_y(dev, np.ascontiguousarray(x[:M]))
+        assert got.shape == (M, N) and np.all(np.isfinite(got))
+        err = rel_l2(got[:, rows], want[:M])
+        assert err <= Y_TOL, f"M={M}: rel L2 {err:.3e}"
+        worst = max(rel_l2(got[m, rows], want[m]) for m in range(M))
+        assert worst <= 2 * Y_TOL, f"M={M}: worst token rel L2 {worst:.3e}"
+
+
 # ------------------------------------------------------------------ reconstruct / quantize
 
 @pytest.mark.parametrize("bits", [4, 3])
