@@ -44,6 +44,7 @@ def parse_args():
     ap.add_argument("--M", type=int, default=0, help="tokens (default: first M of the configuration)")
     ap.add_argument("--copies", type=int, default=0, help="distinct copies of the layer set (default: > 2 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-kernels", action="store_true", help="skip the context timings of the few-token and prefill kernels")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()
 
@@ -273,6 +274,20 @@ def main():
                      "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "avg_launch_us": round(ms_dom * 1e3, 3), "bytes_per_launch": dom_bytes},
     }
+    if not args.no_other_kernels:
+        # Context, not part of `value`: the other two kernel families on the widest layer shape of the set
+        # (random packed words, same rotation protocol; see paper_2501_16385_amd/perf.py).
+        from paper_2501_16385_amd import perf
+        wide = max(specs, key=lambda s: s.N * s.K)
+        del sets
+        torch.cuda.empty_cache()
+        fam = {}
+        for name, m in (("few_token_M16", 16), ("few_token_M4", 4), ("prefill_M1024", 1024)):
+            t = perf.time_layer(wide.N, wide.K, wide.r, wide.bits, m, iters=200 if m <= 16 else 50, warmup=20)
+            fam[name] = {"shape": f"{wide.K}->{wide.N}", "us": t["us"], "GBps": t["GBps"], "TFLOPps": t["TFLOPps"],
+                         "frac_of_hbm_peak": round(t["GBps"] / HBM_PEAK_GBS, 4),
+                         "frac_of_fp16_mfma_peak": round(t["TFLOPps"] / 2500.0, 4)}
+        out["other_kernel_families"] = fam
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, args.config, M, args.cpu_seconds)
     print(json.dumps(out))
