@@ -50,7 +50,7 @@ typedef enum {
     FBQ_OK = 0,
     FBQ_ERR_NULL = 1,        /* a required pointer is NULL */
     FBQ_ERR_SHAPE = 2,       /* N, K, M < 1; r < 0; K % group; K % 32; r % 8; a code above qmax */
-    FBQ_ERR_UNSUPPORTED = 3, /* bits not in {3, 4}; group != 128; r > 256; K > 32768 */
+    FBQ_ERR_UNSUPPORTED = 3, /* bits not in {3, 4}; group != 128; r > 256; K > 32768; packed codes of 1 GiB or more */
     FBQ_ERR_ALIGN = 4,       /* a device pointer is not 16-byte aligned */
     FBQ_ERR_WORKSPACE = 5,   /* workspace smaller than fbq_workspace_bytes() */
     FBQ_ERR_HIP = 6          /* the HIP runtime refused a launch (hipGetLastError) */
@@ -75,11 +75,12 @@ fbq_status fbq_check_desc(const fbq_desc *d);
 /* Bytes of the packed code buffer, N * K * bits / 8.  0 for an invalid descriptor. */
 size_t fbq_packed_bytes(const fbq_desc *d);
 
-/* Bytes of device scratch fbq_linear needs for M tokens.  M <= 4: the down-projection t = x.A on its
- * way from the blocks that compute it to the blocks that use it, as tagged 8-byte words.  5 <= M <= 16:
- * fp32 partial sums of t.  Both are 0 when r == 0.  M > 16: the activations re-ordered for the matrix
- * cores (M rounded up to 128 rows of K fp16), t as two fp16 halves and its partial sums; not 0 even
- * when r == 0.  0 for an invalid descriptor or M < 1. */
+/* Bytes of device scratch fbq_linear needs for M tokens.  M <= 3: the down-projection t = x.A on its
+ * way from the blocks that compute it to the blocks that use it, as tagged 8-byte words (0 when
+ * r == 0).  4 <= M <= 16: the activations as matrix-core operands (16 token rows of K fp16), their
+ * per-group sums, and fp32 partial sums of t; not 0 even when r == 0.  M > 16: the activations
+ * re-ordered for the matrix cores (M rounded up to 128 rows of K fp16), t as two fp16 halves and its
+ * partial sums; not 0 even when r == 0.  0 for an invalid descriptor or M < 1. */
 size_t fbq_workspace_bytes(const fbq_desc *d, int M);
 
 /*
@@ -101,11 +102,12 @@ fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *sca
 /*
  * fbq_linear - the hot path (Sec. 4.3).  y[m,n] = sum_k x[m,k] * s[n,k/g] * (q[n,k] - z[n,k/g])
  *                                               + sum_j (sum_k x[m,k] * At[j,k]) * Bt[n,j]
- * in fp32 accumulation, rounded once to fp16.  M <= 4 runs the decode GEMV in ONE launch per token
+ * in fp32 accumulation, rounded once to fp16.  M <= 3 runs the decode GEMV in ONE launch per token
  * count (packed words streamed once per token, unpacked in registers; the down-projection runs in a
- * few producer blocks of the same launch).  5 <= M <= 16 streams the packed words once for all
- * tokens against a 16-token matrix-core tile, after a small down-projection launch.  M > 16 runs
- * the fp16 MFMA GEMM after a pass that re-orders x and a separate down-projection.
+ * few producer blocks of the same launch).  4 <= M <= 16 streams the packed words once for all
+ * tokens against a 16-token matrix-core tile, after a small launch that does the down-projection
+ * and writes the activations as matrix operands.  M > 16 runs the fp16 MFMA GEMM after a pass that
+ * re-orders x and a separate down-projection.
  *   x         device [M, K] fp16             qweight, scales, zeros, At, Bt: device, layout above
  *   y         device [M, N] fp16, overwritten
  *   workspace device, >= fbq_workspace_bytes(d, M) bytes (may be NULL when that is 0).  Zero-fill it
