@@ -160,7 +160,7 @@ static hipError_t launch_prefill(const LinearArgs &a, hipStream_t s)
 static hipError_t launch_one(const LinearArgs &a, hipStream_t s)
 {
     if (a.M <= kPerTokenMaxM) return launch_gemv_decode(&a, 1, s);
-    if (a.M <= kDecodeMaxM) return launch_gemv_small_m(a, s);
+    if (a.M <= kDecodeMaxM) return launch_gemv_small_m(&a, 1, s);
     return launch_prefill(a, s);
 }
 
@@ -189,22 +189,26 @@ extern "C" fbq_status fbq_linear_group(const fbq_layer_call *calls, int n, int M
     }
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
-    if (M > kPerTokenMaxM) {
+    if (M > kDecodeMaxM) {
         for (int i = 0; i < n && e == hipSuccess; ++i) e = launch_one(args[i], s);
         return hip_status(e);
     }
+    // Decode: layers that fit one launch (the same kernel instance; for 4..16 tokens also the same
+    // activations, which are then prepared once) are served together.
+    const bool few = M > kPerTokenMaxM;
+    const int cap = few ? kMaxSmallGroup : kMaxGroup;
     bool done[kMaxCalls] = {false};
     for (int i = 0; i < n && e == hipSuccess; ++i) {
         if (done[i]) continue;
         LinearArgs batch[kMaxGroup];
         int nb = 0;
-        for (int j = i; j < n && nb < kMaxGroup; ++j) {
-            if (!done[j] && decode_group_compatible(args[i], args[j])) {
+        for (int j = i; j < n && nb < cap; ++j) {
+            if (!done[j] && (few ? small_m_group_compatible(args[i], args[j]) : decode_group_compatible(args[i], args[j]))) {
                 batch[nb++] = args[j];
                 done[j] = true;
             }
         }
-        e = launch_gemv_decode(batch, nb, s);
+        e = few ? launch_gemv_small_m(batch, nb, s) : launch_gemv_decode(batch, nb, s);
     }
     return hip_status(e);
 }

@@ -199,8 +199,6 @@ struct LayerParams {
 };
 
 struct GemvGroup {
-    int n_layers;
-    int block_begin[kMaxGroup + 1];   // first block of each layer (producers first, then consumers)
     LayerParams layer[kMaxGroup];
 };
 
@@ -350,14 +348,18 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     __shared__ float t_lds[RI > 0 ? RI * 128 : 1];                          // t as wave 0 received it
     __shared__ uint4 x_lds[kXChunks * 256];                                 // the token's activations, 16-byte pieces swizzled
 
-    // Which layer of the group this block serves: block_begin[] is padded with the grid size, so the
-    // comparison is false for entries past the last layer and no loop over loads is needed.
-    const int m = blockIdx.y;
-    int l = 0;
-#pragma unroll
-    for (int i = 1; i < kMaxGroup; ++i) l += (int)blockIdx.x >= g.block_begin[i] ? 1 : 0;
-    const LayerParams p = g.layer[l];
-    int bx = (int)blockIdx.x - g.block_begin[l];
+    // Grid: x = block of a layer (producers first, then consumers), y = layer of the group, z = token.
+    // The layer comes from the block index, not from a table in the kernel arguments: its parameters
+    // are then fetched in one go with everything else (a second, dependent round trip to the kernel
+    // arguments costs more than half a microsecond here).  Layers with fewer blocks than the widest
+    // one of the group leave the surplus blocks at once.
+    const int m = blockIdx.z;
+    const LayerParams p = g.layer[blockIdx.y];
+    // (all of them before the first branch: left alone, the compiler fetches only what the branch needs first)
+    asm volatile("" :: "s"(p.qw), "s"(p.scales), "s"(p.zeros), "s"(p.x), "s"(p.y), "s"(p.N), "s"(p.K), "s"(p.row_words), "s"(p.G));
+    if (RI > 0) asm volatile("" :: "s"(p.At), "s"(p.Bt), "s"(p.ttag), "s"(p.r), "s"(p.tslices));
+    int bx = blockIdx.x;
+    if (bx >= p.producers + p.blocks) return;
     uint32_t tag = 0;
     if (RI > 0) {
         tag = launch_tag();
@@ -733,8 +735,7 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
     const int consumer_budget = std::max(budget / 2, budget - producers_total);
 
     GemvGroup g;
-    g.n_layers = n_layers;
-    int next_block = 0;
+    int widest = 0;
     for (int i = 0; i < n_layers; ++i) {
         const LinearArgs &a = layers[i];
         LayerParams &p = g.layer[i];
@@ -748,11 +749,10 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
         const int max_blocks = ceil_div(ceil_div(a.N, rows), row_sets);
         const int share = (int)(consumer_budget * ((double)a.N * a.K / total_work));
         p.blocks = std::max(1, std::min(max_blocks, share));
-        g.block_begin[i] = next_block;
-        next_block += p.producers + p.blocks;
+        widest = std::max(widest, p.producers + p.blocks);
     }
-    for (int i = n_layers; i <= kMaxGroup; ++i) g.block_begin[i] = next_block;
-    const dim3 grid(next_block, M);
+    for (int i = n_layers; i < kMaxGroup; ++i) g.layer[i] = g.layer[0];   // never indexed: grid.y stops at n_layers
+    const dim3 grid(widest, n_layers, M);
 #ifdef FBQ_FAST_BUILD
     return launch_bits<4>(g, v, rows, grid, stream);
 #else

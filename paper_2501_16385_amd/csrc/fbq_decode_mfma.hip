@@ -93,6 +93,17 @@ struct SmallParams {
     int tiles_per_block;   // 16-row tiles a block of the fused kernel owns
 };
 
+// Layers that share their activations (q/k/v, gate/up) share the two launches: the activations are
+// arranged once.  In both grids y is the layer (in the preparation launch row 0 arranges the
+// activations and the layers follow) and x the block of that layer; the layer's parameters are found
+// from the block index alone, so they are fetched in one go with the rest of the kernel arguments
+// (a second, dependent round trip to them costs more than half a microsecond).  Surplus blocks of
+// rows with fewer blocks than the widest leave at once.
+struct SmallGroup {
+    int n_layers;
+    SmallParams layer[kMaxSmallGroup];
+};
+
 // What the weight field of pair p (0..15, in extraction order) is multiplied by; the activation that meets it is divided by it.
 template <int BITS>
 __device__ __forceinline__ constexpr float field_gain(int p)
@@ -259,28 +270,41 @@ __device__ void arrange_block(const SmallParams &p, int b)
 }
 
 template <int BITS>
-__global__ __launch_bounds__(64 * kPrepWaves) void fbq_small_m_prepare_kernel(const SmallParams p)
+__global__ __launch_bounds__(64 * kPrepWaves) void fbq_small_m_prepare_kernel(const SmallGroup g)
 {
     __shared__ float4_t red[kPrepWaves][64];
-    if ((int)blockIdx.x < p.down_blocks) down_proj_block(p, blockIdx.x, red);
-    else arrange_block<BITS>(p, (int)blockIdx.x - p.down_blocks);
+    const int b = blockIdx.x, row = blockIdx.y;         // row 0 arranges the activations, row i + 1 is layer i's down-projection
+    const SmallParams p = g.layer[row == 0 ? 0 : row - 1];
+    // (all parameters before the first branch: left alone, the compiler fetches only what the branch needs first)
+    asm volatile("" :: "s"(p.x), "s"(p.At), "s"(p.tpart), "s"(p.xop), "s"(p.xsum), "s"(p.M), "s"(p.K), "s"(p.r), "s"(p.G), "s"(p.kslice));
+    if (row == 0) {                                     // every layer of the group reads layer 0's copy of the activations
+        if (b < (p.G + kPrepWaves - 1) / kPrepWaves) arrange_block<BITS>(p, b);
+        return;
+    }
+    if (b < p.down_blocks) down_proj_block(p, b, red);
 }
 
 // ------------------------------------------------------------------ fused kernel
 
 // BITS: 3 or 4.  T: 16-row tiles per block.  BRANCH: r > 0.
 template <int BITS, int T, bool BRANCH>
-__global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const SmallParams p)
+__global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const SmallGroup g)
 {
     constexpr int kPiece = BITS == 4 ? 16 : 12;         // bytes of 32 codes
     __shared__ float4_t red[kMainWaves][T][64];
 
+    const SmallParams p = g.layer[blockIdx.y];
+    // (all of them before the first branch: left alone, the compiler fetches only what the branch needs first)
+    asm volatile("" :: "s"(p.qw), "s"(p.scales), "s"(p.zeros), "s"(p.xop), "s"(p.xsum), "s"(p.y), "s"(p.M), "s"(p.K), "s"(p.row_words), "s"(p.G));
+    if (BRANCH) asm volatile("" :: "s"(p.Bt), "s"(p.tpart), "s"(p.r), "s"(p.slices));
+    const int block = blockIdx.x;
+    if (block * p.tiles_per_block >= (p.N + 15) / 16) return;   // a narrower layer of the group
     FBQ_STAMP(0);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 15, q = lane >> 4;
     const int ntiles = (p.N + 15) / 16;
-    const int tile0 = blockIdx.x * p.tiles_per_block;
+    const int tile0 = block * p.tiles_per_block;
     const int row_bytes = p.row_words * 4;
 
     const __amdgpu_buffer_rsrc_t qbuf = buffer_of(p.qw, (long)p.N * row_bytes);
@@ -450,25 +474,25 @@ static int cu_count()
 }
 
 template <int BITS, int T>
-static hipError_t launch_tiles(const SmallParams &p, dim3 grid, hipStream_t stream)
+static hipError_t launch_tiles(const SmallGroup &g, bool branch, dim3 grid, hipStream_t stream)
 {
-    if (p.r > 0) hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true>), grid, dim3(64 * kMainWaves), 0, stream, p);
-    else hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, false>), grid, dim3(64 * kMainWaves), 0, stream, p);
+    if (branch) hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true>), grid, dim3(64 * kMainWaves), 0, stream, g);
+    else hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, false>), grid, dim3(64 * kMainWaves), 0, stream, g);
     return hipGetLastError();
 }
 
 template <int BITS>
-static hipError_t launch_bits(const SmallParams &p, hipStream_t stream)
+static hipError_t launch_bits(const SmallGroup &g, int prep_blocks, int main_blocks, hipStream_t stream)
 {
-    const int arrange_blocks = ceil_div(p.G, kPrepWaves);
-    hipLaunchKernelGGL(fbq_small_m_prepare_kernel<BITS>, dim3(p.down_blocks + arrange_blocks), dim3(64 * kPrepWaves), 0, stream, p);
+    hipLaunchKernelGGL(fbq_small_m_prepare_kernel<BITS>, dim3(prep_blocks, g.n_layers + 1), dim3(64 * kPrepWaves), 0, stream, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const dim3 grid(ceil_div(ceil_div(p.N, 16), p.tiles_per_block));
-    switch (p.tiles_per_block) {
-    case 1: return launch_tiles<BITS, 1>(p, grid, stream);
-    case 2: return launch_tiles<BITS, 2>(p, grid, stream);
-    default: return launch_tiles<BITS, 3>(p, grid, stream);
+    const bool branch = g.layer[0].r > 0;
+    const dim3 grid(main_blocks, g.n_layers);
+    switch (g.layer[0].tiles_per_block) {
+    case 1: return launch_tiles<BITS, 1>(g, branch, grid, stream);
+    case 2: return launch_tiles<BITS, 2>(g, branch, grid, stream);
+    default: return launch_tiles<BITS, 3>(g, branch, grid, stream);
     }
 }
 
@@ -478,24 +502,53 @@ static size_t tpart_bytes(int r) { return (size_t)kMaxSlices * kTokens * r * siz
 static size_t xsum_bytes(int K) { return (size_t)(K / kGroup) * 2 * kTokens * sizeof(float); }
 size_t small_m_workspace_bytes(int K, int r) { return tpart_bytes(r) + xsum_bytes(K) + (size_t)(K / kGroup) * 4 * 64 * 16; }
 
-hipError_t launch_gemv_small_m(const LinearArgs &a, hipStream_t stream)
+static int tiles_per_block_of(int total_tiles)
 {
-    if (a.M < 1 || a.M > kTokens) return hipErrorInvalidValue;
-    SmallParams p;
-    p.qw = a.qw; p.scales = a.scales; p.zeros = a.zeros; p.At = a.At; p.Bt = a.Bt; p.x = a.x; p.y = a.y;
-    unsigned char *ws = (unsigned char *)a.workspace;
-    p.tpart = (float *)ws;
-    p.xsum = (float *)(ws + tpart_bytes(a.r));
-    p.xop = (uint4 *)(ws + tpart_bytes(a.r) + xsum_bytes(a.K));
-    p.M = a.M; p.N = a.N; p.K = a.K; p.r = a.r;
-    p.row_words = (int)row_words(a.K, a.bits);
-    p.G = a.K / kGroup;
-    p.kslice = ceil_div(ceil_div(a.K, kMaxSlices), 32 * kPrepWaves) * (32 * kPrepWaves);
-    p.slices = ceil_div(a.K, p.kslice);
-    p.down_blocks = a.r > 0 ? ceil_div(a.r, 16) * p.slices : 0;
-    // one block per compute unit where the layer has that many tiles, at most kMaxTiles tiles each
-    p.tiles_per_block = std::min(kMaxTiles, std::max(1, ceil_div(ceil_div(a.N, 16), cu_count())));
-    return a.bits == 4 ? launch_bits<4>(p, stream) : launch_bits<3>(p, stream);
+    // one block per compute unit where the launch has that many tiles, at most kMaxTiles tiles each
+    return std::min(kMaxTiles, std::max(1, ceil_div(total_tiles, cu_count())));
+}
+
+// Layers may share the two launches when they read the same activations and need the same kernel
+// instance; a branch-free layer never joins layers with a sub-branch.
+bool small_m_group_compatible(const LinearArgs &a, const LinearArgs &b)
+{
+    return a.x == b.x && a.K == b.K && a.M == b.M && a.bits == b.bits && (a.r > 0) == (b.r > 0);
+}
+
+hipError_t launch_gemv_small_m(const LinearArgs *layers, int n_layers, hipStream_t stream)
+{
+    if (n_layers < 1 || n_layers > kMaxSmallGroup) return hipErrorInvalidValue;
+    const LinearArgs &first = layers[0];
+    if (first.M < 1 || first.M > kTokens) return hipErrorInvalidValue;
+    int total_tiles = 0;
+    for (int i = 0; i < n_layers; ++i) {
+        if (!small_m_group_compatible(first, layers[i])) return hipErrorInvalidValue;
+        total_tiles += ceil_div(layers[i].N, 16);
+    }
+    const int tpb = tiles_per_block_of(total_tiles);
+    SmallGroup g;
+    g.n_layers = n_layers;
+    int prep = ceil_div(first.K / kGroup, kPrepWaves), main_blocks = 0;   // widest row of either grid
+    for (int i = 0; i < n_layers; ++i) {
+        const LinearArgs &a = layers[i];
+        SmallParams &p = g.layer[i];
+        p.qw = a.qw; p.scales = a.scales; p.zeros = a.zeros; p.At = a.At; p.Bt = a.Bt; p.x = a.x; p.y = a.y;
+        p.tpart = (float *)a.workspace;                  // each layer's own partial sums of t ...
+        unsigned char *ws0 = (unsigned char *)first.workspace;   // ... and the first layer's copy of the activations for all
+        p.xsum = (float *)(ws0 + tpart_bytes(first.r));
+        p.xop = (uint4 *)(ws0 + tpart_bytes(first.r) + xsum_bytes(first.K));
+        p.M = a.M; p.N = a.N; p.K = a.K; p.r = a.r;
+        p.row_words = (int)row_words(a.K, a.bits);
+        p.G = a.K / kGroup;
+        p.kslice = ceil_div(ceil_div(a.K, kMaxSlices), 32 * kPrepWaves) * (32 * kPrepWaves);
+        p.slices = ceil_div(a.K, p.kslice);
+        p.down_blocks = a.r > 0 ? ceil_div(a.r, 16) * p.slices : 0;
+        p.tiles_per_block = tpb;
+        prep = std::max(prep, p.down_blocks);
+        main_blocks = std::max(main_blocks, ceil_div(ceil_div(a.N, 16), tpb));
+    }
+    for (int i = n_layers; i < kMaxSmallGroup; ++i) g.layer[i] = g.layer[0];   // never indexed: grid.y stops at n_layers
+    return first.bits == 4 ? launch_bits<4>(g, prep, main_blocks, stream) : launch_bits<3>(g, prep, main_blocks, stream);
 }
 
 }  // namespace fbq

@@ -20,6 +20,7 @@ constexpr int kDecodeMaxM = 16;
 constexpr int kPerTokenMaxM = 3;     // up to here the GEMV streams the weights once per token; above, the matrix-core tile wins
 constexpr int kMaxTSlices = 4;       // K slices of the decode down-projection: kMaxK / (4 passes * 2048)
 constexpr int kMaxGroup = 8;         // layers one grouped decode launch can serve
+constexpr int kMaxSmallGroup = 4;    // ... for 4..16 tokens
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
@@ -41,7 +42,8 @@ struct LinearArgs {
 // Launchers (validated arguments only).  Each returns the hipError_t of its launches.
 hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_t stream);
 bool decode_group_compatible(const LinearArgs &a, const LinearArgs &b);
-hipError_t launch_gemv_small_m(const LinearArgs &a, hipStream_t stream);
+hipError_t launch_gemv_small_m(const LinearArgs *layers, int n_layers, hipStream_t stream);
+bool small_m_group_compatible(const LinearArgs &a, const LinearArgs &b);
 hipError_t launch_arrange_x_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_down_proj_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream);
