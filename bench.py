@@ -279,9 +279,28 @@ def main():
         # (random packed words, same rotation protocol; see paper_2501_16385_amd/perf.py).
         from paper_2501_16385_amd import perf
         wide = max(specs, key=lambda s: s.N * s.K)
+        fam = {}
+        if len(staged) < len(specs):
+            # the same staged layer set with 16 tokens: the layers of a stage share their activations, as in a decoder
+            M16 = 16
+            xs16 = {}
+            for grp in staged:
+                shared = torch.randn((M16, specs[grp[0]].K), device="cuda").half()
+                for i in grp:
+                    xs16[i] = shared
+            ys16 = [torch.empty((M16, s.N), dtype=torch.float16, device="cuda") for s in specs]
+            ws16 = [torch.zeros(max(16, fbq.workspace_bytes(l.desc, M16)), dtype=torch.uint8, device="cuda") for l in base_layers]
+            sched16 = [[GroupCall(fbq, [ls[i] for i in grp], [xs16[i] for i in grp], [ys16[i] for i in grp],
+                                  [ws16[i] for i in grp], M16, sp) for grp in staged] for ls in sets]
+            ms16, _ = timed(sched16, max(50, args.steps // 4), max(5, args.warmup // 4))
+            bytes16 = sum(fbq_synth.algorithmic_bytes(s.N, s.K, s.r, s.bits, M16, s.group) for s in specs)
+            fam["few_token_M16_staged_layer_set"] = {"launches_per_step": 2 * len(staged), "us_per_step": round(ms16 * 1e3, 2),
+                                                     "us_per_layer": round(ms16 * 1e3 / n_layers, 3),
+                                                     "GBps": round(bytes16 / ms16 / 1e6, 1),
+                                                     "frac_of_hbm_peak": round(bytes16 / ms16 / 1e6 / HBM_PEAK_GBS, 4)}
+            del sched16
         del sets
         torch.cuda.empty_cache()
-        fam = {}
         for name, m in (("few_token_M16", 16), ("few_token_M4", 4), ("prefill_M1024", 1024)):
             t = perf.time_layer(wide.N, wide.K, wide.r, wide.bits, m, iters=200 if m <= 16 else 50, warmup=20)
             fam[name] = {"shape": f"{wide.K}->{wide.N}", "us": t["us"], "GBps": t["GBps"], "TFLOPps": t["TFLOPps"],
