@@ -497,7 +497,7 @@ static hipError_t launch_bits(const SmallGroup &g, int prep_blocks, int main_blo
 }
 
 // workspace: [slices][16][r] fp32 partial sums of t, [G][2][16] fp32 sums, [G][4][64] 16-byte operands
-constexpr int kMaxSlices = 4;        // K slices of the down-projection
+constexpr int kMaxSlices = 16;       // K slices of the down-projection
 static size_t tpart_bytes(int r) { return (size_t)kMaxSlices * kTokens * r * sizeof(float); }
 static size_t xsum_bytes(int K) { return (size_t)(K / kGroup) * 2 * kTokens * sizeof(float); }
 size_t small_m_workspace_bytes(int K, int r) { return tpart_bytes(r) + xsum_bytes(K) + (size_t)(K / kGroup) * 4 * 64 * 16; }
@@ -540,7 +540,8 @@ hipError_t launch_gemv_small_m(const LinearArgs *layers, int n_layers, hipStream
         p.M = a.M; p.N = a.N; p.K = a.K; p.r = a.r;
         p.row_words = (int)row_words(a.K, a.bits);
         p.G = a.K / kGroup;
-        p.kslice = ceil_div(ceil_div(a.K, kMaxSlices), 32 * kPrepWaves) * (32 * kPrepWaves);
+        // slices of 1024 (four at K = 4096: more only make the fused kernel add more partial sums), longer where K > 16384
+        p.kslice = std::max(1024, ceil_div(ceil_div(a.K, kMaxSlices), 32 * kPrepWaves) * (32 * kPrepWaves));
         p.slices = ceil_div(a.K, p.kslice);
         p.down_blocks = a.r > 0 ? ceil_div(a.r, 16) * p.slices : 0;
         p.tiles_per_block = tpb;
