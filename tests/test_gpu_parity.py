@@ -214,7 +214,7 @@ def test_gpu_feedback_quantizer_matches_oracle(bits, N, K, r):
 # ------------------------------------------------------------------ grouped launches, graph replay
 
 @pytest.mark.parametrize("bits", [4, 3])
-@pytest.mark.parametrize("M", [1, 3])
+@pytest.mark.parametrize("M", [1, 3, 4, 13])
 def test_group_call_equals_single_calls(bits, M):
     """q/k/v-style layers sharing x, one wider layer, one branch-free layer and one with another K:
     fbq_linear_group must give every layer bit for bit what fbq_linear gives it, and match the oracle."""
@@ -225,7 +225,10 @@ def test_group_call_equals_single_calls(bits, M):
     devs = [to_device_layer(L) for L in Ls]
     x_by_k = {K: fbq_synth.make_x(spec_of(8, K, 0, bits), M, 16, K) for K in {s[1] for s in shapes}}
     xs_np = [x_by_k[K] for (_, K, _) in shapes]
-    xs = [torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16) for x in xs_np]
+    # layers with the same K read the same device tensor, as q/k/v or gate/up do in a decoder: from 4 tokens
+    # on such layers share the preparation of the activations and both launches
+    x_dev = {K: torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16) for K, x in x_by_k.items()}
+    xs = [x_dev[K] for (_, K, _) in shapes]
     ys = fbq.linear_group(devs, xs)
     torch.cuda.synchronize()
     for L, dev, x_np, y in zip(Ls, devs, xs_np, ys):
