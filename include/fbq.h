@@ -138,10 +138,13 @@ typedef struct {
  * fbq_linear_group - the hot path for several independent layers at once (Sec. 4.3 lists launch
  * overhead as part of the sub-branch's cost; on this GPU a launch costs about as much as streaming
  * a 4096x4096 INT4 layer, so layers that do not depend on each other - q/k/v, gate/up - should share
- * one).  Every layer gets exactly the result fbq_linear gives it.  For M <= 16, layers with the same
+ * one).  Every layer gets exactly the result fbq_linear gives it.  For M <= 3, layers with the same
  * bits, the same K-derived kernel variant and a sub-branch (or all without one) are served by ONE
- * launch, up to 8 layers per launch, in the order they appear; anything else, and every layer when
- * M > 16, is launched on its own.
+ * launch, up to 8 layers per launch, in the order they appear.  For 4 <= M <= 16, layers with the
+ * same bits and K that read the SAME x (the same pointer) and all have a sub-branch (or all have
+ * none) share the two launches fbq_linear makes, up to 4 layers: the activations are prepared once,
+ * in the workspace of the first of them.  Anything else, and every layer when M > 16, is launched
+ * on its own.
  *   calls host array of n layers (read during the call only); M tokens, the same for all layers
  * Errors: those of fbq_linear for any layer, reported before ANY launch.
  */

@@ -1,4 +1,4 @@
-// Decode path (M <= 16 tokens): the fused kernel of Sec. 4.3 as a memory-streaming GEMV for gfx950.
+// Decode path for one to three tokens: the fused kernel of Sec. 4.3 as a memory-streaming GEMV for gfx950.
 //
 //   down-projection   t = x.A            a few producer blocks at the front of the SAME launch, each
 //                                        owning four columns of A over all of K (the paper keeps
@@ -6,8 +6,9 @@
 //                                        much as streaming a 4096^2 layer, so it rides along)
 //   fused kernel      y = x.Wq^T + t.B   one pass over the packed codes; de-quantization, main
 //                                        projection and up-projection share one fp32 accumulator
-//                                        and y is written once.  t is needed only for the last few
-//                                        instructions of a wave, so waiting for it hides behind
+//                                        and y is written once.  t is needed only for the second
+//                                        half of a tile (up-projection, sum, store), which is
+//                                        postponed by one trip, so waiting for it hides behind
 //                                        the weight stream.
 //
 // Hand-over of t inside one launch.  Every t[j] travels as one 8-byte word {value, tag}; the tag
@@ -18,13 +19,15 @@
 // written and read with device-scope (sc1) accesses, which do not linger in a per-XCD L2.
 //
 // Work decomposition of the fused kernel.  Waves are persistent: a wave owns a contiguous K range
-// and walks over tiles of ROWS consecutive output rows with a fixed stride, loading the next tile
-// while it computes the current one.  Its 64 lanes lie along K.  One wave-wide load covers 2048
+// and walks over tiles of ROWS consecutive output rows with a fixed stride, with two tile buffers in
+// registers: a buffer is requested again, for the tile two trips ahead, as soon as its arithmetic is
+// done.  Its 64 lanes lie along K.  One wave-wide load covers 2048
 // codes (INT4: 16 B per lane, INT3: 12 B per lane, both fully coalesced), so a lane always holds
-// 32 consecutive codes of one quantization group.  The lane's activations are loaded once and
-// stay in registers for every tile (they are the same for every row), pre-arranged as the fp16
-// pairs that the code extraction produces.  One launch can serve several layers with the same K
-// (q/k/v, gate/up): blocks are shared out in proportion to the layers' sizes.
+// 32 consecutive codes of one quantization group.  The token's activations are fetched once per
+// block, handed to the waves through LDS and stay in registers for every tile (they are the same
+// for every row), pre-arranged as the fp16 pairs that the code extraction produces.  One launch can
+// serve several layers with the same K (q/k/v, gate/up): grid.y is the layer, and blocks are shared
+// out in proportion to the layers' sizes.
 //
 // Code extraction without conversion instructions.  Masking a packed word with 0x000F000F (INT4)
 // or 0x00070007 (INT3) leaves two codes, one per 16-bit half, each in the low mantissa bits of an
@@ -37,15 +40,6 @@
 
 
 #include "fbq_internal.h"
-
-// Timing builds only (never defined for the library): per-wave wall-clock stamps (100 MHz) into a buffer the
-// timing harness owns.
-#ifdef FBQ_TRACE
-extern __device__ long long *fbq_trace_buf;
-#define FBQ_STAMP(slot) do { if ((threadIdx.x & 63) == 0) fbq_trace_buf[((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 8 + (slot)] = wall_clock64(); } while (0)
-#else
-#define FBQ_STAMP(slot) do { } while (0)
-#endif
 
 namespace fbq {
 
@@ -365,15 +359,12 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
         tag = launch_tag();
         if (bx < p.producers) {                         // block-uniform: producer blocks only produce
             __builtin_amdgcn_s_setprio(3);              // every consumer waits for them
-            FBQ_STAMP(0);
             produce_t(p, m, bx, tag, red);
-            FBQ_STAMP(6);
             return;
         }
         bx -= p.producers;
     }
 
-    FBQ_STAMP(0);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in all lanes: lets row offsets live in scalar registers
@@ -416,7 +407,6 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     uint32_t bt0[ROWS][kRI], bt1[ROWS][kRI];            // their rows of Bt
     cur.load(p, tile_buffers(p, true), min(tile, ntiles - 1) * ROWS, qoff, goff);
     if (RI > 0) load_taps<ROWS, kRI>(bt0, p, tile_buffers(p, true), min(tile, ntiles - 1) * ROWS, joff);
-    FBQ_STAMP(4);
     __builtin_amdgcn_sched_barrier(0);
 
     // Activations into LDS (piece j at j ^ ((j >> 4) & 3): the 16 lanes of a quarter wave then read 16
@@ -453,9 +443,6 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     uint4_t tw[kRI][kMaxTSlices];
     float t0[kRI], t1[kRI];
     bool have_t = false;
-#ifdef FBQ_TRACE
-    bool traced = false;
-#endif
     auto request_t = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < RI; ++q)
@@ -515,9 +502,6 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
             t1[q] = t_lds[(q * 64 + lane) * 2 + 1];
         }
         have_t = true;
-#ifdef FBQ_TRACE
-        asm volatile("" : "+v"(t0[0])); FBQ_STAMP(2);
-#endif
     };
 
     // Second half of a tile: up-projection into the same accumulators (the K-slice-0 wave of each row
@@ -553,9 +537,6 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
         const int n0 = tile * ROWS;
         if (ks == 0 && lane < ROWS && tile < ntiles && n0 + lane < p.N)
             p.y[(size_t)m * p.N + n0 + lane] = __builtin_bit_cast(uint16_t, (half_t)out);
-#ifdef FBQ_TRACE
-        if (!traced) { FBQ_STAMP(3); traced = true; }
-#endif
     };
 
     // One trip.  The tile's registers are refilled (with the tile two trips ahead, or with nothing) as
@@ -591,9 +572,6 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
         }
 #pragma unroll
         for (int i = 0; i < ROWS; ++i) asm volatile("" : "+v"(acc[i]));   // the arithmetic is done before the registers are handed back
-#ifdef FBQ_TRACE
-        if (!traced) { FBQ_STAMP(1); }
-#endif
         __builtin_amdgcn_sched_barrier(0);
         T.load(p, tile_buffers(p, j + 2 < trips), min(tile + 2 * tstride, ntiles - 1) * ROWS, qoff, goff);
         __builtin_amdgcn_sched_barrier(0);
@@ -627,7 +605,6 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
         if (trips & 1) finish(acc0, bt0, tile - tstride);
         else finish(acc1, bt1, tile - tstride);
     }
-    FBQ_STAMP(5);
 }
 
 // ------------------------------------------------------------------ dispatch
@@ -684,16 +661,14 @@ template <int BITS>
 static hipError_t launch_bits(const GemvGroup &g, const Variant &v, int rows, dim3 grid, hipStream_t stream)
 {
     switch (v.ks * 10 + v.cpw) {
-    case 12: return launch_rows<BITS, 2, 1>(g, rows, v.ri, grid, stream);
-    case 23: return launch_rows<BITS, 3, 2>(g, rows, v.ri, grid, stream);
-#ifndef FBQ_FAST_BUILD
     case 11: return launch_rows<BITS, 1, 1>(g, rows, v.ri, grid, stream);
+    case 12: return launch_rows<BITS, 2, 1>(g, rows, v.ri, grid, stream);
     case 13: return launch_rows<BITS, 3, 1>(g, rows, v.ri, grid, stream);
     case 14: return launch_rows<BITS, 4, 1>(g, rows, v.ri, grid, stream);
+    case 23: return launch_rows<BITS, 3, 2>(g, rows, v.ri, grid, stream);
     case 24: return launch_rows<BITS, 4, 2>(g, rows, v.ri, grid, stream);
     case 43: return launch_rows<BITS, 3, 4>(g, rows, v.ri, grid, stream);
     case 44: return launch_rows<BITS, 4, 4>(g, rows, v.ri, grid, stream);
-#endif
     }
     return hipErrorInvalidValue;   // K > 32768: rejected by the caller's shape check
 }
@@ -753,11 +728,7 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
     }
     for (int i = n_layers; i < kMaxGroup; ++i) g.layer[i] = g.layer[0];   // never indexed: grid.y stops at n_layers
     const dim3 grid(widest, n_layers, M);
-#ifdef FBQ_FAST_BUILD
-    return launch_bits<4>(g, v, rows, grid, stream);
-#else
     return v.bits == 4 ? launch_bits<4>(g, v, rows, grid, stream) : launch_bits<3>(g, v, rows, grid, stream);
-#endif
 }
 
 }  // namespace fbq

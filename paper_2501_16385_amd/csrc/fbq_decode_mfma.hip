@@ -1,4 +1,4 @@
-// Decode path for a few tokens (5 <= M <= 16): the fused kernel of Sec. 4.3 with the packed codes
+// Decode path for a few tokens (4 <= M <= 16): the fused kernel of Sec. 4.3 with the packed codes
 // streamed exactly once, the tokens riding along as the 16 rows of a matrix-core tile.
 //
 //   y[M,N] = x[M,K] . Wq[N,K]^T + t[M,r] . B[r,N],   t = x . A
@@ -31,19 +31,14 @@
 // instructions, fp32, every product exact), and the lane that holds output row n adds
 // s (D' - XS - z X) to its accumulator: the same factorisation as in the one-token kernel.
 //
-// A block's eight waves split K; their partial tiles meet in LDS, and the wave that finishes a tile
-// folds the up-projection in as r more values of k (t split into two fp16 halves: t_hi + t_lo
-// carries 22 bits of the fp32 sum) before y is stored once.
+// A block's eight waves split K.  The up-projection enters the same accumulators as r more values of
+// k (t split into two fp16 halves: t_hi + t_lo carries 22 bits of the fp32 sum), in units of
+// (tile, 32 taps) dealt out to the waves; then the waves' partial tiles meet in LDS and y is stored
+// once.  Layers that read the same activations (q/k/v, gate/up) share both launches.
 #include <hip/hip_fp16.h>
 
 #include "fbq_internal.h"
 
-#ifdef FBQ_TRACE
-extern __device__ long long *fbq_trace_buf;
-#define FBQ_STAMP(slot) do { if ((threadIdx.x & 63) == 0) fbq_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + (slot)] = wall_clock64(); } while (0)
-#else
-#define FBQ_STAMP(slot) do { } while (0)
-#endif
 
 namespace fbq {
 
@@ -299,7 +294,6 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
     if (BRANCH) asm volatile("" :: "s"(p.Bt), "s"(p.tpart), "s"(p.r), "s"(p.slices));
     const int block = blockIdx.x;
     if (block * p.tiles_per_block >= (p.N + 15) / 16) return;   // a narrower layer of the group
-    FBQ_STAMP(0);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 15, q = lane >> 4;
@@ -385,13 +379,9 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
         }
 #pragma unroll
         for (int ti = 1; ti < T; ++ti) request_tile(ti);
-        FBQ_STAMP(1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ti = 0; ti < T; ++ti) {
-#ifdef FBQ_TRACE
-            if (ti == 1) { asm volatile("" : "+v"(acc[0][0])); FBQ_STAMP(2); }
-#endif
 #pragma unroll
             for (int gi = 0; gi < kWaveGroups; ++gi) {
                 half8_t b[4];
@@ -406,9 +396,6 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
         }
     }
 
-#ifdef FBQ_TRACE
-    asm volatile("" : "+v"(acc[T - 1][0])); FBQ_STAMP(3);
-#endif
     if (BRANCH) {
         for (int u = wave; u < units; u += kMainWaves) {   // wave-uniform; the first unit's Bt operand is already here
             const int ti = u / tap_steps, js = u - ti * tap_steps;
@@ -441,9 +428,7 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
     // K split: every wave leaves its tiles in LDS; wave ti adds them up for tile ti and stores.
 #pragma unroll
     for (int ti = 0; ti < T; ++ti) red[wave][ti][lane] = acc[ti];
-    FBQ_STAMP(4);
     __syncthreads();
-    FBQ_STAMP(5);
     for (int ti = wave; ti < T; ti += kMainWaves) {     // wave-uniform
         if (tile0 + ti >= ntiles) break;
         float4_t sum = red[0][ti][lane];
@@ -459,7 +444,6 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
             }
         }
     }
-    FBQ_STAMP(6);
 }
 
 static int cu_count()
