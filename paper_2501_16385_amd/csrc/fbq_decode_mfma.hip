@@ -302,8 +302,10 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
     const int row_bytes = p.row_words * 4;
 
     const __amdgpu_buffer_rsrc_t qbuf = buffer_of(p.qw, (long)p.N * row_bytes);
-    const __amdgpu_buffer_rsrc_t sbuf = buffer_of(p.scales, (long)p.N * p.G * 2);
-    const __amdgpu_buffer_rsrc_t zbuf = buffer_of(p.zeros, (long)p.N * p.G * 2);
+    // The range check is per dword, so the count is rounded up to whole dwords: with N·G odd the last
+    // half shares an aligned dword with two bytes past the array (same cache line, never another page).
+    const __amdgpu_buffer_rsrc_t sbuf = buffer_of(p.scales, ((long)p.N * p.G * 2 + 3) & ~3L);
+    const __amdgpu_buffer_rsrc_t zbuf = buffer_of(p.zeros, ((long)p.N * p.G * 2 + 3) & ~3L);
     const __amdgpu_buffer_rsrc_t xbuf = buffer_of(p.xop, (long)p.G * 4 * 64 * 16);
     const __amdgpu_buffer_rsrc_t ubuf = buffer_of(p.xsum, (long)p.G * 2 * kTokens * 4);
 

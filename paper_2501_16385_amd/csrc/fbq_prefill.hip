@@ -60,6 +60,8 @@ struct PrefillParams {
     int M, N, K, r;
     int row_words, G;
     int row_blocks;        // ceil(M / block tile rows)
+    int ksplit;            // blocks that split K for the same tile (1: none)
+    float *ypart;          // ksplit > 1 only: [ksplit][M][N] fp32 partial results, added up by fbq_sum_parts_kernel
 };
 
 // Order in which the 32 activations of a lane's code block must sit so that slot s of K step i
@@ -177,12 +179,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // Workgroups go to the eight XCDs round-robin by linear id, and each XCD has its own L2.  Give
     // every XCD its own column blocks (all row blocks of one column block run on the same XCD, one
     // after the other in id order), so that a weight tile is fetched into one L2 only.
-    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    // Where a launch would have fewer blocks than the CUs can hold, ksplit blocks share a tile and split
+    // K; their fp32 partial results are added by a small launch afterwards.
+    const int xcd = blockIdx.x % kXcds, slot = (blockIdx.x / kXcds) / p.ksplit, part = (blockIdx.x / kXcds) % p.ksplit;
     const int bm = slot % p.row_blocks, bn = (slot / p.row_blocks) * kXcds + xcd;
     if (bn * kBN >= p.N) return;                        // block-uniform
     const int m0 = bm * kBM;
     const int nw = bn * kBN + wave * (kTN * 32);
-    const int U = p.K / kBK;
+    const int U_all = p.K / kBK, U_part = (U_all + p.ksplit - 1) / p.ksplit;
+    const int u0 = part * U_part, U = min(U_all, u0 + U_part);   // this block's super-steps: u0 .. U - 1
 
     // this lane's weight rows (clamped: columns past N are computed on a valid row and never stored)
     const uint32_t *wrow[kTN];
@@ -295,12 +300,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     };
 
     StepRegs cur, nxt;
-    step_load(cur, 0);
-    x_copy(0, 0);
+    step_load(cur, min(u0, U_all - 1));
+    x_copy(min(u0, U_all - 1), u0 & 1);
     __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wave's LDS copies have landed
     __syncthreads();
 
-    for (int u = 0; u < U; ++u) {
+    for (int u = u0; u < U; ++u) {
         const bool more = u + 1 < U;                    // block-uniform
         if (more) {
             step_load(nxt, u + 1);
@@ -313,7 +318,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
 
     // up-projection: 2r extra K columns, t_hi and t_lo against the same B^T rows
-    if (p.r > 0) {
+    if (p.r > 0 && part == 0) {
         const int steps = (2 * p.r) / 16;
         for (int st = 0; st < steps; ++st) {
             const int jj = st * 16 + h * 8;             // column of [t_hi | t_lo]
@@ -342,9 +347,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = m0 + tm * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-                if (m < p.M) p.y[(size_t)m * p.N + n] = __builtin_bit_cast(uint16_t, (half_t)acc[tm][tn][v]);
+                if (m >= p.M) continue;
+                if (p.ksplit > 1) p.ypart[((size_t)part * p.M + m) * p.N + n] = acc[tm][tn][v];
+                else p.y[(size_t)m * p.N + n] = __builtin_bit_cast(uint16_t, (half_t)acc[tm][tn][v]);
             }
         }
+    }
+}
+
+// y = sum of the K parts' fp32 partial results (only where K was split over blocks).
+__global__ __launch_bounds__(256) void fbq_sum_parts_kernel(const float *__restrict__ ypart, uint16_t *__restrict__ y, size_t total, int parts)
+{
+    for (size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4; i < total; i += (size_t)gridDim.x * 256 * 4) {
+        float4 acc = *reinterpret_cast<const float4 *>(ypart + i);
+        for (int pt = 1; pt < parts; ++pt) {
+            const float4 v = *reinterpret_cast<const float4 *>(ypart + (size_t)pt * total + i);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        const half2_t lo = half2_t{(half_t)acc.x, (half_t)acc.y}, hi = half2_t{(half_t)acc.z, (half_t)acc.w};
+        *reinterpret_cast<uint2 *>(y + i) = make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
     }
 }
 
@@ -468,9 +489,25 @@ __global__ __launch_bounds__(256) void fbq_down_proj_finish_kernel(const float *
 static size_t xp_bytes(int M, int K) { return (size_t)ceil_div(M, kRowPad) * kRowPad * K * sizeof(uint16_t); }
 static size_t thl_bytes(int M, int r) { return ((size_t)M * 2 * r * sizeof(uint16_t) + 255) & ~(size_t)255; }
 
-size_t prefill_workspace_bytes(int M, int K, int r)
+static size_t down_partial_bytes(int M, int r) { return ((size_t)kDownSlices * M * r * sizeof(float) + 255) & ~(size_t)255; }
+
+// K is split over blocks where 64-row tiles would give at most as many blocks as there are CUs (256
+// assumed: the rule must not depend on the device, the workspace is sized without one), up to four
+// ways and never below eight super-steps per block.  M * N must be a multiple of 4 for the summing
+// launch (N is even... so it is whenever N % 4 == 0 or M % 2 == 0 and N % 2 == 0; otherwise no split).
+static int ksplit_of(int M, int N, int K)
 {
-    return xp_bytes(M, K) + thl_bytes(M, r) + (size_t)kDownSlices * M * r * sizeof(float);
+    const long blocks = (long)ceil_div(N, kBN) * ceil_div(M, 64);
+    if (blocks > 256 || ((size_t)M * N) % 4 != 0 || N % 4 != 0) return 1;
+    int split = (int)std::min<long>(4, 512 / blocks);
+    while (split > 1 && (K / kBK) / split < 8) --split;
+    return std::max(1, split);
+}
+
+size_t prefill_workspace_bytes(int M, int N, int K, int r)
+{
+    const int split = ksplit_of(M, N, K);
+    return xp_bytes(M, K) + thl_bytes(M, r) + down_partial_bytes(M, r) + (split > 1 ? (size_t)split * M * N * sizeof(float) : 0);
 }
 
 hipError_t launch_arrange_x_prefill(const LinearArgs &a, hipStream_t stream)
@@ -526,7 +563,9 @@ hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream)
     const int nb = ceil_div(a.N, kBN);
     const bool tall = (long)nb * ceil_div(a.M, 128) >= prefill_cu_count() || a.M <= 64;
     p.row_blocks = ceil_div(a.M, tall ? 128 : 64);
-    const dim3 grid(kXcds * ceil_div(nb, kXcds) * p.row_blocks);
+    p.ksplit = tall ? 1 : ksplit_of(a.M, a.N, a.K);
+    p.ypart = (float *)((char *)a.workspace + xp_bytes(a.M, a.K) + thl_bytes(a.M, a.r) + down_partial_bytes(a.M, a.r));
+    const dim3 grid(kXcds * ceil_div(nb, kXcds) * p.row_blocks * p.ksplit);
     if (a.bits == 4) {
         if (tall) hipLaunchKernelGGL((fbq_gemm_kernel<4, 4>), grid, dim3(256), 0, stream, p);
         else hipLaunchKernelGGL((fbq_gemm_kernel<4, 2>), grid, dim3(256), 0, stream, p);
@@ -534,7 +573,14 @@ hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream)
         if (tall) hipLaunchKernelGGL((fbq_gemm_kernel<3, 4>), grid, dim3(256), 0, stream, p);
         else hipLaunchKernelGGL((fbq_gemm_kernel<3, 2>), grid, dim3(256), 0, stream, p);
     }
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && p.ksplit > 1) {
+        const size_t total = (size_t)a.M * a.N;
+        hipLaunchKernelGGL(fbq_sum_parts_kernel, dim3((unsigned)std::min<size_t>(2048, (total / 4 + 255) / 256)), dim3(256), 0, stream,
+                           p.ypart, a.y, total, p.ksplit);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 }  // namespace fbq

@@ -52,6 +52,9 @@ DECODE_CASES = [
     (1000, 4096, 0, 1),
     (64, 128, 8, 16),
     (1, 128, 0, 1),
+    # N·G odd: the last row's scale and zero are the last half of their arrays
+    (257, 128, 8, 16),
+    (33, 1408, 8, 6),
     # wide enough for the 64-column blocks of the matrix-core GEMV with K split over blocks
     (1290, 32768, 64, 16),
     (3500, 12288, 32, 7),
