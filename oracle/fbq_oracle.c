@@ -41,7 +41,10 @@
  * the identity W - W_F = R - Q(R) and the s/2 bound, with the negative case (no feedback)
  * violating it; y against exact rational arithmetic on tiny layers, against a dense fp64 GEMM
  * of the materialised W_F, against numpy's textbook group-RTN GEMV when B = 0, and exactly
- * against integer arithmetic when s = 1, z = 0.  No function here is left unpinned.
+ * against integer arithmetic when s = 1, z = 0; the reconstruction step's loss against the trace
+ * form, its gradients against the closed form of Sec. 4.2 and against central differences of the
+ * loss with the quantized weight held fixed, the exact zero of dL/dA while B = 0, and the s/2 bound
+ * after every update.  No function here is left unpinned.
  */
 #include <math.h>
 #include <stdint.h>
@@ -413,6 +416,106 @@ int fbqo_dense_linear(int M, int N, int K, const uint16_t *x, const double *Wd, 
                 acc += fbqo_half_to_double(x[(size_t)m * K + k]) * Wd[(size_t)n * K + k];
             y[(size_t)m * N + n] = acc;
         }
+    return FBQO_OK;
+}
+
+/* ---------------------------------------------------------------- layer-wise reconstruction */
+
+/*
+ * One iteration of the loop body of Alg. 1 (Sec. 4.2) for one layer, on T calibration tokens X [T,K].
+ * The steps are taken in the algorithm's order, and the gradient is obtained by differentiating
+ * the forward pass as written there (not from the closed form -2.Delta_F.X^T.X, which the tests
+ * use as a pin):
+ *   Z  = W X^T                                   the fp16 layer's output                [N,T]
+ *   Z' = Q(W - Sigma) X^T + B A X^T              quantized main path plus sub-branch    [N,T]
+ *   L  = sum of squares of Z - Z'
+ *   backward with W and Q(W - Sigma) held constant ("detached"): only the term B A X^T depends
+ *   on A and B.  In this file's orientation (A [K,r], B [r,N], Z'^T = X Wq^T + (X A) B), with
+ *   E = dL/dZ' = -2 (Z - Z') and S = X A:   dL/dB = S^T E^T,   dL/dA = X^T (E^T B^T).
+ *   A <- A - lr dL/dA,  B <- B - lr dL/dB        plain gradient descent
+ * Readings where the paper is silent:
+ *   - the loss is the SQUARED Frobenius norm: the trace form the paper equates it with, and the
+ *     gradient it prints, are those of the square;
+ *   - "gradient descent" is the plain update above (no momentum, no adaptive scaling);
+ *   - A and B are kept as real-valued masters (fp64 here); the forward pass uses their fp16
+ *     roundings A16, B16 - the values a deployed layer would hold, so that the codes, scales and
+ *     zeros written here together with A16, B16 are a consistent layer for the inference path -
+ *     and the gradient with respect to a master is taken to be that with respect to its rounding.
+ * Outputs describe the parameters BEFORE the update: codes/scales/zeros = Q(W - Sigma16), A16, B16,
+ * loss, gradA [K,r], gradB [r,N].  A and B are updated in place.
+ */
+int fbqo_train_step(int N, int K, int r, int bits, int group, int T, const uint16_t *W, const uint16_t *X,
+                    double *A, double *B, double lr, uint8_t *codes, uint16_t *scales, uint16_t *zeros,
+                    uint16_t *A16, uint16_t *B16, double *gradA, double *gradB, double *loss)
+{
+    if (!shape_ok(N, K, bits, group) || r < 1 || T < 1) return FBQO_BAD_ARG;
+    if (!W || !X || !A || !B || !codes || !scales || !zeros || !A16 || !B16 || !gradA || !gradB || !loss)
+        return FBQO_BAD_ARG;
+    const int G = K / group;
+    fbqo_double_to_half_array(A, A16, (long)K * r);
+    fbqo_double_to_half_array(B, B16, (long)r * N);
+    int rc = fbqo_quantize(N, K, r, bits, group, W, A16, B16, codes, scales, zeros);
+    if (rc != FBQO_OK) return rc;
+
+    double *Xd = (double *)malloc((size_t)T * K * sizeof(double));
+    double *S = (double *)malloc((size_t)T * r * sizeof(double));       /* S = X A16 */
+    double *E = (double *)malloc((size_t)N * T * sizeof(double));       /* E = dL/dZ' */
+    double *dS = (double *)malloc((size_t)T * r * sizeof(double));      /* dL/dS = E^T B16^T */
+    double *row_loss = (double *)malloc((size_t)N * sizeof(double));
+    if (!Xd || !S || !E || !dS || !row_loss) { free(Xd); free(S); free(E); free(dS); free(row_loss); return FBQO_NO_MEM; }
+    fbqo_half_to_double_array(X, Xd, (long)T * K);
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < r; ++j) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k) acc += Xd[(size_t)t * K + k] * fbqo_half_to_double(A16[(size_t)k * r + j]);
+            S[(size_t)t * r + j] = acc;
+        }
+
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        double l = 0.0;
+        for (int t = 0; t < T; ++t) {
+            double z = 0.0, zq = 0.0, zs = 0.0;
+            for (int k = 0; k < K; ++k) {
+                const double s = fbqo_half_to_double(scales[(size_t)n * G + k / group]);
+                const double zp = fbqo_half_to_double(zeros[(size_t)n * G + k / group]);
+                const double wq = s * ((double)codes[(size_t)n * K + k] - zp);
+                z += fbqo_half_to_double(W[(size_t)n * K + k]) * Xd[(size_t)t * K + k];   /* Z  = W X^T */
+                zq += wq * Xd[(size_t)t * K + k];                                         /* Q(W - Sigma) X^T */
+            }
+            for (int j = 0; j < r; ++j) zs += fbqo_half_to_double(B16[(size_t)j * N + n]) * S[(size_t)t * r + j];
+            const double e = z - (zq + zs);
+            l += e * e;
+            E[(size_t)n * T + t] = -2.0 * e;
+        }
+        row_loss[n] = l;
+        for (int j = 0; j < r; ++j) {                                   /* dL/dB = S^T E^T */
+            double acc = 0.0;
+            for (int t = 0; t < T; ++t) acc += S[(size_t)t * r + j] * E[(size_t)n * T + t];
+            gradB[(size_t)j * N + n] = acc;
+        }
+    }
+    double total = 0.0;
+    for (int n = 0; n < N; ++n) total += row_loss[n];
+    *loss = total;
+
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < r; ++j) {
+            double acc = 0.0;
+            for (int n = 0; n < N; ++n) acc += E[(size_t)n * T + t] * fbqo_half_to_double(B16[(size_t)j * N + n]);
+            dS[(size_t)t * r + j] = acc;
+        }
+#pragma omp parallel for schedule(static)
+    for (int k = 0; k < K; ++k)
+        for (int j = 0; j < r; ++j) {                                   /* dL/dA = X^T dS */
+            double acc = 0.0;
+            for (int t = 0; t < T; ++t) acc += Xd[(size_t)t * K + k] * dS[(size_t)t * r + j];
+            gradA[(size_t)k * r + j] = acc;
+        }
+
+    for (long i = 0; i < (long)K * r; ++i) A[i] -= lr * gradA[i];
+    for (long i = 0; i < (long)r * N; ++i) B[i] -= lr * gradB[i];
+    free(Xd); free(S); free(E); free(dS); free(row_loss);
     return FBQO_OK;
 }
 

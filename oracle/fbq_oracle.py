@@ -172,3 +172,37 @@ def dense_linear(x: np.ndarray, Wd: np.ndarray) -> np.ndarray:
     y = np.empty((M, N), np.float64)
     _check(_load().fbqo_dense_linear(M, N, K, _p(_f16(x)), _p(Wd), _p(y)), "dense_linear")
     return y
+
+
+def gram(X: np.ndarray) -> np.ndarray:
+    """H = X^T X in fp64 for X [T,K] fp16: the matrix through which the loss and gradient of Sec. 4.2
+    depend on the calibration activations."""
+    Xd = np.ascontiguousarray(X).astype(np.float64)
+    return Xd.T @ Xd
+
+
+def train_step(W: np.ndarray, X: np.ndarray, A: np.ndarray, B: np.ndarray, lr: float, bits: int, group: int):
+    """One loop-body iteration of Alg. 1.  A [K,r], B [r,N] fp64 masters, updated IN PLACE.
+    Returns a dict describing the parameters before the update: codes, scales, zeros, A16, B16,
+    loss, gradA, gradB."""
+    N, K = W.shape
+    T = X.shape[0]
+    r = A.shape[1]
+    if A.dtype != np.float64 or B.dtype != np.float64 or not A.flags.c_contiguous or not B.flags.c_contiguous:
+        raise TypeError("A and B must be contiguous fp64 arrays (they are updated in place)")
+    G = K // group
+    codes = np.empty((N, K), np.uint8)
+    s = np.empty((N, G), np.uint16)
+    z = np.empty((N, G), np.uint16)
+    A16 = np.empty((K, r), np.uint16)
+    B16 = np.empty((r, N), np.uint16)
+    gA = np.empty((K, r), np.float64)
+    gB = np.empty((r, N), np.float64)
+    loss = ctypes.c_double(0.0)
+    lib = _load()
+    lib.fbqo_train_step.argtypes = [ctypes.c_int] * 6 + [ctypes.c_void_p] * 4 + [ctypes.c_double] + [ctypes.c_void_p] * 7 + [
+        ctypes.POINTER(ctypes.c_double)]
+    _check(lib.fbqo_train_step(N, K, r, bits, group, T, _p(_f16(W)), _p(_f16(X)), _p(A), _p(B), float(lr), _p(codes), _p(s),
+                               _p(z), _p(A16), _p(B16), _p(gA), _p(gB), ctypes.byref(loss)), "train_step")
+    return {"codes": codes, "scales": s.view(np.float16), "zeros": z.view(np.float16), "A16": A16.view(np.float16),
+            "B16": B16.view(np.float16), "loss": loss.value, "gradA": gA, "gradB": gB}
