@@ -178,6 +178,46 @@ fbq_status fbq_unpack_codes(const fbq_desc *d, const void *qweight, uint8_t *cod
 fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, const void *At, const void *Bt,
                                  void *qweight_out, void *scales_out, void *zeros_out, fbq_stream stream);
 
+/*
+ * Layer-wise reconstruction (Alg. 1, Sec. 4.2): gradient descent on the sub-branch of one layer so
+ * that the quantized layer reproduces the fp16 layer's outputs on calibration activations X [T,K].
+ * Loss and gradient depend on X only through H = X^T X (Sec. 4.2: L = tr(Delta_F H Delta_F^T) with
+ * Delta_F = W - Q(W - Sigma) - Sigma; dL/dSigma = -2 Delta_F H once the feedback is detached), so H
+ * is formed once per layer and every iteration works from it.
+ *
+ * fbq_train_workspace_bytes - device scratch for fbq_gram (T tokens) and fbq_train_step: x
+ *   transposed, or fp16 copies of the branch, Delta_F in both orientations, Delta_F H and the
+ *   tiles' shares of the loss (about 6 N K bytes).  0 for an invalid descriptor, r < 1 or T < 1.
+ *
+ * fbq_gram - H16_out [K,K] fp16 = fp16(h_scale * X^T X), accumulated in fp32 on the matrix cores.
+ *   X device [T,K] fp16.  h_scale > 0 keeps H inside fp16's range: h_scale * max_k sum_t x[t,k]^2
+ *   must stay below 65504 (1/T suits unit-variance activations).  d->N, d->r, d->bits are not used
+ *   beyond validation.
+ *
+ * fbq_train_step - one iteration of the loop body of Alg. 1.
+ *   in:     W device [N,K] fp16; H16, h_scale from fbq_gram
+ *   in/out: At32 device [r,K] fp32, Bt32 device [N,r] fp32: the master copies of the branch
+ *           (Alg. 1 initialises A ~ N(0, sigma^2), B = 0), updated in place:
+ *           master <- master - lr * gradient (plain gradient descent)
+ *   out, all describing the branch BEFORE the update, i.e. a consistent layer for fbq_linear:
+ *           At16_out [r,K], Bt16_out [N,r] = fp16 of the masters (what the forward pass uses);
+ *           qweight_out, scales_out, zeros_out = Q(W - Sigma16) exactly as fbq_quantize_feedback
+ *           would write them; grad_At [r,K], grad_Bt [N,r] fp32 = dL/dAt, dL/dBt with W and
+ *           Q(W - Sigma16) held constant; loss: one fp32 = || W X^T - W_F X^T ||_F^2 (the square:
+ *           the trace form and the printed gradient are those of the squared norm).
+ *   lr = 0 evaluates without moving the masters.  Delta_F, H and Delta_F H enter the matrix
+ *   cores as fp16 with fp32 accumulation: gradients and loss carry a relative error of a few 1e-4.
+ *   Nothing is allocated; everything is enqueued on `stream`.  Needs r >= 1.
+ * Errors: FBQ_ERR_NULL, _SHAPE, _UNSUPPORTED, _ALIGN, _WORKSPACE before any launch; FBQ_ERR_HIP.
+ */
+size_t fbq_train_workspace_bytes(const fbq_desc *d, int T);
+fbq_status fbq_gram(const fbq_desc *d, int T, const void *X, float h_scale, void *H16_out, void *workspace,
+                    size_t workspace_bytes, fbq_stream stream);
+fbq_status fbq_train_step(const fbq_desc *d, const void *W, const void *H16, float h_scale, float *At32, float *Bt32,
+                          float lr, void *qweight_out, void *scales_out, void *zeros_out, void *At16_out,
+                          void *Bt16_out, float *grad_At, float *grad_Bt, float *loss, void *workspace,
+                          size_t workspace_bytes, fbq_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libfbq.so")
-SOURCES = ["fbq_api.cpp", "fbq_decode.hip", "fbq_decode_mfma.hip", "fbq_prefill.hip", "fbq_util.hip"]
+SOURCES = ["fbq_api.cpp", "fbq_decode.hip", "fbq_decode_mfma.hip", "fbq_prefill.hip", "fbq_util.hip", "fbq_train.hip"]
 
 
 def build(verbose: bool = False) -> str:

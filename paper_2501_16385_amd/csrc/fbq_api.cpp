@@ -261,3 +261,47 @@ extern "C" fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, co
                                       (uint32_t *)qweight_out, (uint16_t *)scales_out, (uint16_t *)zeros_out,
                                       (hipStream_t)stream));
 }
+
+extern "C" size_t fbq_train_workspace_bytes(const fbq_desc *d, int T)
+{
+    if (fbq_check_desc(d) != FBQ_OK || d->r < 1 || T < 1) return 0;
+    return train_workspace_bytes(d->N, d->K, d->r, T);
+}
+
+extern "C" fbq_status fbq_gram(const fbq_desc *d, int T, const void *X, float h_scale, void *H16_out, void *workspace,
+                               size_t workspace_bytes, fbq_stream stream)
+{
+    fbq_status st = fbq_check_desc(d);
+    if (st != FBQ_OK) return st;
+    if (T < 1 || T > (1 << 20) || !(h_scale > 0.0f)) return FBQ_ERR_SHAPE;
+    if (!X || !H16_out || !workspace) return FBQ_ERR_NULL;
+    if (misaligned(X) || misaligned(H16_out) || misaligned(workspace)) return FBQ_ERR_ALIGN;
+    if (workspace_bytes < train_workspace_bytes(d->N, d->K, d->r > 0 ? d->r : 8, T)) return FBQ_ERR_WORKSPACE;
+    return hip_status(launch_gram(d->K, T, (const uint16_t *)X, h_scale, (uint16_t *)H16_out, workspace, (hipStream_t)stream));
+}
+
+extern "C" fbq_status fbq_train_step(const fbq_desc *d, const void *W, const void *H16, float h_scale, float *At32, float *Bt32,
+                                     float lr, void *qweight_out, void *scales_out, void *zeros_out, void *At16_out,
+                                     void *Bt16_out, float *grad_At, float *grad_Bt, float *loss, void *workspace,
+                                     size_t workspace_bytes, fbq_stream stream)
+{
+    fbq_status st = fbq_check_desc(d);
+    if (st != FBQ_OK) return st;
+    if (d->r < 1 || !(h_scale > 0.0f) || !(lr >= 0.0f)) return FBQ_ERR_SHAPE;
+    if (!W || !H16 || !At32 || !Bt32 || !qweight_out || !scales_out || !zeros_out || !At16_out || !Bt16_out || !grad_At ||
+        !grad_Bt || !loss || !workspace)
+        return FBQ_ERR_NULL;
+    if (misaligned(W) || misaligned(H16) || misaligned(At32) || misaligned(Bt32) || misaligned(qweight_out) ||
+        misaligned(scales_out) || misaligned(zeros_out) || misaligned(At16_out) || misaligned(Bt16_out) || misaligned(grad_At) ||
+        misaligned(grad_Bt) || misaligned(workspace))
+        return FBQ_ERR_ALIGN;
+    if (workspace_bytes < train_workspace_bytes(d->N, d->K, d->r, 1)) return FBQ_ERR_WORKSPACE;
+    TrainArgs a{};
+    a.d = *d;
+    a.W = (const uint16_t *)W; a.H16 = (const uint16_t *)H16; a.h_scale = h_scale; a.lr = lr;
+    a.At32 = At32; a.Bt32 = Bt32;
+    a.qw = (uint32_t *)qweight_out; a.scales = (uint16_t *)scales_out; a.zeros = (uint16_t *)zeros_out;
+    a.At16 = (uint16_t *)At16_out; a.Bt16 = (uint16_t *)Bt16_out;
+    a.gAt = grad_At; a.gBt = grad_Bt; a.loss = loss; a.workspace = workspace;
+    return hip_status(launch_train_step(a, (hipStream_t)stream));
+}

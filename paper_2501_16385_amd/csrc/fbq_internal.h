@@ -54,6 +54,22 @@ hipError_t launch_reconstruct(const fbq_desc &d, const uint32_t *qw, const uint1
 hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t *At, const uint16_t *Bt, uint32_t *qw,
                            uint16_t *scales, uint16_t *zeros, hipStream_t stream);
 
+// Arguments of one reconstruction iteration (validated): see fbq_train_step.
+struct TrainArgs {
+    fbq_desc d;
+    const uint16_t *W;
+    const uint16_t *H16;
+    float h_scale, lr;
+    float *At32, *Bt32;
+    uint32_t *qw;
+    uint16_t *scales, *zeros, *At16, *Bt16;
+    float *gAt, *gBt, *loss;
+    void *workspace;
+};
+hipError_t launch_gram(int K, int T, const uint16_t *X, float h_scale, uint16_t *H16, void *workspace, hipStream_t stream);
+hipError_t launch_train_step(const TrainArgs &a, hipStream_t stream);
+size_t train_workspace_bytes(int N, int K, int r, int T);
+
 size_t decode_workspace_bytes(int M, int K, int r);
 size_t small_m_workspace_bytes(int K, int r);
 size_t prefill_workspace_bytes(int M, int N, int K, int r);

@@ -18,7 +18,8 @@ _LIB_PATH = os.path.join(_HERE, "libfbq.so")
 _lib: Optional[ctypes.CDLL] = None
 
 EXPORTED_SYMBOLS = ["fbq_status_string", "fbq_check_desc", "fbq_packed_bytes", "fbq_workspace_bytes", "fbq_pack",
-                    "fbq_linear", "fbq_linear_group", "fbq_reconstruct", "fbq_unpack_codes", "fbq_quantize_feedback"]
+                    "fbq_linear", "fbq_linear_group", "fbq_reconstruct", "fbq_unpack_codes", "fbq_quantize_feedback",
+                    "fbq_train_workspace_bytes", "fbq_gram", "fbq_train_step"]
 
 
 class FbqError(RuntimeError):
@@ -83,6 +84,13 @@ def load() -> ctypes.CDLL:
         lib.fbq_unpack_codes.argtypes = [dp] + [vp] * 3
         lib.fbq_quantize_feedback.restype = i32
         lib.fbq_quantize_feedback.argtypes = [dp] + [vp] * 7
+        f32 = ctypes.c_float
+        lib.fbq_train_workspace_bytes.restype = sz
+        lib.fbq_train_workspace_bytes.argtypes = [dp, i32]
+        lib.fbq_gram.restype = i32
+        lib.fbq_gram.argtypes = [dp, i32, vp, f32, vp, vp, sz, vp]
+        lib.fbq_train_step.restype = i32
+        lib.fbq_train_step.argtypes = [dp, vp, vp, f32, vp, vp, f32] + [vp] * 9 + [sz, vp]
         _lib = lib
     return _lib
 
@@ -260,3 +268,55 @@ def quantize_feedback(d: Desc, W, At=None, Bt=None, stream=None) -> DeviceLayer:
                                       _dev_ptr(z), _stream(stream))
     _check(rc, "fbq_quantize_feedback")
     return DeviceLayer(d, qw, s, z, At, Bt)
+
+
+def train_workspace_bytes(d: Desc, T: int) -> int:
+    return int(load().fbq_train_workspace_bytes(ctypes.byref(d.c()), int(T)))
+
+
+def gram(d: Desc, X, h_scale: float, workspace=None, stream=None):
+    """fbq_gram: X [T, K] fp16 device tensor -> fp16(h_scale * X^T X) [K, K] device tensor."""
+    import torch
+    T = int(X.shape[0])
+    if workspace is None:
+        workspace = torch.empty(max(256, train_workspace_bytes(d, T)), dtype=torch.uint8, device=X.device)
+    H16 = torch.empty((d.K, d.K), dtype=torch.float16, device=X.device)
+    rc = load().fbq_gram(ctypes.byref(d.c()), T, _dev_ptr(X), float(h_scale), _dev_ptr(H16), _dev_ptr(workspace),
+                         workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "fbq_gram")
+    return H16
+
+
+@dataclass
+class TrainState:
+    """Device tensors one reconstruction iteration reads and writes (allocated once, reused every step)."""
+    desc: Desc
+    At32: "object"        # [r, K] fp32 master, updated in place
+    Bt32: "object"        # [N, r] fp32 master, updated in place
+    layer: DeviceLayer    # the layer as it was BEFORE the last step's update (fp16 branch, codes, scales, zeros)
+    grad_At: "object"
+    grad_Bt: "object"
+    loss: "object"        # 1 fp32
+    workspace: "object"
+
+
+def train_state(d: Desc, At32, Bt32) -> TrainState:
+    import torch
+    dev = At32.device
+    G = d.K // d.group
+    layer = DeviceLayer(d, torch.empty((d.N, packed_bytes(d) // 4 // d.N), dtype=torch.int32, device=dev),
+                        torch.empty((d.N, G), dtype=torch.int16, device=dev), torch.empty((d.N, G), dtype=torch.int16, device=dev),
+                        torch.empty((d.r, d.K), dtype=torch.int16, device=dev), torch.empty((d.N, d.r), dtype=torch.int16, device=dev))
+    return TrainState(d, At32, Bt32, layer, torch.empty((d.r, d.K), dtype=torch.float32, device=dev),
+                      torch.empty((d.N, d.r), dtype=torch.float32, device=dev), torch.empty(1, dtype=torch.float32, device=dev),
+                      torch.empty(max(256, train_workspace_bytes(d, 1)), dtype=torch.uint8, device=dev))
+
+
+def train_step(st: TrainState, W, H16, h_scale: float, lr: float, stream=None) -> None:
+    """fbq_train_step: one loop-body iteration of Alg. 1 on the state's masters."""
+    d, l = st.desc, st.layer
+    rc = load().fbq_train_step(ctypes.byref(d.c()), _dev_ptr(W), _dev_ptr(H16), float(h_scale), _dev_ptr(st.At32),
+                               _dev_ptr(st.Bt32), float(lr), _dev_ptr(l.qweight), _dev_ptr(l.scales), _dev_ptr(l.zeros),
+                               _dev_ptr(l.At), _dev_ptr(l.Bt), _dev_ptr(st.grad_At), _dev_ptr(st.grad_Bt), _dev_ptr(st.loss),
+                               _dev_ptr(st.workspace), st.workspace.numel() * st.workspace.element_size(), _stream(stream))
+    _check(rc, "fbq_train_step")

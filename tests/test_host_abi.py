@@ -65,6 +65,29 @@ def test_linear_argument_errors_without_launch():
     assert lib.fbq_quantize_feedback(ctypes.byref(d.c()), ok, ok, ok, odd, ok, ok, None) == 4
 
 
+def test_training_argument_errors_without_launch():
+    lib = fbq.load()
+    d = fbq.Desc(256, 512, 16, 4)
+    ok, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004)
+    need = fbq.train_workspace_bytes(d, 100)
+    assert need >= 2 * 256 * 512 * 2 and need % 256 == 0
+    assert fbq.train_workspace_bytes(fbq.Desc(256, 512, 0, 4), 100) == 0 and fbq.train_workspace_bytes(d, 0) == 0
+    assert fbq.train_workspace_bytes(d, 1 << 16) >= 512 * (1 << 16) * 2       # x transposed
+    gram = lambda T, X, hs, ws, wb: lib.fbq_gram(ctypes.byref(d.c()), T, X, hs, ok, ws, wb, None)
+    assert gram(0, ok, 1.0, ok, need) == 2
+    assert gram(100, ok, 0.0, ok, need) == 2         # h_scale must be positive
+    assert gram(100, None, 1.0, ok, need) == 1
+    assert gram(100, odd, 1.0, ok, need) == 4
+    assert gram(100, ok, 1.0, ok, 64) == 5
+    step = lambda dd, W, hs, lr, wb: lib.fbq_train_step(ctypes.byref(dd.c()), W, ok, hs, ok, ok, lr, ok, ok, ok, ok, ok, ok, ok, ok,
+                                                        ok, wb, None)
+    assert step(fbq.Desc(256, 512, 0, 4), ok, 1.0, 0.1, need) == 2      # no branch to train
+    assert step(d, ok, 1.0, -1.0, need) == 2
+    assert step(d, None, 1.0, 0.1, need) == 1
+    assert step(d, odd, 1.0, 0.1, need) == 4
+    assert step(d, ok, 1.0, 0.1, 1024) == 5
+
+
 @pytest.mark.parametrize("bits", [3, 4])
 def test_host_pack_writes_the_documented_layout(bits):
     rng = np.random.Generator(np.random.Philox(900 + bits))
