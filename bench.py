@@ -306,6 +306,9 @@ def main():
             fam[name] = {"shape": f"{wide.K}->{wide.N}", "us": t["us"], "GBps": t["GBps"], "TFLOPps": t["TFLOPps"],
                          "frac_of_hbm_peak": round(t["GBps"] / HBM_PEAK_GBS, 4),
                          "frac_of_fp16_mfma_peak": round(t["TFLOPps"] / 2500.0, 4)}
+        # layer-wise reconstruction (Alg. 1) on the 4096 x 4096 shape of the set, 2048 calibration tokens
+        sq = min(specs, key=lambda s: s.N * s.K)
+        fam["reconstruction_step"] = perf.time_train_step(sq.N, sq.K, sq.r, sq.bits, 2048, iters=20, warmup=3)
         out["other_kernel_families"] = fam
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, args.config, M, args.cpu_seconds)

@@ -186,8 +186,9 @@ fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, const void *A
  * is formed once per layer and every iteration works from it.
  *
  * fbq_train_workspace_bytes - device scratch for fbq_gram (T tokens) and fbq_train_step: x
- *   transposed, or fp16 copies of the branch, Delta_F in both orientations, Delta_F H and the
- *   tiles' shares of the loss (about 6 N K bytes).  0 for an invalid descriptor, r < 1 or T < 1.
+ *   transposed, or fp16 copies of the branch, Delta_F in both orientations, the r-row products
+ *   and the partial sums of contractions whose K range is split over blocks (about 4 N K bytes).
+ *   0 for an invalid descriptor, r < 1 or T < 1.
  *
  * fbq_gram - H16_out [K,K] fp16 = fp16(h_scale * X^T X), accumulated in fp32 on the matrix cores.
  *   X device [T,K] fp16.  h_scale > 0 keeps H inside fp16's range: h_scale * max_k sum_t x[t,k]^2
@@ -204,8 +205,10 @@ fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, const void *A
  *           qweight_out, scales_out, zeros_out = Q(W - Sigma16) exactly as fbq_quantize_feedback
  *           would write them; grad_At [r,K], grad_Bt [N,r] fp32 = dL/dAt, dL/dBt with W and
  *           Q(W - Sigma16) held constant; loss: one fp32 = || W X^T - W_F X^T ||_F^2 (the square:
- *           the trace form and the printed gradient are those of the squared norm).
- *   lr = 0 evaluates without moving the masters.  Delta_F, H and Delta_F H enter the matrix
+ *           the trace form and the printed gradient are those of the squared norm), or NULL:
+ *           the gradients need only products with r rows (H is symmetric, so Delta_F H At^T =
+ *           Delta_F (At H)^T), the loss alone needs Delta_F H (2 N K^2 flop) and is skipped then.
+ *   lr = 0 evaluates without moving the masters.  Delta_F, H and their products enter the matrix
  *   cores as fp16 with fp32 accumulation: gradients and loss carry a relative error of a few 1e-4.
  *   Nothing is allocated; everything is enqueued on `stream`.  Needs r >= 1.
  * Errors: FBQ_ERR_NULL, _SHAPE, _UNSUPPORTED, _ALIGN, _WORKSPACE before any launch; FBQ_ERR_HIP.

@@ -289,7 +289,7 @@ extern "C" fbq_status fbq_train_step(const fbq_desc *d, const void *W, const voi
     if (st != FBQ_OK) return st;
     if (d->r < 1 || !(h_scale > 0.0f) || !(lr >= 0.0f)) return FBQ_ERR_SHAPE;
     if (!W || !H16 || !At32 || !Bt32 || !qweight_out || !scales_out || !zeros_out || !At16_out || !Bt16_out || !grad_At ||
-        !grad_Bt || !loss || !workspace)
+        !grad_Bt || !workspace)
         return FBQ_ERR_NULL;
     if (misaligned(W) || misaligned(H16) || misaligned(At32) || misaligned(Bt32) || misaligned(qweight_out) ||
         misaligned(scales_out) || misaligned(zeros_out) || misaligned(At16_out) || misaligned(Bt16_out) || misaligned(grad_At) ||

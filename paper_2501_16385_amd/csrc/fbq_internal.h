@@ -51,8 +51,10 @@ hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_unpack(const fbq_desc &d, const uint32_t *qw, uint8_t *codes, hipStream_t stream);
 hipError_t launch_reconstruct(const fbq_desc &d, const uint32_t *qw, const uint16_t *scales, const uint16_t *zeros,
                               const uint16_t *At, const uint16_t *Bt, float *W_hat, hipStream_t stream);
+// D16 / Dt16 (optional): Delta_F times `gain` as fp16, [N][K] and transposed [K][ldt] (ldt a multiple of 64, >= N).
 hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t *At, const uint16_t *Bt, uint32_t *qw,
-                           uint16_t *scales, uint16_t *zeros, hipStream_t stream);
+                           uint16_t *scales, uint16_t *zeros, hipStream_t stream, uint16_t *D16 = nullptr,
+                           uint16_t *Dt16 = nullptr, int ldt = 0, float gain = 0.0f);
 
 // Arguments of one reconstruction iteration (validated): see fbq_train_step.
 struct TrainArgs {

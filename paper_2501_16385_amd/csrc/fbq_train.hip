@@ -6,15 +6,19 @@
 // detached), so H is formed once per layer and an iteration is
 //
 //   A16, B16   <- fp16 of the fp32 masters                               (cast kernel)
-//   q, s, z    <- Q(W - Sigma16)               feedback quantizer        (fbq_quantize_kernel)
-//   Delta_F    <- W - s (q - z) - Sigma16      Sigma16 by matrix cores   (GEMM, "delta" epilogue)
-//   P          <- Delta_F H                    the dominant contraction  (GEMM, 2 N K^2 flop)
-//   L          <- sum Delta_F o P                                        (same launch, then a reduction)
-//   dL/dBt     <- -2 P At^T           [N,r]                              (GEMM)
-//   dL/dAt     <- -2 (Bt^T Delta_F) H [r,K]                              (two GEMMs)
+//   q, s, z    <- Q(W - Sigma16)               feedback quantizer  } fbq_quantize_kernel: fp64, Delta_F
+//   Delta_F    <- (W - Sigma16) - s (q - z)                        } from the registers that hold W - Sigma16
+//   Q          <- Bt^T Delta_F        [r,K]                              (GEMM, K split)
+//   dL/dAt     <- -2 Q H              [r,K]    } one GEMM on the stacked                                 
+//   V^T        <- At H                [r,K]    } operand [Q; At], K split
+//   dL/dBt     <- -2 Delta_F V        [N,r]                              (GEMM, K split)
+//   L          <- sum Delta_F o (Delta_F H)    only if the caller asks   (GEMM, 2 N K^2 flop, + reduction)
 //   masters    <- masters - lr gradient                                  (update kernel)
 //
-// with Sigma[n,k] = sum_j Bt[n,j] At[j,k] in the device layouts At [r,K], Bt [N,r].
+// with Sigma[n,k] = sum_j Bt[n,j] At[j,k] in the device layouts At [r,K], Bt [N,r].  Multiplying
+// Delta_F H out costs 2 N K^2 flop; the gradients need only products with r rows or columns
+// (8 N K r + 4 r K^2 flop, a twentieth of that at r = 64, K = 4096) because H is symmetric:
+// Delta_F H At^T = Delta_F (At H)^T.  The loss is the one quantity that needs Delta_F H itself.
 //
 // One matrix-core kernel serves every contraction: C[m,n] = sum_k A[m,k] B[n,k] with both operands
 // contiguous along k (fp16 in, fp32 accumulate, v_mfma_f32_32x32x16_f16).  128x128 block tile,
@@ -42,21 +46,18 @@ constexpr int kStepK = 64;           // k per step: one 128-byte row segment per
 constexpr float kDeltaGain = 256.0f; // Delta_F is stored as fp16(256 Delta_F)
 constexpr int kXcds = 8;
 
-enum { kEpiStore = 0, kEpiDelta = 1 };
-
 struct GemmArgs {
     const uint16_t *A;   // [Mr][lda] fp16
     const uint16_t *B;   // [Nr][ldb] fp16
     int Mr, Nr, Kd;      // Kd a multiple of 64
     int lda, ldb;        // elements
     // store epilogue (any of the three may be absent)
-    float *C32; int ldc32; float alpha;          // C32[m,n] = alpha acc
-    uint16_t *C16; int ldc16; float beta;        // C16[m,n] = fp16(beta acc)
-    const uint16_t *D; int ldd; float *dot;      // dot[tile] = sum over the tile of acc D[m,n]
-    // delta epilogue: acc is Sigma[m,n] (m a weight row, n an input feature)
-    const uint16_t *W; const uint32_t *qw; const uint16_t *scales; const uint16_t *zeros;
-    uint16_t *D16; uint16_t *Dt16; int ldt;      // D16 [Mr][Nr], Dt16 [Nr][ldt] = its transpose; both 256 Delta_F
-    int bits, row_words;
+    float *C32; int ldc32; float alpha; int c32_rows;   // C32[m,n] = alpha acc for rows m < c32_rows
+    uint16_t *C16; int ldc16; float beta; int c16_row0; // C16[m - c16_row0, n] = fp16(beta acc) for rows m >= c16_row0
+    const uint16_t *D; int ldd; float *dot;      // dot[tile] = sum over the tile of acc D[m,n]  (splits == 1 only)
+    // K split over `splits` blocks per tile (few tiles, long K): raw sums go to part [splits][Mr][Nr]
+    // and fbq_sum_splits_kernel applies the store epilogue
+    int splits; float *part;
 };
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t rows_buffer(const void *p, long bytes)
@@ -69,18 +70,12 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t rows_buffer(const void *p, lon
 // bytes per clock.
 __device__ __forceinline__ int swizzle_key(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
 
-__device__ __forceinline__ uint32_t packed_code(const uint32_t *row, int bits, int k)
+__device__ __forceinline__ void store_result(const GemmArgs &g, int m, int n, float a)
 {
-    if (bits == 4) return (row[k >> 3] >> ((k & 7) * 4)) & 15u;
-    const uint32_t *u = row + (k >> 5) * 3;
-    const int j = k & 31;
-    if (j == 30) return ((u[0] >> 15) & 1u) | (((u[1] >> 15) & 1u) << 1) | (((u[2] >> 15) & 1u) << 2);
-    if (j == 31) return (u[0] >> 31) | ((u[1] >> 31) << 1) | ((u[2] >> 31) << 2);
-    const int wd = j / 10, f = j % 10;
-    return (u[wd] >> (f < 5 ? 3 * f : 16 + 3 * (f - 5))) & 7u;
+    if (g.C32 && m < g.c32_rows) g.C32[(size_t)m * g.ldc32 + n] = g.alpha * a;
+    if (g.C16 && m >= g.c16_row0) g.C16[(size_t)(m - g.c16_row0) * g.ldc16 + n] = __builtin_bit_cast(uint16_t, (half_t)(g.beta * a));
 }
 
-template <int EPI>
 __global__ __launch_bounds__(256, 2) void fbq_gemm_nt_kernel(GemmArgs g)
 {
     __shared__ __align__(16) unsigned char lds[2 * 2 * kTile * kStepK * 2];   // [buffer][operand][row][128 bytes]
@@ -88,9 +83,10 @@ __global__ __launch_bounds__(256, 2) void fbq_gemm_nt_kernel(GemmArgs g)
 
     // Consecutive tiles (same rows of A, neighbouring rows of B) run on the same XCD and share its L2.
     const int tiles_n = (g.Nr + kTile - 1) / kTile, tiles_m = (g.Mr + kTile - 1) / kTile;
-    const int total = tiles_m * tiles_n, per_xcd = (total + kXcds - 1) / kXcds;
-    const int tile = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-    if (tile >= total) return;
+    const int total = tiles_m * tiles_n * g.splits, per_xcd = (total + kXcds - 1) / kXcds;
+    const int unit = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (unit >= total) return;
+    const int tile = unit / g.splits, split = unit % g.splits;
     const int m0 = (tile / tiles_n) * kTile, n0 = (tile % tiles_n) * kTile;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -152,19 +148,20 @@ __global__ __launch_bounds__(256, 2) void fbq_gemm_nt_kernel(GemmArgs g)
         }
     };
 
-    const int steps = g.Kd / kStepK;
-    fetch(0);
+    const int all_steps = g.Kd / kStepK, per_split = (all_steps + g.splits - 1) / g.splits;
+    const int first = split * per_split, steps = min(all_steps, first + per_split) - first;   // >= 1: the launcher sees to it
+    fetch(first);
     stash(0);
     __syncthreads();
     for (int s = 0; s < steps; ++s) {
-        if (s + 1 < steps) fetch(s + 1);
+        if (s + 1 < steps) fetch(first + s + 1);
         multiply(s & 1);
         if (s + 1 < steps) stash((s + 1) & 1);   // the other buffer: every wave finished reading it before the last barrier
         __syncthreads();
     }
 
     // accumulator register v of a lane: row 8 (v / 4) + 4 h + v % 4 of the 32x32 tile, column `col`
-    if (EPI == kEpiStore) {
+    {
         float dot = 0.0f;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -176,8 +173,11 @@ __global__ __launch_bounds__(256, 2) void fbq_gemm_nt_kernel(GemmArgs g)
                     const int m = m0 + wm * 64 + i * 32 + 8 * (v / 4) + 4 * h + (v % 4);
                     if (m >= g.Mr || n >= g.Nr) continue;
                     const float a = acc[i][j][v];
-                    if (g.C32) g.C32[(size_t)m * g.ldc32 + n] = g.alpha * a;
-                    if (g.C16) g.C16[(size_t)m * g.ldc16 + n] = __builtin_bit_cast(uint16_t, (half_t)(g.beta * a));
+                    if (g.splits > 1) {
+                        g.part[((size_t)split * g.Mr + m) * g.Nr + n] = a;
+                        continue;
+                    }
+                    store_result(g, m, n, a);
                     if (g.D) dot = fmaf(a, (float)__builtin_bit_cast(half_t, g.D[(size_t)m * g.ldd + n]), dot);
                 }
             }
@@ -190,45 +190,44 @@ __global__ __launch_bounds__(256, 2) void fbq_gemm_nt_kernel(GemmArgs g)
             __syncthreads();
             if (tid == 0) g.dot[tile] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
         }
-    } else {
-        // Delta_F = W - s (q - z) - Sigma for weight row m and input feature n, times 256, in both orientations
-        const int G = g.Nr / kGroup;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int n = n0 + wn * 64 + j * 32 + col;
-                if (n >= g.Nr) continue;
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    const int mb = m0 + wm * 64 + i * 32 + 8 * vq + 4 * h;
-                    half4_t out;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int m = mb + e;
-                        float val = 0.0f;
-                        if (m < g.Mr) {
-                            const float w = (float)__builtin_bit_cast(half_t, g.W[(size_t)m * g.Nr + n]);
-                            const float s = (float)__builtin_bit_cast(half_t, g.scales[(size_t)m * G + n / kGroup]);
-                            const float z = (float)__builtin_bit_cast(half_t, g.zeros[(size_t)m * G + n / kGroup]);
-                            const float q = (float)packed_code(g.qw + (size_t)m * g.row_words, g.bits, n);
-                            val = kDeltaGain * (w - s * (q - z) - acc[i][j][vq * 4 + e]);
-                            g.D16[(size_t)m * g.Nr + n] = __builtin_bit_cast(uint16_t, (half_t)val);
-                        }
-                        out[e] = (half_t)val;
-                    }
-                    if (mb < g.ldt) *reinterpret_cast<half4_t *>(g.Dt16 + (size_t)n * g.ldt + mb) = out;   // rows past Mr: zeros
-                }
-            }
     }
 }
 
-static hipError_t launch_gemm(const GemmArgs &g, int epi, hipStream_t stream)
+// The store epilogue over the sum of the K splits' partial results, splits in index order.
+__global__ __launch_bounds__(256) void fbq_sum_splits_kernel(GemmArgs g)
 {
-    const int tiles = ceil_div(g.Mr, kTile) * ceil_div(g.Nr, kTile);
-    const dim3 grid(ceil_div(tiles, kXcds) * kXcds);
-    if (epi == kEpiStore) hipLaunchKernelGGL(fbq_gemm_nt_kernel<kEpiStore>, grid, dim3(256), 0, stream, g);
-    else hipLaunchKernelGGL(fbq_gemm_nt_kernel<kEpiDelta>, grid, dim3(256), 0, stream, g);
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x, count = (size_t)g.Mr * g.Nr;
+    if (i >= count) return;
+    float a = 0.0f;
+    for (int sp = 0; sp < g.splits; ++sp) a += g.part[(size_t)sp * count + i];
+    store_result(g, (int)(i / g.Nr), (int)(i % g.Nr), a);
+}
+
+// Blocks that split K for one tile: enough to give every CU a block when the tiles alone do not,
+// at least 4 steps each, and none left without a step.
+static int splits_for(int Mr, int Nr, int Kd)
+{
+    const int tiles = ceil_div(Mr, kTile) * ceil_div(Nr, kTile), steps = Kd / kStepK;
+    const int want = std::min(256 / std::max(tiles, 1), steps / 4);
+    if (want < 2) return 1;
+    return ceil_div(steps, ceil_div(steps, want));
+}
+
+static size_t split_scratch_bytes(int Mr, int Nr, int Kd)
+{
+    const int sp = splits_for(Mr, Nr, Kd);
+    return sp > 1 ? (size_t)sp * Mr * Nr * 4 : 0;
+}
+
+static hipError_t launch_gemm(GemmArgs g, float *split_scratch, hipStream_t stream)
+{
+    g.splits = (!g.dot && split_scratch) ? splits_for(g.Mr, g.Nr, g.Kd) : 1;
+    g.part = split_scratch;
+    const int units = ceil_div(g.Mr, kTile) * ceil_div(g.Nr, kTile) * g.splits;
+    const dim3 grid(ceil_div(units, kXcds) * kXcds);
+    hipLaunchKernelGGL(fbq_gemm_nt_kernel, grid, dim3(256), 0, stream, g);
+    if (g.splits > 1)
+        hipLaunchKernelGGL(fbq_sum_splits_kernel, dim3((unsigned)(((size_t)g.Mr * g.Nr + 255) / 256)), dim3(256), 0, stream, g);
     return hipGetLastError();
 }
 
@@ -236,6 +235,7 @@ static GemmArgs gemm_args(const uint16_t *A, int Mr, int lda, const uint16_t *B,
 {
     GemmArgs g{};
     g.A = A; g.B = B; g.Mr = Mr; g.Nr = Nr; g.Kd = Kd; g.lda = lda; g.ldb = ldb;
+    g.c32_rows = Mr; g.c16_row0 = 0; g.splits = 1;
     return g;
 }
 
@@ -257,31 +257,21 @@ __global__ __launch_bounds__(256) void fbq_transpose_f16_kernel(const uint16_t *
 }
 
 // fp16 views of the fp32 masters: At16 [r][K] and Bt16 [N][r] (the inference layouts, outputs of the
-// step), and zero-padded operand copies: Ac [K][rp] (A, contiguous along r), Bp [N][rp], Bc [r][Np].
+// step; At16 once more as the lower half of the stacked operand [Q; At]) and Bc [r][Np] = B with
+// rows contiguous along n, columns N..Np-1 zero.
 __global__ __launch_bounds__(256) void fbq_cast_masters_kernel(const float *__restrict__ At32, const float *__restrict__ Bt32,
                                                                uint16_t *__restrict__ At16, uint16_t *__restrict__ Bt16,
-                                                               uint16_t *__restrict__ Ac, uint16_t *__restrict__ Bp,
-                                                               uint16_t *__restrict__ Bc, int N, int K, int r, int rp, int Np)
+                                                               uint16_t *__restrict__ At16_stacked, uint16_t *__restrict__ Bc,
+                                                               int N, int K, int r, int Np)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t nA = (size_t)K * rp, nB = (size_t)N * rp, nC = (size_t)r * Np;
+    const size_t nA = (size_t)r * K, nB = (size_t)N * r, nC = (size_t)r * Np;
     if (i < nA) {
-        const int k = (int)(i / rp), j = (int)(i % rp);
-        uint16_t v = 0;
-        if (j < r) {
-            v = __builtin_bit_cast(uint16_t, (half_t)At32[(size_t)j * K + k]);
-            At16[(size_t)j * K + k] = v;
-        }
-        Ac[i] = v;
+        const uint16_t v = __builtin_bit_cast(uint16_t, (half_t)At32[i]);
+        At16[i] = v;
+        At16_stacked[i] = v;
     } else if (i < nA + nB) {
-        const size_t e = i - nA;
-        const int n = (int)(e / rp), j = (int)(e % rp);
-        uint16_t v = 0;
-        if (j < r) {
-            v = __builtin_bit_cast(uint16_t, (half_t)Bt32[(size_t)n * r + j]);
-            Bt16[(size_t)n * r + j] = v;
-        }
-        Bp[e] = v;
+        Bt16[i - nA] = __builtin_bit_cast(uint16_t, (half_t)Bt32[i - nA]);
     } else if (i < nA + nB + nC) {
         const size_t e = i - nA - nB;
         const int j = (int)(e / Np), n = (int)(e % Np);
@@ -316,90 +306,91 @@ __global__ __launch_bounds__(256) void fbq_descent_kernel(float *__restrict__ At
 static size_t pad256(size_t b) { return (b + 255) & ~(size_t)255; }
 static int pad64(int v) { return (v + 63) & ~63; }
 
+constexpr float kVGain = 64.0f;      // V^T = At H is stored as fp16(64 h_scale At H)
+
 struct TrainLayout {
-    size_t Ac, Bp, Bc, D16, Dt16, P16, Q16, dot, total;
+    size_t Bc, D16, Dt16, S16, Vt16, dot, split, total;
 };
 
 static TrainLayout train_layout(int N, int K, int r)
 {
-    const int rp = pad64(r), Np = pad64(N);
+    const int Np = pad64(N);
     TrainLayout l{};
     size_t o = 0;
-    l.Ac = o;   o += pad256((size_t)K * rp * 2);
-    l.Bp = o;   o += pad256((size_t)N * rp * 2);
     l.Bc = o;   o += pad256((size_t)r * Np * 2);
     l.D16 = o;  o += pad256((size_t)N * K * 2);
     l.Dt16 = o; o += pad256((size_t)K * Np * 2);
-    l.P16 = o;  o += pad256((size_t)N * K * 2);
-    l.Q16 = o;  o += pad256((size_t)r * K * 2);
+    l.S16 = o;  o += pad256((size_t)2 * r * K * 2);          // stacked operand [Q; At]
+    l.Vt16 = o; o += pad256((size_t)r * K * 2);
     l.dot = o;  o += pad256((size_t)ceil_div(N, kTile) * ceil_div(K, kTile) * 4);
+    l.split = o;
+    o += pad256(std::max(std::max(split_scratch_bytes(r, K, Np), split_scratch_bytes(2 * r, K, K)), split_scratch_bytes(N, r, K)));
     l.total = o;
     return l;
 }
 
 size_t train_workspace_bytes(int N, int K, int r, int T)
 {
-    return std::max(train_layout(N, K, r).total, pad256((size_t)K * pad64(T) * 2));
+    const int Tp = pad64(T);
+    return std::max(train_layout(N, K, r).total, pad256((size_t)K * Tp * 2) + pad256(split_scratch_bytes(K, K, Tp)));
 }
 
 hipError_t launch_gram(int K, int T, const uint16_t *X, float h_scale, uint16_t *H16, void *workspace, hipStream_t stream)
 {
     const int Tp = pad64(T);
     uint16_t *Xt = (uint16_t *)workspace;                       // [K][Tp], tokens past T zero
+    float *scratch = (float *)((unsigned char *)workspace + pad256((size_t)K * Tp * 2));
     hipLaunchKernelGGL(fbq_transpose_f16_kernel, dim3(ceil_div(K, 32), ceil_div(Tp, 32)), dim3(32, 8), 0, stream, X, Xt, T, K, Tp);
     GemmArgs g = gemm_args(Xt, K, Tp, Xt, K, Tp, Tp);
     g.C16 = H16; g.ldc16 = K; g.beta = h_scale;
-    return launch_gemm(g, kEpiStore, stream);
+    return launch_gemm(g, scratch, stream);
 }
 
 hipError_t launch_train_step(const TrainArgs &a, hipStream_t stream)
 {
-    const int N = a.d.N, K = a.d.K, r = a.d.r, rp = pad64(r), Np = pad64(N);
+    const int N = a.d.N, K = a.d.K, r = a.d.r, Np = pad64(N);
     const TrainLayout l = train_layout(N, K, r);
     unsigned char *ws = (unsigned char *)a.workspace;
-    uint16_t *Ac = (uint16_t *)(ws + l.Ac), *Bp = (uint16_t *)(ws + l.Bp), *Bc = (uint16_t *)(ws + l.Bc);
-    uint16_t *D16 = (uint16_t *)(ws + l.D16), *Dt16 = (uint16_t *)(ws + l.Dt16), *P16 = (uint16_t *)(ws + l.P16);
-    uint16_t *Q16 = (uint16_t *)(ws + l.Q16);
-    float *dot = (float *)(ws + l.dot);
+    uint16_t *Bc = (uint16_t *)(ws + l.Bc);
+    uint16_t *D16 = (uint16_t *)(ws + l.D16), *Dt16 = (uint16_t *)(ws + l.Dt16);
+    uint16_t *S16 = (uint16_t *)(ws + l.S16), *Vt16 = (uint16_t *)(ws + l.Vt16);
+    float *dot = (float *)(ws + l.dot), *scratch = (float *)(ws + l.split);
     const int tiles = ceil_div(N, kTile) * ceil_div(K, kTile);
 
     // fp16 views of the masters: what the forward pass of Alg. 1 computes with
-    const size_t casts = (size_t)K * rp + (size_t)N * rp + (size_t)r * Np;
+    const size_t casts = (size_t)r * K + (size_t)N * r + (size_t)r * Np;
     hipLaunchKernelGGL(fbq_cast_masters_kernel, dim3((unsigned)((casts + 255) / 256)), dim3(256), 0, stream, a.At32, a.Bt32, a.At16,
-                       a.Bt16, Ac, Bp, Bc, N, K, r, rp, Np);
-    // Q(W - Sigma16): the feedback quantizer, written in the inference layout
-    hipError_t e = launch_quantize(a.d, a.W, a.At16, a.Bt16, a.qw, a.scales, a.zeros, stream);
+                       a.Bt16, S16 + (size_t)r * K, Bc, N, K, r, Np);
+    // Q(W - Sigma16), written in the inference layout, and Delta_F = (W - Sigma16) - Q(W - Sigma16), times 256,
+    // in both orientations
+    hipError_t e = launch_quantize(a.d, a.W, a.At16, a.Bt16, a.qw, a.scales, a.zeros, stream, D16, Dt16, Np, kDeltaGain);
     if (e != hipSuccess) return e;
-    // Delta_F = W - Q(W - Sigma16) - Sigma16, Sigma16[n,k] = sum_j Bt16[n,j] A16[k,j]
-    {
-        GemmArgs g = gemm_args(Bp, N, rp, Ac, K, rp, rp);
-        g.W = a.W; g.qw = a.qw; g.scales = a.scales; g.zeros = a.zeros;
-        g.D16 = D16; g.Dt16 = Dt16; g.ldt = Np; g.bits = a.d.bits; g.row_words = (int)row_words(K, a.d.bits);
-        if ((e = launch_gemm(g, kEpiDelta, stream)) != hipSuccess) return e;
-    }
-    // P = Delta_F H (H symmetric), kept as fp16(256 h_scale P); the tiles' shares of sum Delta_F o P
-    {
-        GemmArgs g = gemm_args(D16, N, K, a.H16, K, K, K);
-        g.C16 = P16; g.ldc16 = K; g.beta = 1.0f;
-        g.D = D16; g.ldd = K; g.dot = dot;
-        if ((e = launch_gemm(g, kEpiStore, stream)) != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL(fbq_loss_kernel, dim3(1), dim3(256), 0, stream, dot, tiles, 1.0f / (kDeltaGain * kDeltaGain * a.h_scale), a.loss);
-    const float gscale = -2.0f / (kDeltaGain * a.h_scale);
-    // dL/dBt = -2 P At^T
-    {
-        GemmArgs g = gemm_args(P16, N, K, a.At16, r, K, K);
-        g.C32 = a.gBt; g.ldc32 = r; g.alpha = gscale;
-        if ((e = launch_gemm(g, kEpiStore, stream)) != hipSuccess) return e;
-    }
-    // dL/dAt = -2 (Bt^T Delta_F) H
+    // Q = Bt^T Delta_F (times 256), the upper half of the stacked operand
     {
         GemmArgs g = gemm_args(Bc, r, Np, Dt16, K, Np, Np);
-        g.C16 = Q16; g.ldc16 = K; g.beta = 1.0f;
-        if ((e = launch_gemm(g, kEpiStore, stream)) != hipSuccess) return e;
-        GemmArgs g2 = gemm_args(Q16, r, K, a.H16, K, K, K);
-        g2.C32 = a.gAt; g2.ldc32 = K; g2.alpha = gscale;
-        if ((e = launch_gemm(g2, kEpiStore, stream)) != hipSuccess) return e;
+        g.C16 = S16; g.ldc16 = K; g.beta = 1.0f;
+        if ((e = launch_gemm(g, scratch, stream)) != hipSuccess) return e;
+    }
+    // [Q; At] H (H symmetric): rows of Q give dL/dAt = -2 Q H, rows of At give V^T = At H
+    {
+        GemmArgs g = gemm_args(S16, 2 * r, K, a.H16, K, K, K);
+        g.C32 = a.gAt; g.ldc32 = K; g.alpha = -2.0f / (kDeltaGain * a.h_scale); g.c32_rows = r;
+        g.C16 = Vt16; g.ldc16 = K; g.beta = kVGain; g.c16_row0 = r;
+        if ((e = launch_gemm(g, scratch, stream)) != hipSuccess) return e;
+    }
+    // dL/dBt = -2 Delta_F H At^T = -2 Delta_F V
+    {
+        GemmArgs g = gemm_args(D16, N, K, Vt16, r, K, K);
+        g.C32 = a.gBt; g.ldc32 = r; g.alpha = -2.0f / (kDeltaGain * kVGain * a.h_scale);
+        if ((e = launch_gemm(g, scratch, stream)) != hipSuccess) return e;
+    }
+    // L = sum Delta_F o (Delta_F H): the only use of the full product, and only on request
+    if (a.loss) {
+        GemmArgs g = gemm_args(D16, N, K, a.H16, K, K, K);
+        g.D = D16; g.ldd = K; g.dot = dot;
+        if ((e = launch_gemm(g, nullptr, stream)) != hipSuccess) return e;
+        hipLaunchKernelGGL(fbq_loss_kernel, dim3(1), dim3(256), 0, stream, dot, tiles, 1.0f / (kDeltaGain * kDeltaGain * a.h_scale),
+                           a.loss);
     }
     // gradient descent on the masters
     const size_t nA = (size_t)r * K, nB = (size_t)N * r;

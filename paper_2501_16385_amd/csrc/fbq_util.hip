@@ -90,37 +90,73 @@ __device__ uint16_t double_to_half_bits(double d)
     return bits >= 0x7c00u ? (sign | 0x7c00u) : (sign | (uint16_t)bits);
 }
 
-// One block of 128 threads per (row, group).  fp64 with no fused multiply-add, so that the result
-// does not depend on contraction choices.
+// One block of 128 threads per group of 128 input features and kQuantRows consecutive rows: thread i
+// keeps column k = 128 g + i of At in registers (32 taps at a time) and walks over the rows with it,
+// so At is read once per 16 rows and Bt is converted once per block (LDS, broadcast reads).  fp64, the
+// taps in index order, no contraction left to the compiler; the one fused multiply-add is exact
+// by construction: the product of two fp16 values has 22 significant bits and is exact in fp64, so
+// fma(a, b, c) and (a * b) + c round the same number.
+// With D16 / Dt16 given, the kernel also writes what the reconstruction step needs from the same
+// registers: Delta_F = (W - Sigma) - s (q - z), times `gain`, as fp16 in both orientations
+// (D16 [N][K]; Dt16 [K][ldt] with columns N..ldt-1 zero).
+constexpr int kQuantRows = 16;
+constexpr int kQuantTaps = 32;
+
 __global__ __launch_bounds__(128) void fbq_quantize_kernel(const uint16_t *__restrict__ W, const uint16_t *__restrict__ At,
                                                            const uint16_t *__restrict__ Bt, uint32_t *__restrict__ qw,
                                                            uint16_t *__restrict__ scales, uint16_t *__restrict__ zeros, int N,
-                                                           int K, int r, int bits, int row_words)
+                                                           int K, int r, int bits, int row_words, uint16_t *__restrict__ D16,
+                                                           uint16_t *__restrict__ Dt16, int ldt, float gain)
 {
 #pragma clang fp contract(off)
-    __shared__ double smin[128], smax[128];
-    __shared__ uint16_t sz[2];
-    __shared__ uint8_t scode[128];
-    const int n = blockIdx.y, g = blockIdx.x, i = threadIdx.x;
+    __shared__ double smin[2][kQuantRows], smax[2][kQuantRows];
+    __shared__ uint16_t sz[kQuantRows][2];
+    __shared__ uint8_t scode[kQuantRows][128];
+    __shared__ float bt[kQuantRows][kQuantTaps];      // the block's rows of Bt (fp16 values are exact in fp32; half the LDS bytes of fp64)
+    const int g = blockIdx.x, n0 = blockIdx.y * kQuantRows, i = threadIdx.x;
+    const int rows = min(kQuantRows, N - n0);
     const int k = g * kGroup + i;
     const int qmax = (1 << bits) - 1;
 
-    double sigma = 0.0;
-    for (int j = 0; j < r; ++j) sigma = sigma + half_bits_to_double(At[(size_t)j * K + k]) * half_bits_to_double(Bt[(size_t)n * r + j]);
-    const double R = half_bits_to_double(W[(size_t)n * K + k]) - sigma;       // feedback: quantize W - Sigma
-
-    smin[i] = R;
-    smax[i] = R;
-    __syncthreads();
-    for (int off = 64; off > 0; off >>= 1) {
-        if (i < off) {
-            smin[i] = fmin(smin[i], smin[i + off]);
-            smax[i] = fmax(smax[i], smax[i + off]);
+    double sigma[kQuantRows];
+#pragma unroll
+    for (int row = 0; row < kQuantRows; ++row) sigma[row] = 0.0;
+    for (int j0 = 0; j0 < r; j0 += kQuantTaps) {
+        // taps past r enter as zeros (adding 0 * b changes nothing); rows past N repeat the last row and are never stored
+        double at[kQuantTaps];
+#pragma unroll
+        for (int jj = 0; jj < kQuantTaps; ++jj) at[jj] = j0 + jj < r ? half_bits_to_double(At[(size_t)(j0 + jj) * K + k]) : 0.0;
+        __syncthreads();
+        for (int idx = i; idx < kQuantRows * kQuantTaps; idx += 128) {
+            const int row = idx / kQuantTaps, jj = idx % kQuantTaps;
+            bt[row][jj] = j0 + jj < r ? (float)__builtin_bit_cast(half_t, Bt[(size_t)min(n0 + row, N - 1) * r + j0 + jj]) : 0.0f;
         }
         __syncthreads();
+#pragma unroll
+        for (int row = 0; row < kQuantRows; ++row)
+#pragma unroll
+            for (int jj = 0; jj < kQuantTaps; ++jj) sigma[row] = __builtin_fma(at[jj], (double)bt[row][jj], sigma[row]);
     }
-    if (i == 0) {
-        const double mn = smin[0], mx = smax[0];
+
+    // feedback: quantize R = W - Sigma.  Extremes over the group: lanes by shuffles, then the two waves.
+    double R[kQuantRows];
+#pragma unroll
+    for (int row = 0; row < kQuantRows; ++row) {
+        R[row] = row < rows ? half_bits_to_double(W[(size_t)(n0 + row) * K + k]) - sigma[row] : 0.0;
+        double mn = R[row], mx = R[row];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            mn = fmin(mn, __shfl_xor(mn, off, 64));
+            mx = fmax(mx, __shfl_xor(mx, off, 64));
+        }
+        if ((i & 63) == 0) {
+            smin[i >> 6][row] = mn;
+            smax[i >> 6][row] = mx;
+        }
+    }
+    __syncthreads();
+    if (i < rows) {
+        const double mn = fmin(smin[0][i], smin[1][i]), mx = fmax(smax[0][i], smax[1][i]);
         double s = (mx - mn) / (double)qmax;
         if (!(s > 0.0)) s = 1.0;
         uint16_t s16 = double_to_half_bits(s);
@@ -133,44 +169,67 @@ __global__ __launch_bounds__(128) void fbq_quantize_kernel(const uint16_t *__res
             if ((mn / sd + zd >= -0.5 && mx / sd + zd <= (double)qmax + 0.5) || s16 >= 0x7bffu) break;
             s16 += 1;
         }
-        sz[0] = s16;
-        sz[1] = z16;
-        scales[(size_t)n * (K / kGroup) + g] = s16;
-        zeros[(size_t)n * (K / kGroup) + g] = z16;
+        sz[i][0] = s16;
+        sz[i][1] = z16;
+        scales[(size_t)(n0 + i) * (K / kGroup) + g] = s16;
+        zeros[(size_t)(n0 + i) * (K / kGroup) + g] = z16;
     }
     __syncthreads();
-    const double sd = half_bits_to_double(sz[0]), zd = half_bits_to_double(sz[1]);
-    double q = rint(R / sd + zd);                                             // ties to even
-    q = fmin(fmax(q, 0.0), (double)qmax);
-    scode[i] = (uint8_t)q;
+#pragma unroll
+    for (int row = 0; row < kQuantRows; ++row) {
+        if (row >= rows) continue;
+        const double sd = half_bits_to_double(sz[row][0]), zd = half_bits_to_double(sz[row][1]);
+        double q = rint(R[row] / sd + zd);                                    // ties to even
+        q = fmin(fmax(q, 0.0), (double)qmax);
+        scode[row][i] = (uint8_t)q;
+        R[row] = R[row] - sd * (q - zd);                                      // Delta_F (Sec. 4.2)
+    }
     __syncthreads();
+    if (D16) {
+        typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+        half8 lo, hi;
+#pragma unroll
+        for (int row = 0; row < kQuantRows; ++row) {
+            const half_t v = row < rows ? (half_t)(float)((double)gain * R[row]) : (half_t)0.0f;
+            if (row < rows) D16[(size_t)(n0 + row) * K + k] = __builtin_bit_cast(uint16_t, v);
+            if (row < 8) lo[row] = v;
+            else hi[row - 8] = v;
+        }
+        half8 *col = reinterpret_cast<half8 *>(Dt16 + (size_t)k * ldt + n0);   // n0 a multiple of 16, ldt of 64
+        col[0] = lo;
+        col[1] = hi;
+        if (n0 + kQuantRows >= N) {                                            // last block of rows: clear the padding
+            const half8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (int c = n0 + kQuantRows; c < ldt; c += 8) *reinterpret_cast<half8 *>(Dt16 + (size_t)k * ldt + c) = zero;
+        }
+    }
 
-    uint32_t *row = qw + (size_t)n * row_words;
-    if (bits == 4) {
-        if (i < 16) {
-            uint32_t w = 0;
-            for (int c = 0; c < 8; ++c) w |= (uint32_t)scode[i * 8 + c] << (4 * c);
-            row[g * 16 + i] = w;
-        }
-    } else if (i < 12) {
-        const int u = i / 3, wd = i % 3;
-        const uint8_t *cu = scode + u * 32;
+    const int words = bits == 4 ? 16 : 12;                                    // packed words per row and group
+    for (int idx = i; idx < rows * words; idx += 128) {
+        const int row = idx / words, wi = idx % words;
+        uint32_t *out = qw + (size_t)(n0 + row) * row_words + g * words;
         uint32_t w = 0;
-        for (int f = 0; f < 5; ++f) {
-            w |= (uint32_t)cu[wd * 10 + f] << (3 * f);
-            w |= (uint32_t)cu[wd * 10 + 5 + f] << (16 + 3 * f);
+        if (bits == 4) {
+            for (int c = 0; c < 8; ++c) w |= (uint32_t)scode[row][wi * 8 + c] << (4 * c);
+        } else {
+            const int u = wi / 3, wd = wi % 3;
+            const uint8_t *cu = scode[row] + u * 32;
+            for (int f = 0; f < 5; ++f) {
+                w |= (uint32_t)cu[wd * 10 + f] << (3 * f);
+                w |= (uint32_t)cu[wd * 10 + 5 + f] << (16 + 3 * f);
+            }
+            w |= ((uint32_t)(cu[30] >> wd) & 1u) << 15;
+            w |= ((uint32_t)(cu[31] >> wd) & 1u) << 31;
         }
-        w |= ((uint32_t)(cu[30] >> wd) & 1u) << 15;
-        w |= ((uint32_t)(cu[31] >> wd) & 1u) << 31;
-        row[g * 12 + i] = w;
+        out[wi] = w;
     }
 }
 
 hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t *At, const uint16_t *Bt, uint32_t *qw,
-                           uint16_t *scales, uint16_t *zeros, hipStream_t stream)
+                           uint16_t *scales, uint16_t *zeros, hipStream_t stream, uint16_t *D16, uint16_t *Dt16, int ldt, float gain)
 {
-    hipLaunchKernelGGL(fbq_quantize_kernel, dim3(d.K / kGroup, d.N), dim3(128), 0, stream, W, At, Bt, qw, scales, zeros, d.N,
-                       d.K, d.r, d.bits, (int)row_words(d.K, d.bits));
+    hipLaunchKernelGGL(fbq_quantize_kernel, dim3(d.K / kGroup, ceil_div(d.N, kQuantRows)), dim3(128), 0, stream, W, At, Bt, qw, scales,
+                       zeros, d.N, d.K, d.r, d.bits, (int)row_words(d.K, d.bits), D16, Dt16, ldt, gain);
     return hipGetLastError();
 }
 

@@ -312,11 +312,12 @@ def train_state(d: Desc, At32, Bt32) -> TrainState:
                       torch.empty(max(256, train_workspace_bytes(d, 1)), dtype=torch.uint8, device=dev))
 
 
-def train_step(st: TrainState, W, H16, h_scale: float, lr: float, stream=None) -> None:
-    """fbq_train_step: one loop-body iteration of Alg. 1 on the state's masters."""
+def train_step(st: TrainState, W, H16, h_scale: float, lr: float, stream=None, want_loss: bool = True) -> None:
+    """fbq_train_step: one loop-body iteration of Alg. 1 on the state's masters (want_loss=False skips the
+    one contraction only the loss needs)."""
     d, l = st.desc, st.layer
     rc = load().fbq_train_step(ctypes.byref(d.c()), _dev_ptr(W), _dev_ptr(H16), float(h_scale), _dev_ptr(st.At32),
                                _dev_ptr(st.Bt32), float(lr), _dev_ptr(l.qweight), _dev_ptr(l.scales), _dev_ptr(l.zeros),
-                               _dev_ptr(l.At), _dev_ptr(l.Bt), _dev_ptr(st.grad_At), _dev_ptr(st.grad_Bt), _dev_ptr(st.loss),
+                               _dev_ptr(l.At), _dev_ptr(l.Bt), _dev_ptr(st.grad_At), _dev_ptr(st.grad_Bt), _dev_ptr(st.loss) if want_loss else None,
                                _dev_ptr(st.workspace), st.workspace.numel() * st.workspace.element_size(), _stream(stream))
     _check(rc, "fbq_train_step")

@@ -76,6 +76,45 @@ def time_layer(N, K, r, bits, M, iters=100, warmup=10, rotate_bytes=1.0e9):
             "TFLOPps": round(algorithmic_flops(N, K, r, M) / us / 1e6, 2), "copies": copies, "iters": iters}
 
 
+def time_train_step(N, K, r, bits, T, iters=20, warmup=3):
+    """Times fbq_gram and fbq_train_step (with and without the loss) on synthetic W ~ N(0, 0.02), X ~ N(0, 1).
+    Flops: gram 2 K^2 T; gradients 8 N K r + 4 r K^2 (products with r rows only); the loss 2 N K^2 more."""
+    d = fbq.Desc(N, K, r, bits)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1)
+    W = (torch.randn(N, K, device="cuda", generator=gen) * 0.02).half()
+    X = torch.randn(T, K, device="cuda", generator=gen).half()
+    At32 = torch.randn(r, K, device="cuda", generator=gen) * 0.01
+    Bt32 = torch.randn(N, r, device="cuda", generator=gen) * 0.01
+    st = fbq.train_state(d, At32, Bt32)
+    ws = torch.empty(fbq.train_workspace_bytes(d, T), dtype=torch.uint8, device="cuda")
+    hs = 1.0 / T
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e3
+
+    H16 = fbq.gram(d, X, hs, ws)
+    us_gram = timed(lambda: fbq.gram(d, X, hs, ws))
+    lr = 0.0        # the masters stay put: every timed iteration does the same work on the same values
+    us_loss = timed(lambda: fbq.train_step(st, W, H16, hs, lr))
+    us_grad = timed(lambda: fbq.train_step(st, W, H16, hs, lr, want_loss=False))
+    fl_grad = 8.0 * N * K * r + 4.0 * r * K * K
+    fl_loss = 2.0 * N * K * K
+    return {"N": N, "K": K, "r": r, "bits": bits, "T": T, "gram_us": round(us_gram, 1),
+            "gram_TFLOPps": round(2.0 * K * K * T / us_gram / 1e6, 1),
+            "step_us": round(us_grad, 1), "step_with_loss_us": round(us_loss, 1),
+            "loss_contraction_TFLOPps": round(fl_loss / max(us_loss - us_grad, 1e-3) / 1e6, 1),
+            "step_TFLOPps": round(fl_grad / us_grad / 1e6, 1), "loss": float(st.loss.cpu()[0])}
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--N", type=int, required=True)
@@ -85,7 +124,11 @@ def main():
     ap.add_argument("--M", type=int, default=1)
     ap.add_argument("--iters", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--train-tokens", type=int, default=0, help="time the reconstruction step on this many calibration tokens instead")
     a = ap.parse_args()
+    if a.train_tokens:
+        print(json.dumps(time_train_step(a.N, a.K, a.r, a.bits, a.train_tokens, a.iters, a.warmup)), flush=True)
+        return
     print(json.dumps(time_layer(a.N, a.K, a.r, a.bits, a.M, a.iters, a.warmup)), flush=True)
 
 

@@ -126,3 +126,18 @@ def test_zero_learning_rate_leaves_the_masters_and_writes_a_usable_layer():
     codes, s, z = orc.quantize(W, A.astype(np.float16), B.astype(np.float16), 4, 128)
     want = orc.linear(x, orc.pack(codes, 4), s, z, A.astype(np.float16), B.astype(np.float16), 4, 128)
     assert rel_l2(y.cpu().numpy().astype(np.float64), want) < 1e-3
+
+
+def test_step_without_loss_gives_the_same_gradients():
+    spec, W, X, A, B = _problem(256, 512, 16, 4, 64, 4, False)
+    d = fbq.Desc(256, 512, 16, 4)
+    mk = lambda: (torch.from_numpy(np.ascontiguousarray(A.T).astype(np.float32)).cuda(),
+                  torch.from_numpy(np.ascontiguousarray(B.T).astype(np.float32)).cuda())
+    st1, st2 = fbq.train_state(d, *mk()), fbq.train_state(d, *mk())
+    Wd = _dev16(W).view(torch.float16)
+    H16 = fbq.gram(d, _dev16(X).view(torch.float16), 1.0 / 64)
+    fbq.train_step(st1, Wd, H16, 1.0 / 64, 1e-3)
+    fbq.train_step(st2, Wd, H16, 1.0 / 64, 1e-3, want_loss=False)
+    torch.cuda.synchronize()
+    assert torch.equal(st1.grad_At, st2.grad_At) and torch.equal(st1.grad_Bt, st2.grad_Bt)
+    assert torch.equal(st1.At32, st2.At32) and torch.equal(st1.Bt32, st2.Bt32)
