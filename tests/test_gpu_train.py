@@ -141,3 +141,34 @@ def test_step_without_loss_gives_the_same_gradients():
     torch.cuda.synchronize()
     assert torch.equal(st1.grad_At, st2.grad_At) and torch.equal(st1.grad_Bt, st2.grad_Bt)
     assert torch.equal(st1.At32, st2.At32) and torch.equal(st1.Bt32, st2.Bt32)
+
+
+def test_reconstruction_loop_lowers_the_loss_and_keeps_the_bound():
+    """Alg. 1 end to end on a small layer: B starts at zero, the loss of every iterate is evaluated, the
+    last layer is checked against the oracle's loss for the same parameters and against the s/2 bound."""
+    from paper_2501_16385_amd.reconstruction import reconstruct_layer
+    N, K, r, T, bits = 256, 512, 16, 256, 4
+    spec = fbq_synth.LayerSpec("loop", N, K, r, bits)
+    W = fbq_synth.make_weight(spec, 34, 0)
+    X = fbq_synth.make_x(spec, T, 34, 0)
+    d = fbq.Desc(N, K, r, bits)
+    lam = float(np.linalg.eigvalsh(orc.gram(X))[-1])
+    a_std = 0.01
+    # plain gradient descent on a product of two factors: the step that is stable at the start stops being so once B has
+    # grown, so stay well below 1 / (lambda_max |A|^2)
+    lr = 0.05 / (lam * (a_std * (np.sqrt(K) + np.sqrt(r))) ** 2)
+    layer, losses = reconstruct_layer(d, _dev16(W).view(torch.float16), _dev16(X).view(torch.float16), 40, lr, a_std=a_std)
+    torch.cuda.synchronize()
+    vals = [l for _, l in losses]
+    assert vals[-1] < 0.85 * vals[0], f"loss {vals[0]:.4g} -> {vals[-1]:.4g}"
+    assert all(np.isfinite(vals))
+    # the oracle's loss for the final parameters (lr = 0 leaves them alone)
+    A16 = layer.At.cpu().numpy().view(np.float16).T
+    B16 = layer.Bt.cpu().numpy().view(np.float16).T
+    want = orc.train_step(W, X, np.ascontiguousarray(A16.astype(np.float64)), np.ascontiguousarray(B16.astype(np.float64)), 0.0,
+                          bits, spec.group)
+    assert vals[-1] == pytest.approx(want["loss"], rel=1e-3)
+    # Sec. 4.1: the reconstructed weight of the trained layer stays within s/2 of W
+    WF = fbq.reconstruct(layer).cpu().numpy().astype(np.float64)
+    s = np.repeat(layer.scales.cpu().numpy().view(np.float16).astype(np.float64), 128, axis=1)
+    assert np.all(np.abs(W.astype(np.float64) - WF) <= 0.5 * s * (1 + 1e-4) + 1e-7)
