@@ -41,7 +41,7 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kTile = 128;           // block tile, both ways
+constexpr int kTile = 128;           // the default block tile, both ways (64 WM x 64 WN in general)
 constexpr int kStepK = 64;           // k per step: one 128-byte row segment per operand row
 constexpr float kDeltaGain = 256.0f; // Delta_F is stored as fp16(256 Delta_F)
 constexpr int kXcds = 8;
@@ -76,75 +76,76 @@ __device__ __forceinline__ void store_result(const GemmArgs &g, int m, int n, fl
     if (g.C16 && m >= g.c16_row0) g.C16[(size_t)(m - g.c16_row0) * g.ldc16 + n] = __builtin_bit_cast(uint16_t, (half_t)(g.beta * a));
 }
 
-__global__ __launch_bounds__(256, 2) void fbq_gemm_nt_kernel(GemmArgs g)
+// WM x WN: 32x32 tiles a wave owns (rows x columns); the block's 2 x 2 waves cover 64 WM x 64 WN.
+template <int WM, int WN>
+__global__ __launch_bounds__(256, (WM * WN > 4 ? 1 : 2)) void fbq_gemm_nt_kernel(GemmArgs g)
 {
-    __shared__ __align__(16) unsigned char lds[2 * 2 * kTile * kStepK * 2];   // [buffer][operand][row][128 bytes]
-    constexpr int kOperandBytes = kTile * kStepK * 2;
+    extern __shared__ __align__(16) unsigned char lds[];   // [buffer][A rows | B rows][128 bytes]
+    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr int kABytes = BM * kStepK * 2, kBufferBytes = (BM + BN) * kStepK * 2;
+    constexpr int LA = BM * 8 / 256, LB = BN * 8 / 256;     // 16-byte loads per thread and step
 
     // Consecutive tiles (same rows of A, neighbouring rows of B) run on the same XCD and share its L2.
-    const int tiles_n = (g.Nr + kTile - 1) / kTile, tiles_m = (g.Mr + kTile - 1) / kTile;
+    const int tiles_n = (g.Nr + BN - 1) / BN, tiles_m = (g.Mr + BM - 1) / BM;
     const int total = tiles_m * tiles_n * g.splits, per_xcd = (total + kXcds - 1) / kXcds;
     const int unit = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
     if (unit >= total) return;
     const int tile = unit / g.splits, split = unit % g.splits;
-    const int m0 = (tile / tiles_n) * kTile, n0 = (tile % tiles_n) * kTile;
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int col = lane & 31, h = lane >> 5;
 
-    const __amdgpu_buffer_rsrc_t abuf = rows_buffer(g.A + (size_t)m0 * g.lda, (long)min(kTile, g.Mr - m0) * g.lda * 2);
-    const __amdgpu_buffer_rsrc_t bbuf = rows_buffer(g.B + (size_t)n0 * g.ldb, (long)min(kTile, g.Nr - n0) * g.ldb * 2);
+    const __amdgpu_buffer_rsrc_t abuf = rows_buffer(g.A + (size_t)m0 * g.lda, (long)min(BM, g.Mr - m0) * g.lda * 2);
+    const __amdgpu_buffer_rsrc_t bbuf = rows_buffer(g.B + (size_t)n0 * g.ldb, (long)min(BN, g.Nr - n0) * g.ldb * 2);
 
-    int goff_a[4], goff_b[4], loff[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int c = tid + 256 * i, row = c >> 3, ch = c & 7;
-        goff_a[i] = row * g.lda * 2 + ch * 16;
-        goff_b[i] = row * g.ldb * 2 + ch * 16;
-        loff[i] = row * 128 + ((ch ^ swizzle_key(row)) * 16);
-    }
-    uint4_t ra[4], rb[4];
+    // thread t fetches chunk t % 8 of rows t / 8, t / 8 + 32, ...: every wave-wide load covers whole 128-byte row segments
+    const int lrow = tid >> 3, lch = tid & 7;
+    const int goff_a = lrow * g.lda * 2 + lch * 16, goff_b = lrow * g.ldb * 2 + lch * 16;
+    const int gstep_a = 32 * g.lda * 2, gstep_b = 32 * g.ldb * 2;
+    const int loff = lrow * 128 + ((lch ^ swizzle_key(lrow)) * 16);     // rows 32 apart share the key
+    uint4_t ra[LA], rb[LB];
     auto fetch = [&](int s) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) ra[i] = __builtin_bit_cast(uint4_t, __builtin_amdgcn_raw_buffer_load_b128(abuf, goff_a[i] + s * 128, 0, 0));
+        for (int i = 0; i < LA; ++i) ra[i] = __builtin_bit_cast(uint4_t, __builtin_amdgcn_raw_buffer_load_b128(abuf, goff_a + i * gstep_a + s * 128, 0, 0));
 #pragma unroll
-        for (int i = 0; i < 4; ++i) rb[i] = __builtin_bit_cast(uint4_t, __builtin_amdgcn_raw_buffer_load_b128(bbuf, goff_b[i] + s * 128, 0, 0));
+        for (int i = 0; i < LB; ++i) rb[i] = __builtin_bit_cast(uint4_t, __builtin_amdgcn_raw_buffer_load_b128(bbuf, goff_b + i * gstep_b + s * 128, 0, 0));
     };
     auto stash = [&](int buf) {
-        unsigned char *la = lds + (buf * 2 + 0) * kOperandBytes, *lb = lds + (buf * 2 + 1) * kOperandBytes;
+        unsigned char *la = lds + buf * kBufferBytes, *lb = la + kABytes;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4_t *>(la + loff[i]) = ra[i];
+        for (int i = 0; i < LA; ++i) *reinterpret_cast<uint4_t *>(la + loff + i * 32 * 128) = ra[i];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4_t *>(lb + loff[i]) = rb[i];
+        for (int i = 0; i < LB; ++i) *reinterpret_cast<uint4_t *>(lb + loff + i * 32 * 128) = rb[i];
     };
 
-    float16_t acc[2][2];
+    float16_t acc[WM][WN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < WN; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     // operand rows of this lane: 32 rows apart, so they share the swizzle key
     const int key = swizzle_key(col);
-    const int arow = (wm * 64 + col) * 128, brow = (wn * 64 + col) * 128;
+    const int arow = (wm * 32 * WM + col) * 128, brow = (wn * 32 * WN + col) * 128;
     auto multiply = [&](int buf) {
-        const unsigned char *la = lds + (buf * 2 + 0) * kOperandBytes, *lb = lds + (buf * 2 + 1) * kOperandBytes;
+        const unsigned char *la = lds + buf * kBufferBytes, *lb = la + kABytes;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             const int chunk = ((kk * 2 + h) ^ key) * 16;
-            half8_t af[2], bf[2];
+            half8_t af[WM], bf[WN];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) af[i] = *reinterpret_cast<const half8_t *>(la + arow + i * 32 * 128 + chunk);
+            for (int i = 0; i < WM; ++i) af[i] = *reinterpret_cast<const half8_t *>(la + arow + i * 32 * 128 + chunk);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) bf[j] = *reinterpret_cast<const half8_t *>(lb + brow + j * 32 * 128 + chunk);
+            for (int j = 0; j < WN; ++j) bf[j] = *reinterpret_cast<const half8_t *>(lb + brow + j * 32 * 128 + chunk);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < WM; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < WN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
         }
     };
 
@@ -164,13 +165,13 @@ __global__ __launch_bounds__(256, 2) void fbq_gemm_nt_kernel(GemmArgs g)
     {
         float dot = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < WM; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int n = n0 + wn * 64 + j * 32 + col;
+            for (int j = 0; j < WN; ++j) {
+                const int n = n0 + (wn * WN + j) * 32 + col;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + wm * 64 + i * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+                    const int m = m0 + (wm * WM + i) * 32 + 8 * (v / 4) + 4 * h + (v % 4);
                     if (m >= g.Mr || n >= g.Nr) continue;
                     const float a = acc[i][j][v];
                     if (g.splits > 1) {
@@ -203,11 +204,28 @@ __global__ __launch_bounds__(256) void fbq_sum_splits_kernel(GemmArgs g)
     store_result(g, (int)(i / g.Nr), (int)(i % g.Nr), a);
 }
 
+// Tile shapes: 128 x 128 in general, 64 rows or 64 columns where an operand has no more than that (the
+// r-row products at r <= 64).  Larger tiles (256 x 128 at one block per CU: 4096^3 at 547 instead of
+// 650 TFLOP/s; 256 x 256: spills) were measured and dropped: with a single block per CU nothing runs
+// while its waves wait at the barrier.
+struct TileShape { int wm, wn; };
+static TileShape tile_for(int Mr, int Nr)
+{
+    if (Mr <= 64) return {1, 2};
+    if (Nr <= 64) return {2, 1};
+    return {2, 2};
+}
+static int tiles_of(int Mr, int Nr)
+{
+    const TileShape t = tile_for(Mr, Nr);
+    return ceil_div(Mr, 64 * t.wm) * ceil_div(Nr, 64 * t.wn);
+}
+
 // Blocks that split K for one tile: enough to give every CU a block when the tiles alone do not,
 // at least 4 steps each, and none left without a step.
 static int splits_for(int Mr, int Nr, int Kd)
 {
-    const int tiles = ceil_div(Mr, kTile) * ceil_div(Nr, kTile), steps = Kd / kStepK;
+    const int tiles = tiles_of(Mr, Nr), steps = Kd / kStepK;
     const int want = std::min(256 / std::max(tiles, 1), steps / 4);
     if (want < 2) return 1;
     return ceil_div(steps, ceil_div(steps, want));
@@ -219,13 +237,24 @@ static size_t split_scratch_bytes(int Mr, int Nr, int Kd)
     return sp > 1 ? (size_t)sp * Mr * Nr * 4 : 0;
 }
 
+template <int WM, int WN>
+static void launch_gemm_tile(const GemmArgs &g, dim3 grid, hipStream_t stream)
+{
+    constexpr int bytes = 2 * (64 * WM + 64 * WN) * kStepK * 2;
+    static_assert(bytes <= 65536, "more LDS than a launch may ask for without raising the function's limit");
+    hipLaunchKernelGGL((fbq_gemm_nt_kernel<WM, WN>), grid, dim3(256), bytes, stream, g);
+}
+
 static hipError_t launch_gemm(GemmArgs g, float *split_scratch, hipStream_t stream)
 {
     g.splits = (!g.dot && split_scratch) ? splits_for(g.Mr, g.Nr, g.Kd) : 1;
     g.part = split_scratch;
-    const int units = ceil_div(g.Mr, kTile) * ceil_div(g.Nr, kTile) * g.splits;
+    const TileShape t = tile_for(g.Mr, g.Nr);
+    const int units = tiles_of(g.Mr, g.Nr) * g.splits;
     const dim3 grid(ceil_div(units, kXcds) * kXcds);
-    hipLaunchKernelGGL(fbq_gemm_nt_kernel, grid, dim3(256), 0, stream, g);
+    if (t.wm == 1) launch_gemm_tile<1, 2>(g, grid, stream);
+    else if (t.wn == 1) launch_gemm_tile<2, 1>(g, grid, stream);
+    else launch_gemm_tile<2, 2>(g, grid, stream);
     if (g.splits > 1)
         hipLaunchKernelGGL(fbq_sum_splits_kernel, dim3((unsigned)(((size_t)g.Mr * g.Nr + 255) / 256)), dim3(256), 0, stream, g);
     return hipGetLastError();
@@ -322,7 +351,7 @@ static TrainLayout train_layout(int N, int K, int r)
     l.Dt16 = o; o += pad256((size_t)K * Np * 2);
     l.S16 = o;  o += pad256((size_t)2 * r * K * 2);          // stacked operand [Q; At]
     l.Vt16 = o; o += pad256((size_t)r * K * 2);
-    l.dot = o;  o += pad256((size_t)ceil_div(N, kTile) * ceil_div(K, kTile) * 4);
+    l.dot = o;  o += pad256((size_t)ceil_div(N, 64) * ceil_div(K, 64) * 4);           // enough for any tile shape
     l.split = o;
     o += pad256(std::max(std::max(split_scratch_bytes(r, K, Np), split_scratch_bytes(2 * r, K, K)), split_scratch_bytes(N, r, K)));
     l.total = o;
@@ -355,7 +384,7 @@ hipError_t launch_train_step(const TrainArgs &a, hipStream_t stream)
     uint16_t *D16 = (uint16_t *)(ws + l.D16), *Dt16 = (uint16_t *)(ws + l.Dt16);
     uint16_t *S16 = (uint16_t *)(ws + l.S16), *Vt16 = (uint16_t *)(ws + l.Vt16);
     float *dot = (float *)(ws + l.dot), *scratch = (float *)(ws + l.split);
-    const int tiles = ceil_div(N, kTile) * ceil_div(K, kTile);
+    const int tiles = tiles_of(N, K);
 
     // fp16 views of the masters: what the forward pass of Alg. 1 computes with
     const size_t casts = (size_t)r * K + (size_t)N * r + (size_t)r * Np;
