@@ -3,8 +3,11 @@
 //
 //   y[M,N] = x[M,K] . Wq[N,K]^T + t[M,r] . B[r,N],   t = x . A
 //
-// Two launches, as in the paper: a small preparation launch (down-projection, and the activations
-// rewritten into operand order), then the fused kernel.
+// One launch.  The first blocks of a grid row do the layer's down-projection and hand t over inside
+// the launch (every partial sum travels as one 8-byte word {value, launch tag}, written and read at
+// device scope: no flag, no fence, nothing to reset); all others stream weights from the start and
+// ask for t only when their main part is done.  (The paper has a second launch there; on this GPU
+// a launch boundary costs 4-5 us, a third of this kernel.)
 //
 // v_mfma_f32_16x16x32_f16 multiplies a 16 (token) x 32 (k) activation fragment with a 32 (k) x 16
 // (output row) weight fragment.  Lane (c = lane % 16, q = lane / 16) supplies 8 values of k for
@@ -20,12 +23,13 @@
 // instruction as they are: one v_and_or_b32 per two codes is all the de-quantization the inner
 // loop does.
 //
-// Activations.  The preparation launch writes, for every group g, matrix instruction t and lane,
-// the 8 activations that meet those 8 weights - already divided by 16 (8, 64) where the weight
-// field is scaled - as one 16-byte operand; 64 lanes read one contiguous kilobyte.  A wave keeps
-// the operands of its four groups in registers and walks over the block's row tiles with them, so
-// a block reads the activations once, whatever the number of rows it owns.  The same launch
-// stores, per group and token, X = sum x and XS = 1024 sum x' (x' the scaled activations).
+// Activations.  For every group, lane (c, q) reads the 32 activations k = 32 q .. 32 q + 31 of token c
+// (four 16-byte loads, while the weights are under way) and re-orders them in registers into the four
+// operands that meet its weight operands - divided by 16 (8, 64) where the weight field is scaled.
+// A wave keeps the operands of its four groups in registers and walks over the block's row tiles
+// with them, so a block reads the activations once, whatever the number of rows it owns.  Per group
+// and token, X = sum x and XS = 1024 sum x' (x' the scaled activations) come from the matrix core as
+// well: the operands against a column of ones, and against the column of field gains.
 //
 // One group of one row tile then is  D' = sum x' (1024 + m q) = XS + sum x q  (four matrix
 // instructions, fp32, every product exact), and the lane that holds output row n adds
@@ -34,7 +38,7 @@
 // A block's eight waves split K.  The up-projection enters the same accumulators as r more values of
 // k (t split into two fp16 halves: t_hi + t_lo carries 22 bits of the fp32 sum), in units of
 // (tile, 32 taps) dealt out to the waves; then the waves' partial tiles meet in LDS and y is stored
-// once.  Layers that read the same activations (q/k/v, gate/up) share both launches.
+// once.  Layers that read the same activations (q/k/v, gate/up) share the launch.
 #include <hip/hip_fp16.h>
 
 #include "fbq_internal.h"
@@ -78,22 +82,21 @@ struct SmallParams {
     const uint16_t *Bt;    // [N][r]
     const uint16_t *x;     // [M][K]
     uint16_t *y;           // [M][N]
-    float *tpart;          // workspace: [slices][16][r] partial sums of t = x.A, one per K slice of the down-projection
-    float *xsum;           // workspace: [G][2][16]: X = sum x and XS = 1024 sum x' per group and token
-    uint4 *xop;            // workspace: [G][4][64] 16-byte activation operands
+    uint64_t *tpart;       // workspace: [slices][16][r] words {fp32 partial sum of t = x.A over one K slice, launch tag}
+    uint64_t *tsum;        // workspace: [16][r] words {t, launch tag}: the slices added up
     int M, N, K, r;
     int row_words, G;
     int slices, kslice;    // down-projection: number of K slices and their length (a multiple of 512)
-    int down_blocks;       // blocks of the preparation launch that do the down-projection; the rest arrange x
-    int tiles_per_block;   // 16-row tiles a block of the fused kernel owns
+    int down_blocks;       // blocks at the start of this layer's grid row that do its down-projection, slice by slice ...
+    int sum_blocks;        // ... and the blocks after them that add the slices up (16 columns each)
+    int tiles_per_block;   // 16-row tiles a consumer block owns
 };
 
-// Layers that share their activations (q/k/v, gate/up) share the two launches: the activations are
-// arranged once.  In both grids y is the layer (in the preparation launch row 0 arranges the
-// activations and the layers follow) and x the block of that layer; the layer's parameters are found
-// from the block index alone, so they are fetched in one go with the rest of the kernel arguments
-// (a second, dependent round trip to them costs more than half a microsecond).  Surplus blocks of
-// rows with fewer blocks than the widest leave at once.
+// Layers that share their activations (q/k/v, gate/up) share the launch.  In the grid y is the layer
+// and x the block of that layer; the layer's parameters are found from the block index alone, so
+// they are fetched in one go with the rest of the kernel arguments (a second, dependent round trip
+// to them costs more than half a microsecond).  Surplus blocks of rows with fewer blocks than the
+// widest leave at once.
 struct SmallGroup {
     int n_layers;
     SmallParams layer[kMaxSmallGroup];
@@ -171,15 +174,19 @@ __device__ __forceinline__ half_t half_at(uint3_t w, int i)
     return __builtin_bit_cast(half_t, (uint16_t)((i & 1) ? lo >> 16 : lo));
 }
 
-// ------------------------------------------------------------------ preparation launch
+// ------------------------------------------------------------------ down-projection, inside the launch
 
-constexpr int kPrepWaves = 16;
+constexpr int kSpinLimit = 1 << 15;   // polls (~0.3 us each) before a wave gives up and computes its share of t itself
+constexpr int kCacheSc1 = 16 | (1 << 31);   // buffer-load policy: device scope (sc1), and volatile so that a poll is never hoisted or merged
 
-// Down-projection for up to 16 tokens: block b = (K slice, column tile of 16); the block's sixteen
-// waves take a sixteenth of the slice each.  partial[slice][token][j] = sum over the slice of
-// x[token][k] At[j][k]; token rows past M repeat the last token.  The slices only exist to put more
-// compute units to work on this short, latency-bound step; the fused kernel adds them up.
-__device__ void down_proj_block(const SmallParams &p, int b, float4_t (*red)[64])
+constexpr int kPrepWaves = 8;      // = kMainWaves: preparing blocks and consumers are blocks of the same launch
+
+// Down-projection for up to 16 tokens: block b = (K slice, column tile of 16); the block's eight
+// waves take an eighth of the slice each.  partial[slice][token][j] = sum over the slice of
+// x[token][k] At[j][k], stored with the launch tag in the other half of its 8-byte word; token rows
+// past M repeat the last token.  The slices only exist to put more compute units to work on this
+// short, latency-bound step; the consumers add them up.
+__device__ void down_proj_block(const SmallParams &p, int b, uint32_t tag, float4_t (*red)[64])
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 15, q = lane >> 4;
@@ -203,80 +210,104 @@ __device__ void down_proj_block(const SmallParams &p, int b, float4_t (*red)[64]
         const int j = j0 + c;                           // lane (c, q) holds column j and tokens 4 q + v
         if (j < p.r) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) p.tpart[((size_t)slice * kTokens + 4 * q + v) * p.r + j] = sum[v];
+            for (int v = 0; v < 4; ++v) {
+                const float partial = sum[v];        // a scalar first: bit_cast of a vector component reads the wrong element
+                const uint64_t word = (uint64_t)__builtin_bit_cast(uint32_t, partial) | ((uint64_t)tag << 32);
+                __hip_atomic_store(p.tpart + ((size_t)slice * kTokens + 4 * q + v) * p.r + j, word, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
 }
 
-// Activation operands: wave w of arrange block b handles group g = 16 b + w; lane (c, q) turns the 32
-// activations k = 128 g + 32 q .. + 31 of token c (zeros for tokens past M) into the four operands
-// that meet the lane-(., q) weight operands, and the four lanes of a token add up X and XS.
-template <int BITS>
-__device__ void arrange_block(const SmallParams &p, int b)
+// Second step of the down-projection: block b adds up the K slices of columns 16 b .. 16 b + 15 for all
+// 16 token rows (one thread per sum) as soon as their words carry this launch's tag, and passes t on
+// in the same form.  Consumers then read one word per value, whatever the number of slices.
+__device__ void sum_slices_block(const SmallParams &p, int b, uint32_t tag)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c = lane & 15, q = lane >> 4;
-    const int g = b * kPrepWaves + wave;
-    if (g >= p.G) return;                               // wave-uniform
-    half_t v[32];
-    if (c < p.M) {
-        const uint4 *src = reinterpret_cast<const uint4 *>(p.x + (size_t)c * p.K + (size_t)g * kGroup + 32 * q);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint4 raw = src[i];
-            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const half2_t h = h2_of(w[j]);
-                v[i * 8 + j * 2] = h.x;
-                v[i * 8 + j * 2 + 1] = h.y;
-            }
+    const int tid = threadIdx.x;
+    if (tid >= 256) return;                             // whole waves
+    const int token = tid >> 4, j = 16 * b + (tid & 15);
+    const bool mine = j < p.r;
+    const __amdgpu_buffer_rsrc_t pb = buffer_of(p.tpart, (long)p.slices * kTokens * p.r * 8);
+    float t = 0.0f;
+    bool ready = false;
+    for (int spin = 0; spin < kSpinLimit && !ready; ++spin) {
+        bool ok = true;
+        t = 0.0f;
+        for (int sl = 0; sl < p.slices; ++sl) {
+            const uint2_t w = __builtin_amdgcn_raw_buffer_load_b64(pb, mine ? ((sl * kTokens + token) * p.r + j) * 8 : 0x7FFFFFF0, 0, kCacheSc1);
+            const uint32_t v = w.x;
+            t += __builtin_bit_cast(float, v);
+            ok = ok && (!mine || w.y == tag);
         }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 32; ++i) v[i] = (half_t)0.0f;
+        ready = __all(ok);
+        if (!ready) __builtin_amdgcn_s_sleep(4);
     }
-    int first[16], second[16];                          // the two codes of pair p
-#pragma unroll
-    for (int pi = 0; pi < 16; ++pi) {
-        if (BITS == 4) { first[pi] = 8 * (pi / 4) + pi % 4; second[pi] = first[pi] + 4; }
-        else if (pi == 15) { first[pi] = 30; second[pi] = 31; }
-        else { first[pi] = 10 * (pi / 5) + pi % 5; second[pi] = first[pi] + 5; }
+    if (!mine) return;
+    if (!ready) {                                       // the slices never showed up: the whole sum, here
+        const uint16_t *xr = p.x + (size_t)min(token, p.M - 1) * p.K, *ar = p.At + (size_t)j * p.K;
+        t = 0.0f;
+        for (int k = 0; k < p.K; ++k) t = fmaf((float)__builtin_bit_cast(half_t, xr[k]), (float)__builtin_bit_cast(half_t, ar[k]), t);
     }
-    float X = 0.0f, XS = 0.0f;
+    const uint64_t word = (uint64_t)__builtin_bit_cast(uint32_t, t) | ((uint64_t)tag << 32);
+    __hip_atomic_store(p.tsum + (size_t)token * p.r + j, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Activation operands of one group: the lane's 32 activations (four 16-byte pieces, k ascending) become
+// the four operands that meet its weight operands, pair by pair in extraction order, each divided by
+// the gain of the weight field it meets (exact unless the quotient is subnormal).  One byte
+// permutation picks the two activations of a pair out of the 16 dwords, one packed multiply scales
+// the pairs whose field has a gain.
+template <int BITS>
+__device__ __forceinline__ void arrange_operands(const uint4_t (&raw)[4], half8_t (&ops)[4])
+{
+    uint32_t d[16];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { d[4 * i] = raw[i].x; d[4 * i + 1] = raw[i].y; d[4 * i + 2] = raw[i].z; d[4 * i + 3] = raw[i].w; }
     half2_t pr[16];
 #pragma unroll
     for (int pi = 0; pi < 16; ++pi) {
-        const half_t inv = (half_t)(1.0f / field_gain<BITS>(pi));
-        const half_t a = v[first[pi]] * inv, d = v[second[pi]] * inv;   // exact unless the quotient is subnormal
-        pr[pi] = half2_t{a, d};
-        X += (float)v[first[pi]] + (float)v[second[pi]];
-        XS += (float)a + (float)d;
+        int first, second;                              // the two codes of pair pi
+        if (BITS == 4) { first = 8 * (pi / 4) + pi % 4; second = first + 4; }
+        else if (pi == 15) { first = 30; second = 31; }
+        else { first = 10 * (pi / 5) + pi % 5; second = first + 5; }
+        // result bytes 0,1 <- half `first` (bytes 0..3 of the selector's view are its dword), bytes 2,3 <- half `second`
+        const uint32_t sel = (uint32_t)(2 * (first & 1)) | ((uint32_t)(2 * (first & 1) + 1) << 8) |
+                             ((uint32_t)(4 + 2 * (second & 1)) << 16) | ((uint32_t)(4 + 2 * (second & 1) + 1) << 24);
+        const half2_t both = h2_of(__builtin_amdgcn_perm(d[second / 2], d[first / 2], sel));
+        const float gain = field_gain<BITS>(pi);
+        const half_t inv = (half_t)(1.0f / gain);
+        pr[pi] = gain == 1.0f ? both : both * half2_t{inv, inv};
     }
-    uint4 *dst = p.xop + ((size_t)g * 4) * 64 + lane;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) dst[t * 64] = __builtin_bit_cast(uint4, pack8(pr[4 * t], pr[4 * t + 1], pr[4 * t + 2], pr[4 * t + 3]));
-    X += __shfl_xor(X, 16); X += __shfl_xor(X, 32);
-    XS += __shfl_xor(XS, 16); XS += __shfl_xor(XS, 32);
-    if (q == 0) {
-        p.xsum[((size_t)g * 2 + 0) * kTokens + c] = X;
-        p.xsum[((size_t)g * 2 + 1) * kTokens + c] = 1024.0f * XS;
-    }
+    for (int t = 0; t < 4; ++t) ops[t] = pack8(pr[4 * t], pr[4 * t + 1], pr[4 * t + 2], pr[4 * t + 3]);
 }
 
+// The gains of the eight weight fields that operand t holds: against this column the scaled
+// activations sum to X = sum x.
 template <int BITS>
-__global__ __launch_bounds__(64 * kPrepWaves) void fbq_small_m_prepare_kernel(const SmallGroup g)
+__device__ __forceinline__ half8_t gain_operand(int t)
 {
-    __shared__ float4_t red[kPrepWaves][64];
-    const int b = blockIdx.x, row = blockIdx.y;         // row 0 arranges the activations, row i + 1 is layer i's down-projection
-    const SmallParams p = g.layer[row == 0 ? 0 : row - 1];
-    // (all parameters before the first branch: left alone, the compiler fetches only what the branch needs first)
-    asm volatile("" :: "s"(p.x), "s"(p.At), "s"(p.tpart), "s"(p.xop), "s"(p.xsum), "s"(p.M), "s"(p.K), "s"(p.r), "s"(p.G), "s"(p.kslice));
-    if (row == 0) {                                     // every layer of the group reads layer 0's copy of the activations
-        if (b < (p.G + kPrepWaves - 1) / kPrepWaves) arrange_block<BITS>(p, b);
-        return;
-    }
-    if (b < p.down_blocks) down_proj_block(p, b, red);
+    half8_t g;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) g[e] = (half_t)field_gain<BITS>(4 * t + e / 2);
+    return g;
+}
+
+// ------------------------------------------------------------------ hand-over inside the launch
+
+
+extern "C" __device__ unsigned long long fbq_small_m_dispatch_id(void) __asm("llvm.amdgcn.dispatch.id");
+
+// Identity of this launch, the same in every block and different for every launch (also for every
+// replay of a captured graph): never zero, so a zero-filled workspace never matches.
+__device__ __forceinline__ uint32_t small_m_launch_tag()
+{
+    const uint64_t id = fbq_small_m_dispatch_id();
+    const uint64_t q = (uint64_t)__builtin_amdgcn_queue_ptr();
+    const uint32_t tag = (uint32_t)id + (uint32_t)(q >> 6) * 0x9E3779B1u;
+    return tag ? tag : 0x80000000u;
 }
 
 // ------------------------------------------------------------------ fused kernel
@@ -287,12 +318,25 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
 {
     constexpr int kPiece = BITS == 4 ? 16 : 12;         // bytes of 32 codes
     __shared__ float4_t red[kMainWaves][T][64];
+    // one group of activations per wave on its way from row order (as loaded, coalesced) to lane order:
+    // [token][16 pieces of 16 bytes + 1 of padding], the padding keeps both directions free of bank conflicts
+    __shared__ uint4_t xslab[kMainWaves][kTokens * 17];
+    float4_t (*red_prep)[64] = reinterpret_cast<float4_t (*)[64]>(&red[0][0][0]);   // [8][64], what a down-projection block needs
 
     const SmallParams p = g.layer[blockIdx.y];
     // (all of them before the first branch: left alone, the compiler fetches only what the branch needs first)
-    asm volatile("" :: "s"(p.qw), "s"(p.scales), "s"(p.zeros), "s"(p.xop), "s"(p.xsum), "s"(p.y), "s"(p.M), "s"(p.K), "s"(p.row_words), "s"(p.G));
-    if (BRANCH) asm volatile("" :: "s"(p.Bt), "s"(p.tpart), "s"(p.r), "s"(p.slices));
-    const int block = blockIdx.x;
+    asm volatile("" :: "s"(p.qw), "s"(p.scales), "s"(p.zeros), "s"(p.x), "s"(p.y), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.row_words), "s"(p.G), "s"(p.tiles_per_block));
+    if (BRANCH) asm volatile("" :: "s"(p.Bt), "s"(p.At), "s"(p.tpart), "s"(p.tsum), "s"(p.r), "s"(p.slices), "s"(p.kslice), "s"(p.down_blocks), "s"(p.sum_blocks));
+    const uint32_t tag = BRANCH ? small_m_launch_tag() : 0u;
+
+    // The first blocks of a grid row do the layer's down-projection.  They come first in dispatch
+    // order, so whoever waits for their words waits for blocks that are already running.
+    if (BRANCH && (int)blockIdx.x < p.down_blocks + p.sum_blocks) {
+        if ((int)blockIdx.x < p.down_blocks) down_proj_block(p, blockIdx.x, tag, red_prep);
+        else sum_slices_block(p, blockIdx.x - p.down_blocks, tag);
+        return;
+    }
+    const int block = blockIdx.x - (BRANCH ? p.down_blocks + p.sum_blocks : 0);
     if (block * p.tiles_per_block >= (p.N + 15) / 16) return;   // a narrower layer of the group
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -306,8 +350,10 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
     // half shares an aligned dword with two bytes past the array (same cache line, never another page).
     const __amdgpu_buffer_rsrc_t sbuf = buffer_of(p.scales, ((long)p.N * p.G * 2 + 3) & ~3L);
     const __amdgpu_buffer_rsrc_t zbuf = buffer_of(p.zeros, ((long)p.N * p.G * 2 + 3) & ~3L);
-    const __amdgpu_buffer_rsrc_t xbuf = buffer_of(p.xop, (long)p.G * 4 * 64 * 16);
-    const __amdgpu_buffer_rsrc_t ubuf = buffer_of(p.xsum, (long)p.G * 2 * kTokens * 4);
+    const __amdgpu_buffer_rsrc_t xbuf = buffer_of(p.x, (long)p.M * p.K * 2);
+    // activations are fetched a group at a time in four loads of four token rows each: 16 lanes per row,
+    // 256 contiguous bytes (the lane's own 64 bytes of its token would make every load a 64-segment gather)
+    const int xtok = lane >> 4, xpiece = lane & 15;
 
     // rows past N re-read the last row: computed, never stored
     int qrow[T], srow[T], odd[T];
@@ -325,7 +371,7 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
     // here with everything else; t (a few KB that every block reads) is fetched when it is needed.
     const int tap_steps = BRANCH ? (p.r + 31) / 32 : 0;
     const int units = T * tap_steps;
-    const __amdgpu_buffer_rsrc_t tbuf = buffer_of(p.tpart, BRANCH ? (long)p.slices * kTokens * p.r * 4 : 0);
+    const __amdgpu_buffer_rsrc_t tbuf = buffer_of(p.tsum, BRANCH ? (long)kTokens * p.r * 8 : 0);
     const __amdgpu_buffer_rsrc_t bbuf = buffer_of(p.Bt, BRANCH ? (long)p.N * p.r * 2 : 0);
     constexpr int kNowhere = 0x7FFFFFF0;                // beyond every buffer
     half8_t ubf;
@@ -371,17 +417,40 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
             zp[ti] = __builtin_amdgcn_raw_buffer_load_b96(zbuf, (srow[ti] + g0 * 2) & ~3, 0, 0);
         };
         request_tile(0);
+        uint4_t xraw[kWaveGroups][4];
 #pragma unroll
-        for (int gi = 0; gi < kWaveGroups; ++gi) {
+        for (int gi = 0; gi < kWaveGroups; ++gi)
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
-                xa[gi][t] = __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(xbuf, c < p.M ? ((g0 + gi) * 4 + t) * 1024 + lane * 16 : kNowhere, 0, 0));
-            X[gi] = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(ubuf, ((g0 + gi) * 2 + 0) * kTokens * 4 + q * 16, 0, 0));
-            XS[gi] = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(ubuf, ((g0 + gi) * 2 + 1) * kTokens * 4 + q * 16, 0, 0));
-        }
+            for (int i = 0; i < 4; ++i)
+                xraw[gi][i] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, 4 * i + xtok < p.M && g0 + gi < p.G ? (4 * i + xtok) * p.K * 2 + (g0 + gi) * 256 + xpiece * 16 : kNowhere, 0, 0);
 #pragma unroll
         for (int ti = 1; ti < T; ++ti) request_tile(ti);
         __builtin_amdgcn_sched_barrier(0);
+        // while the weights stream: operands, and both sums per token from the matrix core (accumulator
+        // register v of lane (., q) belongs to token 4 q + v, which is where the sums are needed)
+        half8_t ones;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ones[e] = (half_t)1.0f;
+#pragma unroll
+        for (int gi = 0; gi < kWaveGroups; ++gi) {
+            // through the wave's slab: token rows in, the lane's 64 bytes (token c, quarter q) out
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xslab[wave][(4 * i + xtok) * 17 + xpiece] = xraw[gi][i];
+            __builtin_amdgcn_wave_barrier();
+            uint4_t mine[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mine[i] = xslab[wave][c * 17 + 4 * q + i];
+            __builtin_amdgcn_wave_barrier();
+            arrange_operands<BITS>(mine, xa[gi]);
+            float4_t sx = zero4, sxs = zero4;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                sx = mfma(xa[gi][t], gain_operand<BITS>(t), sx);
+                sxs = mfma(xa[gi][t], ones, sxs);
+            }
+            X[gi] = sx;
+            XS[gi] = 1024.0f * sxs;
+        }
 #pragma unroll
         for (int ti = 0; ti < T; ++ti) {
 #pragma unroll
@@ -402,15 +471,33 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
         for (int u = wave; u < units; u += kMainWaves) {   // wave-uniform; the first unit's Bt operand is already here
             const int ti = u / tap_steps, js = u - ti * tap_steps;
             const int j = js * 32 + q * 8;
+            // t[token c][j .. j + 7]: eight words {t, launch tag} (four 16-byte device-scope loads), written long ago
+            // as a rule.  Should the tags not turn up, the lane computes its eight values itself.
             float t[8];
+            bool ready = false;
+            const int off = j < p.r ? (c * p.r + j) * 8 : kNowhere;
+            for (int spin = 0; spin < kSpinLimit && !ready; ++spin) {
+                bool ok = true;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) t[e] = 0.0f;
-            for (int sl = 0; sl < p.slices; ++sl) {
-                const int off = j < p.r ? ((sl * kTokens + c) * p.r + j) * 4 : kNowhere;
-                const float4_t lo = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(tbuf, off, 0, 0));
-                const float4_t hi = __builtin_bit_cast(float4_t, __builtin_amdgcn_raw_buffer_load_b128(tbuf, off + 16, 0, 0));
+                for (int i = 0; i < 4; ++i) {
+                    const uint4_t w = __builtin_amdgcn_raw_buffer_load_b128(tbuf, off + 16 * i, 0, kCacheSc1);
+                    const uint32_t v0 = w.x, v1 = w.z;
+                    t[2 * i] = __builtin_bit_cast(float, v0);
+                    t[2 * i + 1] = __builtin_bit_cast(float, v1);
+                    ok = ok && (j >= p.r || (w.y == tag && w.w == tag));
+                }
+                ready = __all(ok);
+                if (!ready) __builtin_amdgcn_s_sleep(4);
+            }
+            if (!ready && j < p.r) {
+                const uint16_t *xr = p.x + (size_t)min(c, p.M - 1) * p.K;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) { t[e] += lo[e]; t[4 + e] += hi[e]; }
+                for (int e = 0; e < 8; ++e) {
+                    const uint16_t *ar = p.At + (size_t)(j + e) * p.K;
+                    float a = 0.0f;
+                    for (int k = 0; k < p.K; ++k) a = fmaf((float)__builtin_bit_cast(half_t, xr[k]), (float)__builtin_bit_cast(half_t, ar[k]), a);
+                    t[e] = a;
+                }
             }
             half8_t thi, tlo;                           // t_hi + t_lo carries 22 bits of the fp32 sum
 #pragma unroll
@@ -468,13 +555,10 @@ static hipError_t launch_tiles(const SmallGroup &g, bool branch, dim3 grid, hipS
 }
 
 template <int BITS>
-static hipError_t launch_bits(const SmallGroup &g, int prep_blocks, int main_blocks, hipStream_t stream)
+static hipError_t launch_bits(const SmallGroup &g, int row_blocks, hipStream_t stream)
 {
-    hipLaunchKernelGGL(fbq_small_m_prepare_kernel<BITS>, dim3(prep_blocks, g.n_layers + 1), dim3(64 * kPrepWaves), 0, stream, g);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     const bool branch = g.layer[0].r > 0;
-    const dim3 grid(main_blocks, g.n_layers);
+    const dim3 grid(row_blocks, g.n_layers);
     switch (g.layer[0].tiles_per_block) {
     case 1: return launch_tiles<BITS, 1>(g, branch, grid, stream);
     case 2: return launch_tiles<BITS, 2>(g, branch, grid, stream);
@@ -482,11 +566,10 @@ static hipError_t launch_bits(const SmallGroup &g, int prep_blocks, int main_blo
     }
 }
 
-// workspace: [slices][16][r] fp32 partial sums of t, [G][2][16] fp32 sums, [G][4][64] 16-byte operands
+// workspace: [16 slices][16][r] 8-byte words {fp32 partial sum of t, launch tag}, then [16][r] words {t, launch tag};
+// zero-filled once by the caller
 constexpr int kMaxSlices = 16;       // K slices of the down-projection
-static size_t tpart_bytes(int r) { return (size_t)kMaxSlices * kTokens * r * sizeof(float); }
-static size_t xsum_bytes(int K) { return (size_t)(K / kGroup) * 2 * kTokens * sizeof(float); }
-size_t small_m_workspace_bytes(int K, int r) { return tpart_bytes(r) + xsum_bytes(K) + (size_t)(K / kGroup) * 4 * 64 * 16; }
+size_t small_m_workspace_bytes(int K, int r) { (void)K; return (size_t)(kMaxSlices + 1) * kTokens * r * 8; }
 
 static int tiles_per_block_of(int total_tiles)
 {
@@ -514,28 +597,28 @@ hipError_t launch_gemv_small_m(const LinearArgs *layers, int n_layers, hipStream
     const int tpb = tiles_per_block_of(total_tiles);
     SmallGroup g;
     g.n_layers = n_layers;
-    int prep = ceil_div(first.K / kGroup, kPrepWaves), main_blocks = 0;   // widest row of either grid
+    int row_blocks = 0;                                  // widest row of the grid
     for (int i = 0; i < n_layers; ++i) {
         const LinearArgs &a = layers[i];
         SmallParams &p = g.layer[i];
         p.qw = a.qw; p.scales = a.scales; p.zeros = a.zeros; p.At = a.At; p.Bt = a.Bt; p.x = a.x; p.y = a.y;
-        p.tpart = (float *)a.workspace;                  // each layer's own partial sums of t ...
-        unsigned char *ws0 = (unsigned char *)first.workspace;   // ... and the first layer's copy of the activations for all
-        p.xsum = (float *)(ws0 + tpart_bytes(first.r));
-        p.xop = (uint4 *)(ws0 + tpart_bytes(first.r) + xsum_bytes(first.K));
+        p.tpart = (uint64_t *)a.workspace;               // each layer's own partial sums of t ...
+        p.tsum = p.tpart + (size_t)kMaxSlices * kTokens * a.r;   // ... and their sums
         p.M = a.M; p.N = a.N; p.K = a.K; p.r = a.r;
         p.row_words = (int)row_words(a.K, a.bits);
         p.G = a.K / kGroup;
-        // slices of 1024 (four at K = 4096: more only make the fused kernel add more partial sums), longer where K > 16384
+        // Every consumer block reads all of t at device scope, slice by slice, so few slices: one up to K = 8192 (its
+        // producers have the whole main part of the consumers to finish in), at most four.
+        // slices of 1024 (they only exist to put more compute units to work on a short, latency-bound step), longer where K > 16384
         p.kslice = std::max(1024, ceil_div(ceil_div(a.K, kMaxSlices), 32 * kPrepWaves) * (32 * kPrepWaves));
         p.slices = ceil_div(a.K, p.kslice);
         p.down_blocks = a.r > 0 ? ceil_div(a.r, 16) * p.slices : 0;
+        p.sum_blocks = a.r > 0 ? ceil_div(a.r, 16) : 0;
         p.tiles_per_block = tpb;
-        prep = std::max(prep, p.down_blocks);
-        main_blocks = std::max(main_blocks, ceil_div(ceil_div(a.N, 16), tpb));
+        row_blocks = std::max(row_blocks, p.down_blocks + p.sum_blocks + ceil_div(ceil_div(a.N, 16), tpb));
     }
     for (int i = n_layers; i < kMaxSmallGroup; ++i) g.layer[i] = g.layer[0];   // never indexed: grid.y stops at n_layers
-    return first.bits == 4 ? launch_bits<4>(g, prep, main_blocks, stream) : launch_bits<3>(g, prep, main_blocks, stream);
+    return first.bits == 4 ? launch_bits<4>(g, row_blocks, stream) : launch_bits<3>(g, row_blocks, stream);
 }
 
 }  // namespace fbq

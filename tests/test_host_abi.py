@@ -29,8 +29,8 @@ def test_sizes_and_status_strings():
     assert fbq.workspace_bytes(d, 1) > 0 and fbq.workspace_bytes(fbq.Desc(4096, 4096, 0, 4), 1) == 0
     assert fbq.workspace_bytes(d, 16) >= 16 * 64 * 4
     assert fbq.workspace_bytes(fbq.Desc(4096, 4096, 0, 4), 100) >= 128 * 4096 * 2   # prefill keeps a copy of x
-    assert fbq.workspace_bytes(d, 9) >= 16 * d.r * 4 + 16 * 4096 * 2                 # t partial sums + activations in operand order
-    assert fbq.workspace_bytes(fbq.Desc(4096, 4096, 0, 4), 9) >= 16 * 4096 * 2          # the latter even without a sub-branch
+    assert fbq.workspace_bytes(d, 9) >= 4 * 16 * d.r * 8                               # tagged partial sums of t, one set per K slice
+    assert fbq.workspace_bytes(fbq.Desc(4096, 4096, 0, 4), 9) == 0                      # nothing to hand over without a sub-branch
     assert fbq.workspace_bytes(d, 3) == 3 * fbq.workspace_bytes(d, 1)        # one set of tagged words per token
     assert fbq.status_string(0) == "ok"
     assert all(fbq.status_string(c) for c in range(8))
