@@ -77,8 +77,8 @@ size_t fbq_packed_bytes(const fbq_desc *d);
 
 /* Bytes of device scratch fbq_linear needs for M tokens.  M <= 3: the down-projection t = x.A on its
  * way from the blocks that compute it to the blocks that use it, as tagged 8-byte words (0 when
- * r == 0).  4 <= M <= 16: the activations as matrix-core operands (16 token rows of K fp16), their
- * per-group sums, and fp32 partial sums of t; not 0 even when r == 0.  M > 64: the activations
+ * r == 0).  4 <= M <= 16: the same hand-over for 16 token rows, per K slice and summed (0 when
+ * r == 0).  M > 64: the activations
  * re-ordered for the matrix cores (M rounded up to 128 rows of K fp16), t as two fp16 halves and its
  * partial sums, and, where the launch splits K over blocks, fp32 partial outputs (up to 4 x M x N);
  * not 0 even when r == 0.  17 <= M <= 64: the larger of the two figures above.  0 for an invalid
@@ -107,10 +107,9 @@ fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *sca
  * in fp32 accumulation, rounded once to fp16.  M <= 3 runs the decode GEMV in ONE launch per token
  * count (packed words streamed once per token, unpacked in registers; the down-projection runs in a
  * few producer blocks of the same launch).  4 <= M <= 16 streams the packed words once for all
- * tokens against a 16-token matrix-core tile, after a small launch that does the down-projection
- * and writes the activations as matrix operands; 17 <= M <= 64 takes that same pair of launches 16
- * tokens at a time (the packed words are read once per 16 tokens, which at these counts is still
- * cheaper than unpacking them into fp16 tiles).  M > 64 runs the fp16 MFMA GEMM after a pass that
+ * tokens against a 16-token matrix-core tile, also in ONE launch whose first blocks do the
+ * down-projection; 17 <= M <= 64 takes that launch 16 tokens at a time (the packed words are read
+ * once per 16 tokens, which at these counts is still cheaper than unpacking them into fp16 tiles).  M > 64 runs the fp16 MFMA GEMM after a pass that
  * re-orders x and a separate down-projection; a layer with too few output tiles to fill the GPU has
  * its K range split over up to 4 blocks per tile, summed in fp32 by a last small launch.
  *   x         device [M, K] fp16             qweight, scales, zeros, At, Bt: device, layout above
@@ -147,8 +146,7 @@ typedef struct {
  * bits, the same K-derived kernel variant and a sub-branch (or all without one) are served by ONE
  * launch, up to 8 layers per launch, in the order they appear.  For 4 <= M <= 16, layers with the
  * same bits and K that read the SAME x (the same pointer) and all have a sub-branch (or all have
- * none) share the two launches fbq_linear makes, up to 4 layers: the activations are prepared once,
- * in the workspace of the first of them.  Anything else, and every layer when M > 16, is launched
+ * none) share one launch, up to 4 layers.  Anything else, and every layer when M > 16, is launched
  * on its own.
  *   calls host array of n layers (read during the call only); M tokens, the same for all layers
  * Errors: those of fbq_linear for any layer, reported before ANY launch.

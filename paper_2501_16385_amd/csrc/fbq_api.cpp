@@ -207,7 +207,7 @@ extern "C" fbq_status fbq_linear_group(const fbq_layer_call *calls, int n, int M
         return hip_status(e);
     }
     // Decode: layers that fit one launch (the same kernel instance; for 4..16 tokens also the same
-    // activations, which are then prepared once) are served together.
+    // activations) are served together.
     const bool few = M > kPerTokenMaxM;
     const int cap = few ? kMaxSmallGroup : kMaxGroup;
     bool done[kMaxCalls] = {false};

@@ -256,24 +256,26 @@ def test_group_rejects_a_bad_layer_before_launching_any():
 
 
 @pytest.mark.parametrize("bits", [4, 3])
-def test_replayed_graph_follows_new_activations(bits):
+@pytest.mark.parametrize("M", [1, 9, 20])
+def test_replayed_graph_follows_new_activations(bits, M):
     """A captured launch replayed with new x must hand over the NEW down-projection: the words that carry
-    t are marked with the identity of the launch that wrote them, and every replay is a new launch."""
+    t are marked with the identity of the launch that wrote them, and every replay is a new launch.
+    (One token: the GEMV; 9: the few-token kernel; 20: the same, 16 tokens at a time on one workspace.)"""
     import torch
     import paper_2501_16385_amd as fbq
     spec = spec_of(640, 4096, 64, bits)
     L = make_oracle_layer(spec, config=18)
     dev = to_device_layer(L)
-    x = torch.zeros((1, spec.K), dtype=torch.float16, device="cuda")
-    y = torch.empty((1, spec.N), dtype=torch.float16, device="cuda")
-    ws = torch.zeros(fbq.workspace_bytes(dev.desc, 1), dtype=torch.uint8, device="cuda")
+    x = torch.zeros((M, spec.K), dtype=torch.float16, device="cuda")
+    y = torch.empty((M, spec.N), dtype=torch.float16, device="cuda")
+    ws = torch.zeros(fbq.workspace_bytes(dev.desc, M), dtype=torch.uint8, device="cuda")
     fbq.linear(dev, x, y=y, workspace=ws)                                  # warm-up outside the capture
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         fbq.linear(dev, x, y=y, workspace=ws)
     for rep in range(4):
-        x_np = fbq_synth.make_x(spec, 1, 18, 10 + rep)
+        x_np = fbq_synth.make_x(spec, M, 18, 10 + rep)
         x.copy_(torch.from_numpy(x_np.view(np.int16)).cuda().view(torch.float16))
         torch.cuda.synchronize()
         graph.replay()
