@@ -417,12 +417,20 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
             zp[ti] = __builtin_amdgcn_raw_buffer_load_b96(zbuf, (srow[ti] + g0 * 2) & ~3, 0, 0);
         };
         request_tile(0);
-        uint4_t xraw[kWaveGroups][4];
+        // Activations: all four groups at once (INT4), or two at a time (INT3, whose instances are short of
+        // registers): the second pair is then requested when the first has been arranged, long before the weights are in.
+        constexpr int kXG = BITS == 4 ? kWaveGroups : 2;
+        uint4_t xraw[kXG][4];
+        auto request_x = [&](int part) __attribute__((always_inline)) {
 #pragma unroll
-        for (int gi = 0; gi < kWaveGroups; ++gi)
+            for (int gj = 0; gj < kXG; ++gj)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                xraw[gi][i] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, 4 * i + xtok < p.M && g0 + gi < p.G ? (4 * i + xtok) * p.K * 2 + (g0 + gi) * 256 + xpiece * 16 : kNowhere, 0, 0);
+                for (int i = 0; i < 4; ++i) {
+                    const int grp = g0 + kXG * part + gj;
+                    xraw[gj][i] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, 4 * i + xtok < p.M && grp < p.G ? (4 * i + xtok) * p.K * 2 + grp * 256 + xpiece * 16 : kNowhere, 0, 0);
+                }
+        };
+        request_x(0);
 #pragma unroll
         for (int ti = 1; ti < T; ++ti) request_tile(ti);
         __builtin_amdgcn_sched_barrier(0);
@@ -432,24 +440,32 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
 #pragma unroll
         for (int e = 0; e < 8; ++e) ones[e] = (half_t)1.0f;
 #pragma unroll
-        for (int gi = 0; gi < kWaveGroups; ++gi) {
-            // through the wave's slab: token rows in, the lane's 64 bytes (token c, quarter q) out
+        for (int part = 0; part < kWaveGroups / kXG; ++part) {
+            uint4_t mine[kXG][4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) xslab[wave][(4 * i + xtok) * 17 + xpiece] = xraw[gi][i];
-            __builtin_amdgcn_wave_barrier();
-            uint4_t mine[4];
+            for (int gj = 0; gj < kXG; ++gj) {
+                // through the wave's slab: token rows in, the lane's 64 bytes (token c, quarter q) out
 #pragma unroll
-            for (int i = 0; i < 4; ++i) mine[i] = xslab[wave][c * 17 + 4 * q + i];
-            __builtin_amdgcn_wave_barrier();
-            arrange_operands<BITS>(mine, xa[gi]);
-            float4_t sx = zero4, sxs = zero4;
+                for (int i = 0; i < 4; ++i) xslab[wave][(4 * i + xtok) * 17 + xpiece] = xraw[gj][i];
+                __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                sx = mfma(xa[gi][t], gain_operand<BITS>(t), sx);
-                sxs = mfma(xa[gi][t], ones, sxs);
+                for (int i = 0; i < 4; ++i) mine[gj][i] = xslab[wave][c * 17 + 4 * q + i];
+                __builtin_amdgcn_wave_barrier();
             }
-            X[gi] = sx;
-            XS[gi] = 1024.0f * sxs;
+            if (part + 1 < kWaveGroups / kXG) request_x(part + 1);
+#pragma unroll
+            for (int gj = 0; gj < kXG; ++gj) {
+                const int gi = kXG * part + gj;
+                arrange_operands<BITS>(mine[gj], xa[gi]);
+                float4_t sx = zero4, sxs = zero4;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    sx = mfma(xa[gi][t], gain_operand<BITS>(t), sx);
+                    sxs = mfma(xa[gi][t], ones, sxs);
+                }
+                X[gi] = sx;
+                XS[gi] = 1024.0f * sxs;
+            }
         }
 #pragma unroll
         for (int ti = 0; ti < T; ++ti) {
@@ -549,7 +565,9 @@ static int cu_count()
 template <int BITS, int T>
 static hipError_t launch_tiles(const SmallGroup &g, bool branch, dim3 grid, hipStream_t stream)
 {
-    if (branch) hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true>), grid, dim3(64 * kMainWaves), 0, stream, g);
+    // (the INT3 three-tile instance without the branch comes out of the compiler with spills; the one with
+    // the branch does not, and with r = 0 it does the same work)
+    if (branch || (BITS == 3 && T == 3)) hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true>), grid, dim3(64 * kMainWaves), 0, stream, g);
     else hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, false>), grid, dim3(64 * kMainWaves), 0, stream, g);
     return hipGetLastError();
 }
@@ -571,10 +589,19 @@ static hipError_t launch_bits(const SmallGroup &g, int row_blocks, hipStream_t s
 constexpr int kMaxSlices = 16;       // K slices of the down-projection
 size_t small_m_workspace_bytes(int K, int r) { (void)K; return (size_t)(kMaxSlices + 1) * kTokens * r * 8; }
 
-static int tiles_per_block_of(int total_tiles)
+static int tiles_per_block_of(int total_tiles, int preparing_blocks)
 {
-    // one block per compute unit where the launch has that many tiles, at most kMaxTiles tiles each
-    return std::min(kMaxTiles, std::max(1, ceil_div(total_tiles, cu_count())));
+    // One block per compute unit where the launch has that many tiles, at most kMaxTiles tiles each.  The
+    // blocks that do the down-projection hold a compute unit each while they run: counted in, a 4096-row
+    // layer takes two tiles per block in one round instead of one tile in a round and a bit.
+    const int free_units = std::max(cu_count() / 2, cu_count() - preparing_blocks);
+    return std::min(kMaxTiles, std::max(1, ceil_div(total_tiles, free_units)));
+}
+
+static int slice_length(int K)
+{
+    // slices of 1024 (they only exist to put more compute units to work on a short, latency-bound step), longer where K > 16384
+    return std::max(1024, ceil_div(ceil_div(K, kMaxSlices), 32 * kPrepWaves) * (32 * kPrepWaves));
 }
 
 // Layers may share the two launches when they read the same activations and need the same kernel
@@ -594,7 +621,10 @@ hipError_t launch_gemv_small_m(const LinearArgs *layers, int n_layers, hipStream
         if (!small_m_group_compatible(first, layers[i])) return hipErrorInvalidValue;
         total_tiles += ceil_div(layers[i].N, 16);
     }
-    const int tpb = tiles_per_block_of(total_tiles);
+    int preparing = 0;
+    for (int i = 0; i < n_layers; ++i)
+        if (layers[i].r > 0) preparing += ceil_div(layers[i].r, 16) * (ceil_div(layers[i].K, slice_length(layers[i].K)) + 1);
+    const int tpb = tiles_per_block_of(total_tiles, preparing);
     SmallGroup g;
     g.n_layers = n_layers;
     int row_blocks = 0;                                  // widest row of the grid
@@ -609,8 +639,7 @@ hipError_t launch_gemv_small_m(const LinearArgs *layers, int n_layers, hipStream
         p.G = a.K / kGroup;
         // Every consumer block reads all of t at device scope, slice by slice, so few slices: one up to K = 8192 (its
         // producers have the whole main part of the consumers to finish in), at most four.
-        // slices of 1024 (they only exist to put more compute units to work on a short, latency-bound step), longer where K > 16384
-        p.kslice = std::max(1024, ceil_div(ceil_div(a.K, kMaxSlices), 32 * kPrepWaves) * (32 * kPrepWaves));
+        p.kslice = slice_length(a.K);
         p.slices = ceil_div(a.K, p.kslice);
         p.down_blocks = a.r > 0 ? ceil_div(a.r, 16) * p.slices : 0;
         p.sum_blocks = a.r > 0 ? ceil_div(a.r, 16) : 0;
