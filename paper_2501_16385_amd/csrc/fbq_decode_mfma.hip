@@ -58,7 +58,7 @@ constexpr int kTokens = 16;          // rows of the matrix-core tile; M is padde
 constexpr int kMainWaves = 8;        // waves per block of the fused kernel; they split K
 constexpr int kWaveGroups = 4;       // consecutive quantization groups a wave takes per pass over the block's tiles
 constexpr int kPassGroups = kMainWaves * kWaveGroups;   // groups one pass covers (4096 codes)
-constexpr int kMaxTiles = 3;         // 16-row tiles per block (more would not fit the register file next to the activations)
+constexpr int kMaxTiles = 4;         // 16-row tiles per block (more would not fit the register file next to the activations)
 
 __device__ __forceinline__ half2_t h2_of(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
 __device__ __forceinline__ half8_t pack8(half2_t a, half2_t b, half2_t c, half2_t d)
@@ -417,9 +417,9 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
             zp[ti] = __builtin_amdgcn_raw_buffer_load_b96(zbuf, (srow[ti] + g0 * 2) & ~3, 0, 0);
         };
         request_tile(0);
-        // Activations: all four groups at once (INT4), or two at a time (INT3, whose instances are short of
-        // registers): the second pair is then requested when the first has been arranged, long before the weights are in.
-        constexpr int kXG = BITS == 4 ? kWaveGroups : 2;
+        // Activations: all four groups at once, or two at a time where the instance is short of registers (INT3,
+        // four tiles): the second pair is then requested when the first has been arranged, long before the weights are in.
+        constexpr int kXG = BITS == 4 && T <= 3 ? kWaveGroups : 2;
         uint4_t xraw[kXG][4];
         auto request_x = [&](int part) __attribute__((always_inline)) {
 #pragma unroll
@@ -580,7 +580,8 @@ static hipError_t launch_bits(const SmallGroup &g, int row_blocks, hipStream_t s
     switch (g.layer[0].tiles_per_block) {
     case 1: return launch_tiles<BITS, 1>(g, branch, grid, stream);
     case 2: return launch_tiles<BITS, 2>(g, branch, grid, stream);
-    default: return launch_tiles<BITS, 3>(g, branch, grid, stream);
+    case 3: return launch_tiles<BITS, 3>(g, branch, grid, stream);
+    default: return launch_tiles<4, 4>(g, branch, grid, stream);   // INT4 only
     }
 }
 
@@ -589,13 +590,21 @@ static hipError_t launch_bits(const SmallGroup &g, int row_blocks, hipStream_t s
 constexpr int kMaxSlices = 16;       // K slices of the down-projection
 size_t small_m_workspace_bytes(int K, int r) { (void)K; return (size_t)(kMaxSlices + 1) * kTokens * r * 8; }
 
-static int tiles_per_block_of(int total_tiles, int preparing_blocks)
+static int tiles_per_block_of(int total_tiles, int preparing_blocks, int bits)
 {
-    // One block per compute unit where the launch has that many tiles, at most kMaxTiles tiles each.  The
-    // blocks that do the down-projection hold a compute unit each while they run: counted in, a 4096-row
-    // layer takes two tiles per block in one round instead of one tile in a round and a bit.
-    const int free_units = std::max(cu_count() / 2, cu_count() - preparing_blocks);
-    return std::min(kMaxTiles, std::max(1, ceil_div(total_tiles, free_units)));
+    // Blocks run one per compute unit, in rounds; a block's time grows with its tiles plus about one
+    // tile's worth of fixed work (arranging the activations, the up-projection, the reduction).  So: the
+    // tile count that makes rounds x (tiles + 1) smallest, the blocks that do the down-projection
+    // counted in (they hold a compute unit each while they run).  4096 rows: two tiles in one round
+    // instead of one tile in a round and a bit; q/k/v together: four tiles in one round instead of
+    // three in two; gate/up together: three tiles in two full rounds rather than four in one and a half.
+    const int max_tiles = bits == 4 ? kMaxTiles : kMaxTiles - 1;           // INT3 with four tiles spills
+    int best = 1, best_cost = 1 << 30;
+    for (int t = 1; t <= max_tiles; ++t) {
+        const int cost = ceil_div(ceil_div(total_tiles, t) + preparing_blocks, cu_count()) * (t + 1);
+        if (cost < best_cost) { best = t; best_cost = cost; }
+    }
+    return best;
 }
 
 static int slice_length(int K)
@@ -624,7 +633,7 @@ hipError_t launch_gemv_small_m(const LinearArgs *layers, int n_layers, hipStream
     int preparing = 0;
     for (int i = 0; i < n_layers; ++i)
         if (layers[i].r > 0) preparing += ceil_div(layers[i].r, 16) * (ceil_div(layers[i].K, slice_length(layers[i].K)) + 1);
-    const int tpb = tiles_per_block_of(total_tiles, preparing);
+    const int tpb = tiles_per_block_of(total_tiles, preparing, first.bits);
     SmallGroup g;
     g.n_layers = n_layers;
     int row_blocks = 0;                                  // widest row of the grid
