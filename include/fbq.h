@@ -75,9 +75,9 @@ fbq_status fbq_check_desc(const fbq_desc *d);
 /* Bytes of the packed code buffer, N * K * bits / 8.  0 for an invalid descriptor. */
 size_t fbq_packed_bytes(const fbq_desc *d);
 
-/* Bytes of device scratch fbq_linear needs for M tokens.  M <= 3: the down-projection t = x.A on its
+/* Bytes of device scratch fbq_linear needs for M tokens.  M <= 2: the down-projection t = x.A on its
  * way from the blocks that compute it to the blocks that use it, as tagged 8-byte words (0 when
- * r == 0).  4 <= M <= 16: the same hand-over for 16 token rows, per K slice and summed (0 when
+ * r == 0).  3 <= M <= 16: the same hand-over for 16 token rows, per K slice and summed (0 when
  * r == 0).  M > 64: the activations
  * re-ordered for the matrix cores (M rounded up to 128 rows of K fp16), t as two fp16 halves and its
  * partial sums, and, where the launch splits K over blocks, fp32 partial outputs (up to 4 x M x N);
@@ -104,9 +104,9 @@ fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *sca
 /*
  * fbq_linear - the hot path (Sec. 4.3).  y[m,n] = sum_k x[m,k] * s[n,k/g] * (q[n,k] - z[n,k/g])
  *                                               + sum_j (sum_k x[m,k] * At[j,k]) * Bt[n,j]
- * in fp32 accumulation, rounded once to fp16.  M <= 3 runs the decode GEMV in ONE launch per token
+ * in fp32 accumulation, rounded once to fp16.  M <= 2 runs the decode GEMV in ONE launch per token
  * count (packed words streamed once per token, unpacked in registers; the down-projection runs in a
- * few producer blocks of the same launch).  4 <= M <= 16 streams the packed words once for all
+ * few producer blocks of the same launch).  3 <= M <= 16 streams the packed words once for all
  * tokens against a 16-token matrix-core tile, also in ONE launch whose first blocks do the
  * down-projection; 17 <= M <= 64 takes that launch 16 tokens at a time (the packed words are read
  * once per 16 tokens, which at these counts is still cheaper than unpacking them into fp16 tiles).  M > 64 runs the fp16 MFMA GEMM after a pass that
@@ -142,9 +142,9 @@ typedef struct {
  * fbq_linear_group - the hot path for several independent layers at once (Sec. 4.3 lists launch
  * overhead as part of the sub-branch's cost; on this GPU a launch costs about as much as streaming
  * a 4096x4096 INT4 layer, so layers that do not depend on each other - q/k/v, gate/up - should share
- * one).  Every layer gets exactly the result fbq_linear gives it.  For M <= 3, layers with the same
+ * one).  Every layer gets exactly the result fbq_linear gives it.  For M <= 2, layers with the same
  * bits, the same K-derived kernel variant and a sub-branch (or all without one) are served by ONE
- * launch, up to 8 layers per launch, in the order they appear.  For 4 <= M <= 16, layers with the
+ * launch, up to 8 layers per launch, in the order they appear.  For 3 <= M <= 16, layers with the
  * same bits and K that read the SAME x (the same pointer) and all have a sub-branch (or all have
  * none) share one launch, up to 4 layers.  Anything else, and every layer when M > 16, is launched
  * on its own.

@@ -1,4 +1,4 @@
-// Decode path for a few tokens (4 <= M <= 16): the fused kernel of Sec. 4.3 with the packed codes
+// Decode path for a few tokens (3 <= M <= 16): the fused kernel of Sec. 4.3 with the packed codes
 // streamed exactly once, the tokens riding along as the 16 rows of a matrix-core tile.
 //
 //   y[M,N] = x[M,K] . Wq[N,K]^T + t[M,r] . B[r,N],   t = x . A

@@ -217,7 +217,7 @@ def test_gpu_feedback_quantizer_matches_oracle(bits, N, K, r):
 # ------------------------------------------------------------------ grouped launches, graph replay
 
 @pytest.mark.parametrize("bits", [4, 3])
-@pytest.mark.parametrize("M", [1, 3, 4, 13])
+@pytest.mark.parametrize("M", [1, 2, 3, 13])
 def test_group_call_equals_single_calls(bits, M):
     """q/k/v-style layers sharing x, one wider layer, one branch-free layer and one with another K:
     fbq_linear_group must give every layer bit for bit what fbq_linear gives it, and match the oracle."""
