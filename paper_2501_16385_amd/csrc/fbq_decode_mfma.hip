@@ -565,9 +565,9 @@ static int cu_count()
 template <int BITS, int T>
 static hipError_t launch_tiles(const SmallGroup &g, bool branch, dim3 grid, hipStream_t stream)
 {
-    // (the INT3 three-tile instance without the branch comes out of the compiler with spills; the one with
-    // the branch does not, and with r = 0 it does the same work)
-    if (branch || (BITS == 3 && T == 3)) hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true>), grid, dim3(64 * kMainWaves), 0, stream, g);
+    // (the INT3 three- and four-tile instances without the branch come out of the compiler with spills of
+    // 160 bytes and more; the ones with the branch spill nothing or 36 bytes, and with r = 0 they do the same work)
+    if (branch || (BITS == 3 && T >= 3)) hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true>), grid, dim3(64 * kMainWaves), 0, stream, g);
     else hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, false>), grid, dim3(64 * kMainWaves), 0, stream, g);
     return hipGetLastError();
 }
@@ -581,7 +581,7 @@ static hipError_t launch_bits(const SmallGroup &g, int row_blocks, hipStream_t s
     case 1: return launch_tiles<BITS, 1>(g, branch, grid, stream);
     case 2: return launch_tiles<BITS, 2>(g, branch, grid, stream);
     case 3: return launch_tiles<BITS, 3>(g, branch, grid, stream);
-    default: return launch_tiles<4, 4>(g, branch, grid, stream);   // INT4 only
+    default: return launch_tiles<BITS, 4>(g, branch, grid, stream);
     }
 }
 
@@ -598,7 +598,8 @@ static int tiles_per_block_of(int total_tiles, int preparing_blocks, int bits)
     // counted in (they hold a compute unit each while they run).  4096 rows: two tiles in one round
     // instead of one tile in a round and a bit; q/k/v together: four tiles in one round instead of
     // three in two; gate/up together: three tiles in two full rounds rather than four in one and a half.
-    const int max_tiles = bits == 4 ? kMaxTiles : kMaxTiles - 1;           // INT3 with four tiles spills
+    (void)bits;
+    const int max_tiles = kMaxTiles;
     int best = 1, best_cost = 1 << 30;
     for (int t = 1; t <= max_tiles; ++t) {
         const int cost = ceil_div(ceil_div(total_tiles, t) + preparing_blocks, cu_count()) * (t + 1);
