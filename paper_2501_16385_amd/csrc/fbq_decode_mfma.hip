@@ -121,7 +121,7 @@ __device__ __forceinline__ half2_t field(uint32_t w, uint32_t mask, uint32_t k64
 }
 
 // The lane's 32 codes of one group and their four matrix operands.  Pair order (also the order of
-// the prepared activations): INT4 word j -> codes (8j+f, 8j+f+4), f = 0..3;  INT3 word j -> codes
+// the arranged activations): INT4 word j -> codes (8j+f, 8j+f+4), f = 0..3;  INT3 word j -> codes
 // (10j+f, 10j+f+5), f = 0..4, and codes (30, 31) last.
 template <int BITS>
 struct SmallCodes {
@@ -567,8 +567,12 @@ static hipError_t launch_tiles(const SmallGroup &g, bool branch, dim3 grid, hipS
 {
     // (the INT3 three- and four-tile instances without the branch come out of the compiler with spills of
     // 160 bytes and more; the ones with the branch spill nothing or 36 bytes, and with r = 0 they do the same work)
-    if (branch || (BITS == 3 && T >= 3)) hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true>), grid, dim3(64 * kMainWaves), 0, stream, g);
-    else hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, false>), grid, dim3(64 * kMainWaves), 0, stream, g);
+    if constexpr (BITS == 3 && T >= 3) {
+        hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true>), grid, dim3(64 * kMainWaves), 0, stream, g);
+    } else {
+        if (branch) hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true>), grid, dim3(64 * kMainWaves), 0, stream, g);
+        else hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, false>), grid, dim3(64 * kMainWaves), 0, stream, g);
+    }
     return hipGetLastError();
 }
 
@@ -614,7 +618,7 @@ static int slice_length(int K)
     return std::max(1024, ceil_div(ceil_div(K, kMaxSlices), 32 * kPrepWaves) * (32 * kPrepWaves));
 }
 
-// Layers may share the two launches when they read the same activations and need the same kernel
+// Layers may share the launch when they read the same activations and need the same kernel
 // instance; a branch-free layer never joins layers with a sub-branch.
 bool small_m_group_compatible(const LinearArgs &a, const LinearArgs &b)
 {
