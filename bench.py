@@ -142,6 +142,10 @@ def main():
         print("bench.py: the default benchmark times the decode path (M <= 16)", file=sys.stderr)
         sys.exit(2)
     base_layers, xs = build_layer_set(specs, args.config, M, torch, fbq)
+    # the layers of a stage read the same activations, as in a decoder (q/k/v: the normalised hidden state; gate/up alike)
+    for grp in stages_of(specs):
+        for i in grp[1:]:
+            xs[i] = xs[grp[0]]
     nbytes = [fbq_synth.algorithmic_bytes(s.N, s.K, s.r, s.bits, M, s.group) for s in specs]
     nbytes_plain = [fbq_synth.algorithmic_bytes(s.N, s.K, 0, s.bits, M, s.group) for s in specs]
     set_bytes = sum(nbytes)
@@ -269,7 +273,7 @@ def main():
                                                      "GBps": round(set_bytes / ms_graph_all / 1e6, 1)},
                       "per_layer": mode(ms_layer, ms_layer_plain, len(per_layer)),
                       "merged": mode(ms_merged, ms_merged_plain, 2)},
-        "roofline": {"bound": "hbm", "kernel": "fbq_gemv_kernel, the launch serving {" +
+        "roofline": {"bound": "hbm", "kernel": ("fbq_gemv_kernel" if M <= 2 else "fbq_small_m_kernel") + ", the launch serving {" +
                      ",".join(specs[i].name for i in dom) + "}", "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "avg_launch_us": round(ms_dom * 1e3, 3), "bytes_per_launch": dom_bytes},
