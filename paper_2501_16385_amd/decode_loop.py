@@ -3,7 +3,9 @@ down) are fused sub-branched quantized linears, replayed from one HIP graph per 
 
     python -m paper_2501_16385_amd.decode_loop --layers 32 --hidden 4096 --inter 11008 --r 128 --bits 4
 
-The paper reports whole-model decode speed for this configuration (Sec. 5.3: batch 1, rank 128).  Only
+The paper reports whole-model decode speed for this configuration (Sec. 5.3: batch 1, rank 128);
+--batch B decodes B independent sequences per step (B rows through every linear: from three rows on
+the matrix-core kernel streams the weights once for all of them).  Only
 the linear layers are the paper's method, so only they are real here; the glue between them is the
 least that keeps the data flow of a decoder layer and the values bounded:
 
@@ -39,11 +41,11 @@ def layer_shapes(hidden: int, inter: int):
 class DecoderStack:
     """layers: list (one per decoder layer) of dicts name -> fbq.DeviceLayer."""
 
-    def __init__(self, layers, hidden: int, inter: int, keep_per_layer_buffers: bool = False):
-        self.layers, self.hidden, self.inter = layers, hidden, inter
+    def __init__(self, layers, hidden: int, inter: int, keep_per_layer_buffers: bool = False, batch: int = 1):
+        self.layers, self.hidden, self.inter, self.batch = layers, hidden, inter, batch
         self.lib = fbq.load()
         dev = "cuda"
-        f16 = lambda n: torch.zeros((1, n), dtype=torch.float16, device=dev)
+        f16 = lambda n: torch.zeros((batch, n), dtype=torch.float16, device=dev)
         self.x = f16(hidden)
         n_buf = len(layers) if keep_per_layer_buffers else 1
         self.buf = [{"q": f16(hidden), "k": f16(hidden), "v": f16(hidden), "o": f16(hidden), "h": f16(hidden),
@@ -53,15 +55,14 @@ class DecoderStack:
         self.ws = [{n: self._workspace(l[n].desc) for n in NAMES} for l in layers]
         self.graph = None
 
-    @staticmethod
-    def _workspace(desc):
-        need = fbq.workspace_bytes(desc, 1)
+    def _workspace(self, desc):
+        need = fbq.workspace_bytes(desc, self.batch)
         return torch.zeros(need, dtype=torch.uint8, device="cuda") if need else None
 
     def _group(self, li, names, xs, ys, stream_ptr):
         l, ws = self.layers[li], self.ws[li]
         arr = fbq.make_group([l[n] for n in names], xs, ys, [ws[n] for n in names])
-        rc = self.lib.fbq_linear_group(arr, len(names), 1, stream_ptr)
+        rc = self.lib.fbq_linear_group(arr, len(names), self.batch, stream_ptr)
         if rc:
             raise RuntimeError(f"fbq_linear_group: {fbq.status_string(rc)}")
 
@@ -111,11 +112,12 @@ def main():
     ap.add_argument("--inter", type=int, default=11008)
     ap.add_argument("--r", type=int, default=128)
     ap.add_argument("--bits", type=int, default=4)
-    ap.add_argument("--tokens", type=int, default=64)
+    ap.add_argument("--tokens", type=int, default=64, help="decode steps to time")
+    ap.add_argument("--batch", type=int, default=1, help="sequences decoded together (rows per step)")
     ap.add_argument("--warmup", type=int, default=4)
     a = ap.parse_args()
-    stack = DecoderStack(random_stack(a.layers, a.hidden, a.inter, a.r, a.bits), a.hidden, a.inter)
-    stack.x.copy_(torch.randn(1, a.hidden, device="cuda").half())
+    stack = DecoderStack(random_stack(a.layers, a.hidden, a.inter, a.r, a.bits), a.hidden, a.inter, batch=a.batch)
+    stack.x.copy_(torch.randn(a.batch, a.hidden, device="cuda").half())
     g = stack.capture()
     for _ in range(a.warmup):
         g.replay()
@@ -129,9 +131,9 @@ def main():
     us = e0.elapsed_time(e1) / a.tokens * 1e3
     shapes = layer_shapes(a.hidden, a.inter)
     from .perf import algorithmic_bytes
-    nbytes = a.layers * sum(algorithmic_bytes(N, K, a.r, a.bits, 1) for N, K in shapes.values())
-    print(json.dumps({"tokens_per_s": round(1e6 / us, 1), "us_per_token": round(us, 1), "layers": a.layers,
-                      "fused_launches_per_token": 4 * a.layers, "GBps_over_linear_layers": round(nbytes / us / 1e3, 1),
+    nbytes = a.layers * sum(algorithmic_bytes(N, K, a.r, a.bits, a.batch) for N, K in shapes.values())
+    print(json.dumps({"tokens_per_s": round(a.batch * 1e6 / us, 1), "us_per_step": round(us, 1), "batch": a.batch, "layers": a.layers,
+                      "fused_launches_per_step": 4 * a.layers, "GBps_over_linear_layers": round(nbytes / us / 1e3, 1),
                       "bits": a.bits, "r": a.r, "hidden": a.hidden, "inter": a.inter, "tokens_timed": a.tokens,
                       "finite": bool(torch.isfinite(stack.x).all())}), flush=True)
 

@@ -12,8 +12,9 @@ Y_TOL = 1e-3          # relative L2 per linear layer, as for the single-layer te
 HIDDEN, INTER, RANK = 256, 640, 16
 
 
+@pytest.mark.parametrize("batch", [1, 5])
 @pytest.mark.parametrize("bits", [4, 3])
-def test_decoder_stack_linears_match_oracle_and_graph_replays_are_exact(bits):
+def test_decoder_stack_linears_match_oracle_and_graph_replays_are_exact(bits, batch):
     import torch
     from paper_2501_16385_amd.decode_loop import DecoderStack, NAMES, layer_shapes
 
@@ -27,10 +28,10 @@ def test_decoder_stack_linears_match_oracle_and_graph_replays_are_exact(bits):
         oracle_layers.append(ol)
         dev_layers.append({n: to_device_layer(ol[n]) for n in NAMES})
 
-    x0 = fbq_synth.make_x(fbq_synth.LayerSpec("x", HIDDEN, HIDDEN, 0, bits), 1, 40 + bits, 0)
+    x0 = fbq_synth.make_x(fbq_synth.LayerSpec("x", HIDDEN, HIDDEN, 0, bits), batch, 40 + bits, 0)
     x0d = torch.from_numpy(x0.view(np.int16)).cuda().view(torch.float16)
 
-    stack = DecoderStack(dev_layers, HIDDEN, INTER, keep_per_layer_buffers=True)
+    stack = DecoderStack(dev_layers, HIDDEN, INTER, keep_per_layer_buffers=True, batch=batch)
     stack.x.copy_(x0d)
     stack.step()
     torch.cuda.synchronize()
