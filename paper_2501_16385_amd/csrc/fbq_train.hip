@@ -41,7 +41,6 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kTile = 128;           // the default block tile, both ways (64 WM x 64 WN in general)
 constexpr int kStepK = 64;           // k per step: one 128-byte row segment per operand row
 constexpr float kDeltaGain = 256.0f; // Delta_F is stored as fp16(256 Delta_F)
 constexpr int kXcds = 8;
