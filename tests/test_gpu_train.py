@@ -34,7 +34,7 @@ def _problem(N, K, r, bits, T, seed, b_zero):
     return spec, W, X, A, B
 
 
-@pytest.mark.parametrize("K,T", [(256, 100), (1408, 321)])
+@pytest.mark.parametrize("K,T", [(256, 100), (1408, 321), (256, 4100)])     # the last one: few tiles, long contraction, K split over blocks
 def test_gram_matches_definition(K, T):
     spec = fbq_synth.LayerSpec("gram", 128, K, 8, 4)
     X = fbq_synth.make_x(spec, T, 33, 1)
@@ -52,6 +52,8 @@ CASES = [
     (300, 1408, 24, 130, False),      # ragged N: partial tiles, zero padding of the transposed operands
     (384, 1024, 64, 256, True),
     (130, 256, 8, 70, False),
+    (256, 512, 128, 96, False),       # rank 128: the stacked operand [Q; At] spans two tile rows
+    (1100, 384, 40, 64, False),       # more rows than input features; a rank that is no multiple of 16
 ]
 
 
