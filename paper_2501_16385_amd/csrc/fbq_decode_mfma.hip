@@ -14,10 +14,12 @@
 // token c in the first operand and for output row c in the second, and the instruction only needs
 // both operands to agree on which k that is.
 //
-// Weights.  For one quantization group (128 codes) of 16 consecutive output rows, lane (c, q) loads
+// Weights.  For one quantization group (128 codes) of 16 consecutive output rows, lane (c, q) needs
 // the 32 codes k = 32 q .. 32 q + 31 of row c: one 16-byte (INT4) or 12-byte (INT3) load straight
-// from the packed row into registers, no LDS in between.  A wave owns four consecutive groups, so
-// the 16 row segments it reads are 256 (192) contiguous bytes each.  Masking a packed word with
+// from the packed row into registers, no LDS memory in between (in most instances a neighbouring
+// lane does the load, so that the four lanes of a load quad read one row, and the words change lanes
+// afterwards).  A wave owns four consecutive groups, so the 16 row segments it reads are 256 (192)
+// contiguous bytes each.  Masking a packed word with
 // 0x000F000F and OR-ing 0x64006400 leaves two codes as the fp16 pair (1024 + q, 1024 + q'); fields
 // that sit 4 (3, 6) bits higher come out as 1024 + 16 q (8 q, 64 q).  These go into the matrix
 // instruction as they are: one v_and_or_b32 per two codes is all the de-quantization the inner
@@ -139,8 +141,13 @@ struct SmallCodes {
         }
     }
 
-    __device__ __forceinline__ void operands(uint32_t k6400, half8_t (&b)[4]) const
+    // With from_lane >= 0 the words arrived in load order (lane l: row l / 4, quarter l % 4) and move to matrix order first.
+    __device__ __forceinline__ void operands(uint32_t k6400, int from_lane, half8_t (&b)[4])
     {
+        if (from_lane >= 0) {
+#pragma unroll
+            for (int j = 0; j < kWords; ++j) w[j] = (uint32_t)__builtin_amdgcn_ds_bpermute(from_lane, (int)w[j]);
+        }
         if constexpr (BITS == 4) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -355,14 +362,26 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
     // 256 contiguous bytes (the lane's own 64 bytes of its token would make every load a 64-segment gather)
     const int xtok = lane >> 4, xpiece = lane & 15;
 
-    // rows past N re-read the last row: computed, never stored
+    // Who loads what.  The matrix instruction wants lane (c, q) = lane q * 16 + c to hold quarter q of row c,
+    // but loaded that way the four neighbouring lanes of a load quad read four different rows, i.e. four
+    // cache lines, and a wave-wide load costs the address path 64 cycles.  So lane l fetches quarter l % 4 of
+    // row l / 4 - a quad reads 64 (48) contiguous bytes of one row, 16 cycles per load - and the words change
+    // lanes afterwards (ds_bpermute: lane (c, q) takes those of lane 4 c + q).  Scale and zero likewise: the
+    // four lanes of a quad read the same 12 bytes of row l / 4, lane (c, q) takes them from lane 4 c.
+    // Measured: 4096 -> 11008 11.9 -> 10.8 us, the {gate,up} pair 21.2 -> 19.9, 28672 -> 8192 52.7 -> 49.1.  Not
+    // for INT4 with four tiles per block (the extra lane traffic costs more than the address path gains: q/k/v
+    // 13.3 -> 14.0; INT3 with four tiles gains, 14.3 -> 13.0) and not for INT3 with two tiles (that instance then spills).
+    // Rows past N re-read the last row: computed, never stored.
+    constexpr bool kQuadLoads = BITS == 4 ? T <= 3 : T != 2;
+    const int from_lane = (4 * c + q) * 4, from_quad = (4 * c) * 4;   // byte addresses of the source lanes
     int qrow[T], srow[T], odd[T];
 #pragma unroll
     for (int ti = 0; ti < T; ++ti) {
         const int n = min((tile0 + ti) * 16 + c, p.N - 1);
-        qrow[ti] = n * row_bytes + q * kPiece;
-        srow[ti] = n * p.G * 2;
-        odd[ti] = (n * p.G) & 1;                        // the wave's first group is a multiple of four
+        const int n_ld = kQuadLoads ? min((tile0 + ti) * 16 + (lane >> 2), p.N - 1) : n;
+        qrow[ti] = n_ld * row_bytes + (kQuadLoads ? lane & 3 : q) * kPiece;
+        srow[ti] = n_ld * p.G * 2;
+        odd[ti] = (n * p.G) & 1;                        // of the row the lane ends up with; the wave's first group is a multiple of four
     }
 
     // Up-projection: r more values of k, in units of (tile, 32 taps) dealt out to the waves.  Lane (c, q)
@@ -469,10 +488,17 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
         }
 #pragma unroll
         for (int ti = 0; ti < T; ++ti) {
+            // scale and zero of the lane's row from the lane that fetched them
+            if constexpr (kQuadLoads) {
+            sc[ti] = uint3_t{(uint32_t)__builtin_amdgcn_ds_bpermute(from_quad, (int)sc[ti].x), (uint32_t)__builtin_amdgcn_ds_bpermute(from_quad, (int)sc[ti].y),
+                             (uint32_t)__builtin_amdgcn_ds_bpermute(from_quad, (int)sc[ti].z)};
+            zp[ti] = uint3_t{(uint32_t)__builtin_amdgcn_ds_bpermute(from_quad, (int)zp[ti].x), (uint32_t)__builtin_amdgcn_ds_bpermute(from_quad, (int)zp[ti].y),
+                             (uint32_t)__builtin_amdgcn_ds_bpermute(from_quad, (int)zp[ti].z)};
+            }
 #pragma unroll
             for (int gi = 0; gi < kWaveGroups; ++gi) {
                 half8_t b[4];
-                cw[ti][gi].operands(k6400, b);
+                cw[ti][gi].operands(k6400, kQuadLoads ? from_lane : -1, b);
                 float4_t D = zero4;
 #pragma unroll
                 for (int t = 0; t < 4; ++t) D = mfma(xa[gi][t], b[t], D);
