@@ -202,12 +202,20 @@ __device__ void down_proj_block(const SmallParams &p, int b, uint32_t tag, float
     const int kw = p.kslice / kPrepWaves;               // a multiple of 32
     const int kbeg = slice * p.kslice + wave * kw;
     const int kend = min(p.K, kbeg + kw);
-    const uint16_t *xr = p.x + (size_t)min(c, p.M - 1) * p.K + 8 * q;
-    const uint16_t *ar = p.At + (size_t)min(j0 + c, p.r - 1) * p.K + 8 * q;
+    // As in the consumers: lane l fetches the piece l % 4 of row l / 4 (a load quad reads 64 contiguous bytes
+    // of one row), and lane (c, q) then takes the words of lane 4 c + q.
+    const int ld_row = lane >> 2, ld_piece = lane & 3, from_lane = (4 * c + q) * 4;
+    const uint16_t *xr = p.x + (size_t)min(ld_row, p.M - 1) * p.K + 8 * ld_piece;
+    const uint16_t *ar = p.At + (size_t)min(j0 + ld_row, p.r - 1) * p.K + 8 * ld_piece;
+    auto to_matrix_order = [&](uint4 v) __attribute__((always_inline)) {
+        const uint4_t w = {(uint32_t)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.x), (uint32_t)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.y),
+                           (uint32_t)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.z), (uint32_t)__builtin_amdgcn_ds_bpermute(from_lane, (int)v.w)};
+        return __builtin_bit_cast(half8_t, w);
+    };
     float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll 8
     for (int k = kbeg; k < kend; k += 32)
-        acc = mfma(*reinterpret_cast<const half8_t *>(xr + k), *reinterpret_cast<const half8_t *>(ar + k), acc);
+        acc = mfma(to_matrix_order(*reinterpret_cast<const uint4 *>(xr + k)), to_matrix_order(*reinterpret_cast<const uint4 *>(ar + k)), acc);
     red[wave][lane] = acc;
     __syncthreads();
     if (wave == 0) {
