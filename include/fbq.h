@@ -119,6 +119,10 @@ fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *sca
  *             and under graph replay: every launch marks what it writes with its own identity.
  *             Calls that may run concurrently must not share a workspace.
  * Errors: FBQ_ERR_NULL, _SHAPE, _UNSUPPORTED, _ALIGN, _WORKSPACE before any launch; FBQ_ERR_HIP.
+ * Test hook: up to 16 tokens the blocks that use t wait a bounded number of polls (32768, about 10 ms)
+ * for the blocks of the same launch that compute it, then compute their share themselves; the
+ * environment variable FBQ_SPIN_LIMIT, read at every call, replaces that number, and a negative value
+ * sends every block down the fall-back path at once (same results, slower; every kernel still ends).
  */
 fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
                       const void *zeros, const void *At, const void *Bt, void *y, void *workspace,

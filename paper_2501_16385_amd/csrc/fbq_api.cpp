@@ -3,6 +3,8 @@
 // (a one-off layout conversion that is off the hot path by definition).
 #include <string.h>
 
+#include <cstdlib>
+
 #include "fbq_internal.h"
 
 using namespace fbq;
@@ -261,6 +263,14 @@ extern "C" fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, co
                                       (uint32_t *)qweight_out, (uint16_t *)scales_out, (uint16_t *)zeros_out,
                                       (hipStream_t)stream));
 }
+
+namespace fbq {
+int spin_limit()
+{
+    const char *v = getenv("FBQ_SPIN_LIMIT");
+    return v && *v ? atoi(v) : kDefaultSpinLimit;
+}
+}  // namespace fbq
 
 extern "C" size_t fbq_train_workspace_bytes(const fbq_desc *d, int T)
 {

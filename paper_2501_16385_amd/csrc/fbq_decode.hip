@@ -190,6 +190,7 @@ struct LayerParams {
     int tslices;          // K slices of the down-projection (1..kMaxTSlices); consumers add the partial sums
     int producers;        // producer blocks in front of this layer's consumer blocks (0 when r == 0)
     int blocks;           // consumer blocks of this layer
+    int spin_limit;       // polls for t before a wave computes it itself; negative: at once (test hook)
 };
 
 struct GemvGroup {
@@ -198,7 +199,6 @@ struct GemvGroup {
 
 constexpr int kProdCols = 4;          // columns of A per producer block
 constexpr int kProdPasses = 4;        // passes of 2048 activations a producer block makes at most (all loads issued up front)
-constexpr int kSpinLimit = 1 << 15;   // polls (~0.3 us each) before a wave gives up and computes t itself
 constexpr int kCacheSc1 = 16 | (1 << 31);   // buffer-load policy: device scope (sc1), and volatile so that a poll is never hoisted or merged
 
 extern "C" __device__ unsigned long long fbq_llvm_dispatch_id(void) __asm("llvm.amdgcn.dispatch.id");
@@ -351,7 +351,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     const LayerParams p = g.layer[blockIdx.y];
     // (all of them before the first branch: left alone, the compiler fetches only what the branch needs first)
     asm volatile("" :: "s"(p.qw), "s"(p.scales), "s"(p.zeros), "s"(p.x), "s"(p.y), "s"(p.N), "s"(p.K), "s"(p.row_words), "s"(p.G));
-    if (RI > 0) asm volatile("" :: "s"(p.At), "s"(p.Bt), "s"(p.ttag), "s"(p.r), "s"(p.tslices));
+    if (RI > 0) asm volatile("" :: "s"(p.At), "s"(p.Bt), "s"(p.ttag), "s"(p.r), "s"(p.tslices), "s"(p.spin_limit));
     int bx = blockIdx.x;
     if (bx >= p.producers + p.blocks) return;
     uint32_t tag = 0;
@@ -465,8 +465,8 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     // yet, and passes it to the other waves through LDS.
     auto take_t = [&]() __attribute__((always_inline)) {
         if (wave == 0) {
-            bool ready = t_arrived();
-            for (int spin = 0; spin < kSpinLimit && !ready; ++spin) {
+            bool ready = p.spin_limit >= 0 && t_arrived();
+            for (int spin = 0; spin < p.spin_limit && !ready; ++spin) {
                 request_t();
                 ready = t_arrived();
                 if (!ready) __builtin_amdgcn_s_sleep(4);
@@ -720,6 +720,7 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
         p.row_words = (int)row_words(a.K, a.bits);
         p.G = a.K / kGroup;
         p.tslices = t_slices_of(a.K);
+        p.spin_limit = spin_limit();
         p.producers = ceil_div(a.r, kProdCols) * p.tslices;
         const int max_blocks = ceil_div(ceil_div(a.N, rows), row_sets);
         const int share = (int)(consumer_budget * ((double)a.N * a.K / total_work));

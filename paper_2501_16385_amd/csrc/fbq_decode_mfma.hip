@@ -92,6 +92,7 @@ struct SmallParams {
     int down_blocks;       // blocks at the start of this layer's grid row that do its down-projection, slice by slice ...
     int sum_blocks;        // ... and the blocks after them that add the slices up (16 columns each)
     int tiles_per_block;   // 16-row tiles a consumer block owns
+    int spin_limit;        // polls for t before a wave computes it itself; negative: at once (test hook)
 };
 
 // Layers that share their activations (q/k/v, gate/up) share the launch.  In the grid y is the layer
@@ -183,7 +184,6 @@ __device__ __forceinline__ half_t half_at(uint3_t w, int i)
 
 // ------------------------------------------------------------------ down-projection, inside the launch
 
-constexpr int kSpinLimit = 1 << 15;   // polls (~0.3 us each) before a wave gives up and computes its share of t itself
 constexpr int kCacheSc1 = 16 | (1 << 31);   // buffer-load policy: device scope (sc1), and volatile so that a poll is never hoisted or merged
 
 constexpr int kPrepWaves = 8;      // = kMainWaves: preparing blocks and consumers are blocks of the same launch
@@ -247,7 +247,7 @@ __device__ void sum_slices_block(const SmallParams &p, int b, uint32_t tag)
     const __amdgpu_buffer_rsrc_t pb = buffer_of(p.tpart, (long)p.slices * kTokens * p.r * 8);
     float t = 0.0f;
     bool ready = false;
-    for (int spin = 0; spin < kSpinLimit && !ready; ++spin) {
+    for (int spin = 0; spin < p.spin_limit && !ready; ++spin) {
         bool ok = true;
         t = 0.0f;
         for (int sl = 0; sl < p.slices; ++sl) {
@@ -341,7 +341,7 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
     const SmallParams p = g.layer[blockIdx.y];
     // (all of them before the first branch: left alone, the compiler fetches only what the branch needs first)
     asm volatile("" :: "s"(p.qw), "s"(p.scales), "s"(p.zeros), "s"(p.x), "s"(p.y), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.row_words), "s"(p.G), "s"(p.tiles_per_block));
-    if (BRANCH) asm volatile("" :: "s"(p.Bt), "s"(p.At), "s"(p.tpart), "s"(p.tsum), "s"(p.r), "s"(p.slices), "s"(p.kslice), "s"(p.down_blocks), "s"(p.sum_blocks));
+    if (BRANCH) asm volatile("" :: "s"(p.Bt), "s"(p.At), "s"(p.tpart), "s"(p.tsum), "s"(p.r), "s"(p.slices), "s"(p.kslice), "s"(p.down_blocks), "s"(p.sum_blocks), "s"(p.spin_limit));
     const uint32_t tag = BRANCH ? small_m_launch_tag() : 0u;
 
     // The first blocks of a grid row do the layer's down-projection.  They come first in dispatch
@@ -526,7 +526,7 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
             float t[8];
             bool ready = false;
             const int off = j < p.r ? (c * p.r + j) * 8 : kNowhere;
-            for (int spin = 0; spin < kSpinLimit && !ready; ++spin) {
+            for (int spin = 0; spin < p.spin_limit && !ready; ++spin) {
                 bool ok = true;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -692,6 +692,7 @@ hipError_t launch_gemv_small_m(const LinearArgs *layers, int n_layers, hipStream
         p.down_blocks = a.r > 0 ? ceil_div(a.r, 16) * p.slices : 0;
         p.sum_blocks = a.r > 0 ? ceil_div(a.r, 16) : 0;
         p.tiles_per_block = tpb;
+        p.spin_limit = spin_limit();
         row_blocks = std::max(row_blocks, p.down_blocks + p.sum_blocks + ceil_div(ceil_div(a.N, 16), tpb));
     }
     for (int i = n_layers; i < kMaxSmallGroup; ++i) g.layer[i] = g.layer[0];   // never indexed: grid.y stops at n_layers

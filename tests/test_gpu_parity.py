@@ -285,6 +285,23 @@ def test_replayed_graph_follows_new_activations(bits, M):
         assert np.array_equal(got, gpu_y(dev, x_np))                       # and equals an eager launch
 
 
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K,r,M", [(300, 1408, 24, 1), (300, 1408, 24, 2), (130, 2304, 40, 5), (96, 1408, 24, 16)])
+def test_fallback_when_the_down_projection_never_arrives(monkeypatch, bits, N, K, r, M):
+    """Consumers wait a bounded number of polls for the words that carry t and then compute their share
+    themselves.  FBQ_SPIN_LIMIT < 0 (read by the library at every launch) makes them do so at once:
+    every kernel still runs to its end, and the result must be the same."""
+    import torch
+    monkeypatch.setenv("FBQ_SPIN_LIMIT", "-1")
+    spec = spec_of(N, K, r, bits)
+    L = make_oracle_layer(spec, config=21)
+    dev = to_device_layer(L)
+    x = fbq_synth.make_x(spec, M, 21, 0)
+    got = gpu_y(dev, x)
+    torch.cuda.synchronize()
+    assert rel_l2(got, oracle_y(L, x)) <= Y_TOL
+
+
 # ------------------------------------------------------------------ prefill (fp16 MFMA GEMM, M > 16)
 
 PREFILL_CASES = [
