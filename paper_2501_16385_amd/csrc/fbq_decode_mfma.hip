@@ -238,6 +238,7 @@ __device__ void down_proj_block(const SmallParams &p, int b, uint32_t tag, float
 // Second step of the down-projection: block b adds up the K slices of columns 16 b .. 16 b + 15 for all
 // 16 token rows (one thread per sum) as soon as their words carry this launch's tag, and passes t on
 // in the same form.  Consumers then read one word per value, whatever the number of slices.
+constexpr int kSumSlices = 16;        // = the most K slices a layer can have
 __device__ void sum_slices_block(const SmallParams &p, int b, uint32_t tag)
 {
     const int tid = threadIdx.x;
@@ -250,11 +251,17 @@ __device__ void sum_slices_block(const SmallParams &p, int b, uint32_t tag)
     for (int spin = 0; spin < p.spin_limit && !ready; ++spin) {
         bool ok = true;
         t = 0.0f;
-        for (int sl = 0; sl < p.slices; ++sl) {
-            const uint2_t w = __builtin_amdgcn_raw_buffer_load_b64(pb, mine ? ((sl * kTokens + token) * p.r + j) * 8 : 0x7FFFFFF0, 0, kCacheSc1);
-            const uint32_t v = w.x;
-            t += __builtin_bit_cast(float, v);
-            ok = ok && (!mine || w.y == tag);
+        // all slices are asked for at once (one device-scope round trip per poll, not one per slice);
+        // slices the layer does not have aim past the buffer: zero, no access
+        uint2_t w[kSumSlices];
+#pragma unroll
+        for (int sl = 0; sl < kSumSlices; ++sl)
+            w[sl] = __builtin_amdgcn_raw_buffer_load_b64(pb, mine && sl < p.slices ? ((sl * kTokens + token) * p.r + j) * 8 : 0x7FFFFFF0, 0, kCacheSc1);
+#pragma unroll
+        for (int sl = 0; sl < kSumSlices; ++sl) {
+            const uint32_t v = w[sl].x;
+            t += __builtin_bit_cast(float, v);               // (zero for the slices that are not there)
+            ok = ok && (!mine || sl >= p.slices || w[sl].y == tag);
         }
         ready = __all(ok);
         if (!ready) __builtin_amdgcn_s_sleep(4);
@@ -626,6 +633,7 @@ static hipError_t launch_bits(const SmallGroup &g, int row_blocks, hipStream_t s
 // workspace: [16 slices][16][r] 8-byte words {fp32 partial sum of t, launch tag}, then [16][r] words {t, launch tag};
 // zero-filled once by the caller
 constexpr int kMaxSlices = 16;       // K slices of the down-projection
+static_assert(kMaxSlices == kSumSlices, "the summing blocks ask for every slice at once");
 size_t small_m_workspace_bytes(int K, int r) { (void)K; return (size_t)(kMaxSlices + 1) * kTokens * r * 8; }
 
 static int tiles_per_block_of(int total_tiles, int preparing_blocks, int bits)
