@@ -90,6 +90,16 @@ __device__ uint16_t double_to_half_bits(double d)
     return bits >= 0x7c00u ? (sign | 0x7c00u) : (sign | (uint16_t)bits);
 }
 
+// A double from the lane that the data-parallel control word names (quad permutations, row mirrors).
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v)
+{
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)u, CTRL, 0xF, 0xF, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)(uint32_t)(u >> 32), CTRL, 0xF, 0xF, true);
+    return __builtin_bit_cast(double, (uint64_t)lo | ((uint64_t)hi << 32));
+}
+
 // One block of 128 threads per group of 128 input features and kQuantRows consecutive rows: thread i
 // keeps column k = 128 g + i of At in registers (32 taps at a time) and walks over the rows with it,
 // so At is read once per 16 rows and Bt is converted once per block (LDS, broadcast reads).  fp64, the
@@ -144,11 +154,13 @@ __global__ __launch_bounds__(128) void fbq_quantize_kernel(const uint16_t *__res
     for (int row = 0; row < kQuantRows; ++row) {
         R[row] = row < rows ? half_bits_to_double(W[(size_t)(n0 + row) * K + k]) - sigma[row] : 0.0;
         double mn = R[row], mx = R[row];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            mn = fmin(mn, __shfl_xor(mn, off, 64));
-            mx = fmax(mx, __shfl_xor(mx, off, 64));
-        }
+        // within rows of 16 lanes by data-parallel moves (no LDS traffic), across the four rows by two shuffles
+        mn = fmin(mn, dpp_move<0xB1>(mn)); mx = fmax(mx, dpp_move<0xB1>(mx));       // neighbours
+        mn = fmin(mn, dpp_move<0x4E>(mn)); mx = fmax(mx, dpp_move<0x4E>(mx));       // pairs of a quad
+        mn = fmin(mn, dpp_move<0x141>(mn)); mx = fmax(mx, dpp_move<0x141>(mx));     // quads of a half row (mirror)
+        mn = fmin(mn, dpp_move<0x140>(mn)); mx = fmax(mx, dpp_move<0x140>(mx));     // halves of a row (mirror)
+        mn = fmin(mn, __shfl_xor(mn, 16, 64)); mx = fmax(mx, __shfl_xor(mx, 16, 64));
+        mn = fmin(mn, __shfl_xor(mn, 32, 64)); mx = fmax(mx, __shfl_xor(mx, 32, 64));
         if ((i & 63) == 0) {
             smin[i >> 6][row] = mn;
             smax[i >> 6][row] = mx;
