@@ -101,8 +101,9 @@ __device__ __forceinline__ double dpp_move(double v)
 }
 
 // One block of 128 threads per group of 128 input features and kQuantRows consecutive rows: thread i
-// keeps column k = 128 g + i of At in registers (32 taps at a time) and walks over the rows with it,
-// so At is read once per 16 rows and Bt is converted once per block (LDS, broadcast reads).  fp64, the
+// keeps column k = 128 g + i of At in registers (32 taps at a time, fetched by the block as a tile) and
+// walks over the rows with it, so At is read once per 16 rows and Bt is converted once per block (LDS,
+// broadcast reads).  fp64, the
 // taps in index order, no contraction left to the compiler; the one fused multiply-add is exact
 // by construction: the product of two fp16 values has 22 significant bits and is exact in fp64, so
 // fma(a, b, c) and (a * b) + c round the same number.
@@ -122,6 +123,7 @@ __global__ __launch_bounds__(128) void fbq_quantize_kernel(const uint16_t *__res
     __shared__ double smin[2][kQuantRows], smax[2][kQuantRows];
     __shared__ uint16_t sz[kQuantRows][2];
     __shared__ uint8_t scode[kQuantRows][128];
+    __shared__ __align__(16) uint16_t at_tile[kQuantTaps][kGroup];   // the block's tile of At
     __shared__ float bt[kQuantRows][kQuantTaps];      // the block's rows of Bt (fp16 values are exact in fp32; half the LDS bytes of fp64)
     const int g = blockIdx.x, n0 = blockIdx.y * kQuantRows, i = threadIdx.x;
     const int rows = min(kQuantRows, N - n0);
@@ -133,15 +135,24 @@ __global__ __launch_bounds__(128) void fbq_quantize_kernel(const uint16_t *__res
     for (int row = 0; row < kQuantRows; ++row) sigma[row] = 0.0;
     for (int j0 = 0; j0 < r; j0 += kQuantTaps) {
         // taps past r enter as zeros (adding 0 * b changes nothing); rows past N repeat the last row and are never stored
-        double at[kQuantTaps];
-#pragma unroll
-        for (int jj = 0; jj < kQuantTaps; ++jj) at[jj] = j0 + jj < r ? half_bits_to_double(At[(size_t)(j0 + jj) * K + k]) : 0.0;
+        // the 32 x 128 tile of At: 16-byte loads (four per thread) into LDS, from where a thread takes its column
+        // (32 two-byte global loads per thread cost the load path eight times the instructions)
         __syncthreads();
+#pragma unroll
+        for (int pc = 0; pc < kQuantTaps * kGroup / 8 / 128; ++pc) {
+            const int piece = pc * 128 + i, jj = piece / (kGroup / 8), k8 = piece % (kGroup / 8);
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (j0 + jj < r) v = *reinterpret_cast<const uint4 *>(At + (size_t)(j0 + jj) * K + g * kGroup + k8 * 8);
+            *reinterpret_cast<uint4 *>(&at_tile[jj][k8 * 8]) = v;
+        }
         for (int idx = i; idx < kQuantRows * kQuantTaps; idx += 128) {
             const int row = idx / kQuantTaps, jj = idx % kQuantTaps;
             bt[row][jj] = j0 + jj < r ? (float)__builtin_bit_cast(half_t, Bt[(size_t)min(n0 + row, N - 1) * r + j0 + jj]) : 0.0f;
         }
         __syncthreads();
+        double at[kQuantTaps];
+#pragma unroll
+        for (int jj = 0; jj < kQuantTaps; ++jj) at[jj] = half_bits_to_double(at_tile[jj][i]);   // zero past r
 #pragma unroll
         for (int row = 0; row < kQuantRows; ++row)
 #pragma unroll
