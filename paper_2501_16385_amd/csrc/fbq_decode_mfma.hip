@@ -213,7 +213,7 @@ __device__ void down_proj_block(const SmallParams &p, int b, uint32_t tag, float
         return __builtin_bit_cast(half8_t, w);
     };
     float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll 8
+#pragma unroll 4
     for (int k = kbeg; k < kend; k += 32)
         acc = mfma(to_matrix_order(*reinterpret_cast<const uint4 *>(xr + k)), to_matrix_order(*reinterpret_cast<const uint4 *>(ar + k)), acc);
     red[wave][lane] = acc;
