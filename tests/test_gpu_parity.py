@@ -59,6 +59,11 @@ DECODE_CASES = [
     (1290, 32768, 64, 16),
     (3500, 12288, 32, 7),
     (3500, 12288, 0, 9),
+    # many row tiles: three and four tiles per block in the matrix-core kernel, with and without a sub-branch
+    (11008, 256, 0, 5),
+    (16400, 128, 0, 4),
+    (16400, 128, 8, 4),
+    (11008, 256, 16, 16),
 ]
 
 
