@@ -245,6 +245,23 @@ def test_group_call_equals_single_calls(bits, M):
         assert rel_l2(y.cpu().numpy(), oracle_y(L, x_np)) <= Y_TOL
 
 
+@pytest.mark.parametrize("bits", [4, 3])
+def test_group_of_wide_layers_four_tiles_per_block(bits):
+    """Three 4096-row layers on the same activations: together they fill the GPU four tiles per block (alone:
+    two), and must still give bit for bit what single calls give."""
+    import torch
+    import paper_2501_16385_amd as fbq
+    Ls = [make_oracle_layer(spec_of(4096, 256, 16, bits), config=22, layer_index=i) for i in range(3)]
+    devs = [to_device_layer(L) for L in Ls]
+    x_np = fbq_synth.make_x(spec_of(8, 256, 0, bits), 7, 22, 0)
+    x = torch.from_numpy(x_np.view(np.int16)).cuda().view(torch.float16)
+    ys = fbq.linear_group(devs, [x, x, x])
+    torch.cuda.synchronize()
+    for L, dev, y in zip(Ls, devs, ys):
+        assert np.array_equal(y.cpu().numpy(), gpu_y(dev, x_np))
+        assert rel_l2(y.cpu().numpy(), oracle_y(L, x_np)) <= Y_TOL
+
+
 def test_group_rejects_a_bad_layer_before_launching_any():
     import torch
     import paper_2501_16385_amd as fbq
