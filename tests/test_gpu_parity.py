@@ -64,6 +64,8 @@ DECODE_CASES = [
     (16400, 128, 0, 4),
     (16400, 128, 8, 4),
     (11008, 256, 16, 16),
+    # widest sub-branch on the longest K: more down-projection blocks (16 slices x 16 column tiles + 16) than compute units
+    (64, 32768, 256, 16),
 ]
 
 
