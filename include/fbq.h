@@ -109,7 +109,8 @@ fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *sca
  * few producer blocks of the same launch).  3 <= M <= 16 streams the packed words once for all
  * tokens against a 16-token matrix-core tile, also in ONE launch whose first blocks do the
  * down-projection; 17 <= M <= 64 takes that launch 16 tokens at a time (the packed words are read
- * once per 16 tokens, which at these counts is still cheaper than unpacking them into fp16 tiles).  M > 64 runs the fp16 MFMA GEMM after a pass that
+ * once per 16 tokens, which at these counts is still cheaper than unpacking them into fp16 tiles; one or two
+ * tokens left over go through the GEMV).  M > 64 runs the fp16 MFMA GEMM after a pass that
  * re-orders x and a separate down-projection; a layer with too few output tiles to fill the GPU has
  * its K range split over up to 4 blocks per tile, summed in fp32 by a last small launch.
  *   x         device [M, K] fp16             qweight, scales, zeros, At, Bt: device, layout above

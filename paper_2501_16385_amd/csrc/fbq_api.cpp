@@ -172,7 +172,9 @@ static hipError_t launch_one(const LinearArgs &a, hipStream_t s)
             c.M = std::min(kDecodeMaxM, a.M - m0);
             c.x = a.x + (size_t)m0 * a.K;
             c.y = a.y + (size_t)m0 * a.N;
-            e = launch_gemv_small_m(&c, 1, s);         // the chunks reuse the workspace one after the other on the stream
+            // the chunks reuse the workspace one after the other on the stream (every launch marks its words with its own
+            // tag, whichever kernel wrote there before); one or two tokens left over go through the GEMV, which is cheaper
+            e = c.M <= kPerTokenMaxM ? launch_gemv_decode(&c, 1, s) : launch_gemv_small_m(&c, 1, s);
         }
         return e;
     }

@@ -280,11 +280,12 @@ def test_group_rejects_a_bad_layer_before_launching_any():
 
 
 @pytest.mark.parametrize("bits", [4, 3])
-@pytest.mark.parametrize("M", [1, 9, 20])
+@pytest.mark.parametrize("M", [1, 9, 18, 20])
 def test_replayed_graph_follows_new_activations(bits, M):
     """A captured launch replayed with new x must hand over the NEW down-projection: the words that carry
     t are marked with the identity of the launch that wrote them, and every replay is a new launch.
-    (One token: the GEMV; 9: the few-token kernel; 20: the same, 16 tokens at a time on one workspace.)"""
+    (One token: the GEMV; 9: the few-token kernel; 20: the same, 16 tokens at a time on one workspace; 18: 16 tokens,
+    then two through the GEMV on that same workspace.)"""
     import torch
     import paper_2501_16385_amd as fbq
     spec = spec_of(640, 4096, 64, bits)
@@ -334,6 +335,7 @@ PREFILL_CASES = [
     (512, 4096, 64, 256),
     (1000, 2048, 0, 130),
     (257, 128, 8, 17),
+    (300, 1408, 24, 34),              # 16 + 16 + 2: the last two tokens through the GEMV
     (768, 5120, 128, 300),
     (320, 2304, 256, 129),
 ]
