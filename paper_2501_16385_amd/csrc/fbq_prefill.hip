@@ -223,15 +223,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // weights, scale and zero of one super-step: two code blocks (k halves) per N tile
     struct StepRegs {
         WeightRegs<BITS> w[kTN][2];
-        uint32_t s[kTN], z[kTN];                        // fp16 bits
+        uint32_t s[kTN], z[kTN];                        // fp16 bits (with an even G: of super-steps u & ~1 and u | 1)
     };
-    auto step_load = [&](StepRegs &sr, int u) __attribute__((always_inline)) {
+    // Scale and zero are 2-byte loads of 32 different rows: as expensive for the load path as the 16-byte weight
+    // loads.  With an even number of groups per row the pair of an even and the following odd super-step is one
+    // aligned dword: fetched on the even step, handed on to the odd one.
+    const bool pairs = (p.G & 1) == 0;                  // block-uniform
+    auto step_load = [&](StepRegs &sr, int u, const StepRegs &before, bool has_before) __attribute__((always_inline)) {
 #pragma unroll
         for (int tn = 0; tn < kTN; ++tn) {
 #pragma unroll
             for (int c = 0; c < 2; ++c) sr.w[tn][c].load(wrow[tn], 4 * u + 2 * c + h);
-            sr.s[tn] = p.scales[(size_t)nrow[tn] * p.G + u];
-            sr.z[tn] = p.zeros[(size_t)nrow[tn] * p.G + u];
+            if (pairs) {
+                if ((u & 1) && has_before) {
+                    sr.s[tn] = before.s[tn];
+                    sr.z[tn] = before.z[tn];
+                } else {
+                    sr.s[tn] = *reinterpret_cast<const uint32_t *>(p.scales + (size_t)nrow[tn] * p.G + (u & ~1));
+                    sr.z[tn] = *reinterpret_cast<const uint32_t *>(p.zeros + (size_t)nrow[tn] * p.G + (u & ~1));
+                }
+            } else {
+                sr.s[tn] = p.scales[(size_t)nrow[tn] * p.G + u];
+                sr.z[tn] = p.zeros[(size_t)nrow[tn] * p.G + u];
+            }
         }
     };
 
@@ -241,7 +255,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // one super-step: eight K steps of 16 on the tile in lds[buf].  The activation fragments of K step
     // i + 1 are fetched from LDS before the matrix instructions of step i are issued.
     auto compute = [&](const StepRegs &sr, int buf) __attribute__((always_inline)) {
-        const typename WeightRegs<BITS>::Affine aff[kTN] = {{sr.s[0], sr.z[0]}, {sr.s[1], sr.z[1]}};
+        const int half_shift = pairs ? 16 * buf : 0;     // buf is the parity of the super-step
+        const typename WeightRegs<BITS>::Affine aff[kTN] = {{(sr.s[0] >> half_shift) & 0xFFFFu, (sr.z[0] >> half_shift) & 0xFFFFu},
+                                                            {(sr.s[1] >> half_shift) & 0xFFFFu, (sr.z[1] >> half_shift) & 0xFFFFu}};
         auto a_frag = [&](int tm, int step) __attribute__((always_inline)) {
             const uint32_t off = a_lane ^ (uint32_t)((8 * (step / 4) + (step % 4)) << 4);
             return *reinterpret_cast<const half8_t *>(&lds[buf][off + tm * (32 * kLdsRow)]);
@@ -300,7 +316,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     };
 
     StepRegs cur, nxt;
-    step_load(cur, min(u0, U_all - 1));
+    step_load(cur, min(u0, U_all - 1), cur, false);
     x_copy(min(u0, U_all - 1), u0 & 1);
     __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wave's LDS copies have landed
     __syncthreads();
@@ -308,7 +324,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int u = u0; u < U; ++u) {
         const bool more = u + 1 < U;                    // block-uniform
         if (more) {
-            step_load(nxt, u + 1);
+            step_load(nxt, u + 1, cur, true);
             x_copy(u + 1, (u + 1) & 1);
         }
         compute(cur, u & 1);
