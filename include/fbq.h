@@ -129,6 +129,25 @@ fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweig
                       const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
                       size_t workspace_bytes, fbq_stream stream);
 
+/*
+ * fbq_linear_static - fbq_linear for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc) and therefore cannot supply a
+ * workspace: the same kernels, with the hand-over scratch taken from a device array inside the
+ * library (544 KiB per GPU the library runs on, held until the process ends).  The call itself
+ * allocates nothing and frees nothing.
+ *   Arguments as for fbq_linear, without workspace and workspace_bytes.  M <= 16 only: larger token
+ *   counts need scratch that grows with M, N and K and are refused with FBQ_ERR_UNSUPPORTED;
+ *   FBQ_ERR_WORKSPACE if the layer's scratch would not fit the array (it always fits for r <= 256).
+ *   All calls on one GPU share that GPU's array, on whatever stream: calls that may overlap in time on
+ *   one GPU race on it and must be ordered by the caller.  Nothing needs clearing between calls (the
+ *   array starts zeroed and every launch marks what it writes with its own identity).
+ *   The first call on a device looks the array's address up (once per device); make that call outside
+ *   a graph capture.
+ * Errors: those of fbq_linear, before any launch; FBQ_ERR_HIP if the array cannot be found.
+ */
+fbq_status fbq_linear_static(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
+                             const void *zeros, const void *At, const void *Bt, void *y, fbq_stream stream);
+
 /* One layer of a grouped call: the arguments fbq_linear takes, per layer. */
 typedef struct {
     fbq_desc desc;

@@ -11,7 +11,8 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfbq.so")
-SOURCES = ["fbq_api.cpp", "fbq_decode.hip", "fbq_decode_mfma.hip", "fbq_prefill.hip", "fbq_util.hip", "fbq_train.hip"]
+SOURCES = ["fbq_api.cpp", "fbq_decode.hip", "fbq_decode_mfma.hip", "fbq_prefill.hip", "fbq_util.hip", "fbq_train.hip",
+           "fbq_static.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-I", INCLUDE, "-I", CSRC]
 

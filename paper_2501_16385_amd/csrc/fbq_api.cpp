@@ -115,14 +115,18 @@ extern "C" fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const ui
 
 static inline bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
 
-static fbq_status hip_status(hipError_t e)
+namespace fbq {
+fbq_status hip_status(hipError_t e)
 {
     if (e == hipSuccess) e = hipGetLastError();
     return e == hipSuccess ? FBQ_OK : FBQ_ERR_HIP;
 }
+}  // namespace fbq
+
+namespace fbq {
 
 // Validates one layer's arguments and fills the launch record; nothing is launched here.
-static fbq_status check_layer(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
+fbq_status check_layer(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
                               const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
                               size_t workspace_bytes, LinearArgs *a)
 {
@@ -161,7 +165,7 @@ static hipError_t launch_prefill(const LinearArgs &a, hipStream_t s)
 // 4..16 tokens: one pass over the packed words against a matrix-core tile of tokens.  17..64 tokens:
 // the same, 16 tokens at a time (the prefill GEMM has too few tiles to fill the GPU there: 103 us
 // against 4 x 11 us for a 4096 x 4096 layer at 64 tokens).  More: the prefill GEMM.
-static hipError_t launch_one(const LinearArgs &a, hipStream_t s)
+hipError_t launch_one(const LinearArgs &a, hipStream_t s)
 {
     if (a.M <= kPerTokenMaxM) return launch_gemv_decode(&a, 1, s);
     if (a.M <= kDecodeMaxM) return launch_gemv_small_m(&a, 1, s);
@@ -180,6 +184,8 @@ static hipError_t launch_one(const LinearArgs &a, hipStream_t s)
     }
     return launch_prefill(a, s);
 }
+
+}  // namespace fbq
 
 extern "C" fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
                                  const void *zeros, const void *At, const void *Bt, void *y, void *workspace,

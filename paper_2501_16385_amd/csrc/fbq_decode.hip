@@ -675,6 +675,7 @@ static hipError_t launch_bits(const GemvGroup &g, const Variant &v, int rows, di
 
 static int t_slices_of(int K) { return ceil_div(K, kProdPasses * 2048); }
 
+static_assert((size_t)kPerTokenMaxM * kMaxTSlices * kMaxRank * sizeof(uint64_t) <= kStaticScratchBytes, "the static scratch must hold the largest GEMV hand-over");
 size_t decode_workspace_bytes(int M, int K, int r) { return (size_t)M * t_slices_of(K) * r * sizeof(uint64_t); }
 
 // Layers may share a launch when they need the same kernel variant.  A branch-free layer never joins

@@ -634,6 +634,7 @@ static hipError_t launch_bits(const SmallGroup &g, int row_blocks, hipStream_t s
 // zero-filled once by the caller
 constexpr int kMaxSlices = 16;       // K slices of the down-projection
 static_assert(kMaxSlices == kSumSlices, "the summing blocks ask for every slice at once");
+static_assert((size_t)(kMaxSlices + 1) * kTokens * kMaxRank * 8 <= kStaticScratchBytes, "the static scratch must hold the largest few-token hand-over");
 size_t small_m_workspace_bytes(int K, int r) { (void)K; return (size_t)(kMaxSlices + 1) * kTokens * r * 8; }
 
 static int tiles_per_block_of(int total_tiles, int preparing_blocks, int bits)

@@ -79,6 +79,17 @@ hipError_t launch_gram(int K, int T, const uint16_t *X, float h_scale, uint16_t 
 hipError_t launch_train_step(const TrainArgs &a, hipStream_t stream);
 size_t train_workspace_bytes(int N, int K, int r, int T);
 
+// Shared by the entry points (fbq_api.cpp, fbq_static.hip): argument validation that fills the launch
+// record without launching, the dispatch on the token count, and the mapping of a HIP error to a status.
+fbq_status check_layer(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales, const void *zeros,
+                       const void *At, const void *Bt, void *y, void *workspace, size_t workspace_bytes, LinearArgs *a);
+hipError_t launch_one(const LinearArgs &a, hipStream_t s);
+fbq_status hip_status(hipError_t e);
+
+// Largest hand-over scratch any call of up to kDecodeMaxM tokens needs (r = kMaxRank): 16 K slices and their
+// sums, 16 token rows each, one 8-byte word per value.
+constexpr size_t kStaticScratchBytes = (size_t)(16 + 1) * 16 * kMaxRank * 8;
+
 size_t decode_workspace_bytes(int M, int K, int r);
 size_t small_m_workspace_bytes(int K, int r);
 size_t prefill_workspace_bytes(int M, int N, int K, int r);

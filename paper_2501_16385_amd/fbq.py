@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libfbq.so")
 _lib: Optional[ctypes.CDLL] = None
 
 EXPORTED_SYMBOLS = ["fbq_status_string", "fbq_check_desc", "fbq_packed_bytes", "fbq_workspace_bytes", "fbq_pack",
-                    "fbq_linear", "fbq_linear_group", "fbq_reconstruct", "fbq_unpack_codes", "fbq_quantize_feedback",
+                    "fbq_linear", "fbq_linear_static", "fbq_linear_group", "fbq_reconstruct", "fbq_unpack_codes", "fbq_quantize_feedback",
                     "fbq_train_workspace_bytes", "fbq_gram", "fbq_train_step"]
 
 
@@ -76,6 +76,8 @@ def load() -> ctypes.CDLL:
         lib.fbq_pack.argtypes = [dp] + [vp] * 10
         lib.fbq_linear.restype = i32
         lib.fbq_linear.argtypes = [dp, i32] + [vp] * 8 + [sz, vp]
+        lib.fbq_linear_static.restype = i32
+        lib.fbq_linear_static.argtypes = [dp, i32] + [vp] * 8
         lib.fbq_linear_group.restype = i32
         lib.fbq_linear_group.argtypes = [ctypes.POINTER(_CLayerCall), i32, i32, vp]
         lib.fbq_reconstruct.restype = i32
@@ -203,6 +205,20 @@ def linear(layer: DeviceLayer, x, y=None, workspace=None, stream=None):
                            _dev_ptr(layer.zeros), _dev_ptr(layer.At), _dev_ptr(layer.Bt), _dev_ptr(y), _dev_ptr(workspace),
                            wbytes, _stream(stream))
     _check(rc, "fbq_linear")
+    return y
+
+
+def linear_static(layer: DeviceLayer, x, y=None, stream=None):
+    """fbq_linear_static: fbq_linear for up to 16 tokens with the library's own scratch (nothing is allocated
+    by the call; pass y to keep this wrapper from allocating the output)."""
+    import torch
+    d = layer.desc
+    M = int(x.shape[0])
+    if y is None:
+        y = torch.empty((M, d.N), dtype=torch.float16, device=x.device)
+    rc = load().fbq_linear_static(ctypes.byref(d.c()), M, _dev_ptr(x), _dev_ptr(layer.qweight), _dev_ptr(layer.scales),
+                                  _dev_ptr(layer.zeros), _dev_ptr(layer.At), _dev_ptr(layer.Bt), _dev_ptr(y), _stream(stream))
+    _check(rc, "fbq_linear_static")
     return y
 
 

@@ -60,6 +60,10 @@ def test_linear_argument_errors_without_launch():
     assert call(1, ok, None, 1 << 20) == 1          # workspace needed but null
     assert call(1, ok, ok, 8) == 5                  # workspace too small
     assert lib.fbq_linear(None, 1, ok, ok, ok, ok, ok, ok, ok, ok, 1 << 20, None) == 1
+    # the entry point with the library's own scratch checks the same things, and its token limit, before it touches the GPU
+    static = lambda M, x: lib.fbq_linear_static(ctypes.byref(d.c()), M, x, ok, ok, ok, ok, ok, ok, None)
+    assert static(0, ok) == 2 and static(17, ok) == 3 and static(1, None) == 1 and static(1, odd) == 4
+    assert lib.fbq_linear_static(None, 1, ok, ok, ok, ok, ok, ok, ok, None) == 1
     assert lib.fbq_unpack_codes(ctypes.byref(d.c()), None, ok, None) == 1
     assert lib.fbq_reconstruct(ctypes.byref(d.c()), ok, ok, ok, None, ok, ok, None) == 1
     assert lib.fbq_quantize_feedback(ctypes.byref(d.c()), ok, ok, ok, odd, ok, ok, None) == 4
