@@ -76,13 +76,12 @@ fbq_status fbq_check_desc(const fbq_desc *d);
 size_t fbq_packed_bytes(const fbq_desc *d);
 
 /* Bytes of device scratch fbq_linear needs for M tokens.  M <= 2: the down-projection t = x.A on its
- * way from the blocks that compute it to the blocks that use it, as tagged 8-byte words (0 when
- * r == 0).  3 <= M <= 16: the same hand-over for 16 token rows, per K slice and summed (0 when
- * r == 0).  M > 64: the activations
+ * way from the blocks that compute it to the blocks that use it, as tagged 8-byte words, one per token,
+ * column of A and K slice (0 when r == 0).  3 <= M <= 64: the same hand-over for 16 token rows, per
+ * K slice and summed (0 when r == 0); the tokens are served 16 at a time.  M > 64: the activations
  * re-ordered for the matrix cores (M rounded up to 128 rows of K fp16), t as two fp16 halves and its
  * partial sums, and, where the launch splits K over blocks, fp32 partial outputs (up to 4 x M x N);
- * not 0 even when r == 0.  17 <= M <= 64: the larger of the two figures above.  0 for an invalid
- * descriptor or M < 1. */
+ * not 0 even when r == 0.  0 for an invalid descriptor or M < 1. */
 size_t fbq_workspace_bytes(const fbq_desc *d, int M);
 
 /*
@@ -105,8 +104,8 @@ fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *sca
  * fbq_linear - the hot path (Sec. 4.3).  y[m,n] = sum_k x[m,k] * s[n,k/g] * (q[n,k] - z[n,k/g])
  *                                               + sum_j (sum_k x[m,k] * At[j,k]) * Bt[n,j]
  * in fp32 accumulation, rounded once to fp16.  M <= 2 runs the decode GEMV in ONE launch per token
- * count (packed words streamed once per token, unpacked in registers; the down-projection runs in a
- * few producer blocks of the same launch).  3 <= M <= 16 streams the packed words once for all
+ * count (packed words streamed once per token, unpacked in registers; the down-projection runs in
+ * the same launch, one column of A per block as a small job in front of the block's first tile).  3 <= M <= 16 streams the packed words once for all
  * tokens against a 16-token matrix-core tile, also in ONE launch whose first blocks do the
  * down-projection; 17 <= M <= 64 takes that launch 16 tokens at a time (the packed words are read
  * once per 16 tokens, which at these counts is still cheaper than unpacking them into fp16 tiles; one or two
@@ -120,10 +119,9 @@ fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *sca
  *             and under graph replay: every launch marks what it writes with its own identity.
  *             Calls that may run concurrently must not share a workspace.
  * Errors: FBQ_ERR_NULL, _SHAPE, _UNSUPPORTED, _ALIGN, _WORKSPACE before any launch; FBQ_ERR_HIP.
- * Test hook: up to 16 tokens the blocks that use t wait a bounded number of polls (32768, about 10 ms)
- * for the blocks of the same launch that compute it, then compute their share themselves; the
- * environment variable FBQ_SPIN_LIMIT, read at every call, replaces that number, and a negative value
- * sends every block down the fall-back path at once (same results, slower; every kernel still ends).
+ * Up to 16 tokens the blocks that use t wait a bounded number of polls (32768, about 10 ms) for the
+ * blocks of the same launch that compute it, then compute their share themselves (same results, slower;
+ * every kernel still ends): see fbq_test_set_spin_limit.
  */
 fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
                       const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
@@ -148,6 +146,15 @@ fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweig
 fbq_status fbq_linear_static(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
                              const void *zeros, const void *At, const void *Bt, void *y, fbq_stream stream);
 
+/*
+ * fbq_test_set_spin_limit - test hook, not for production use.  Sets, for the whole process and every
+ * later launch, how many polls a block waits for the down-projection's hand-over words before it
+ * computes them itself: clamped to at most the default 32768; a negative value sends every block down
+ * that fall-back path at once, which is how the tests check a path no healthy run takes.  Returns the
+ * value that was in force.  Launches already enqueued keep the value they were launched with.
+ */
+int fbq_test_set_spin_limit(int polls);
+
 /* One layer of a grouped call: the arguments fbq_linear takes, per layer. */
 typedef struct {
     fbq_desc desc;
@@ -158,7 +165,7 @@ typedef struct {
     const void *At;         /* NULL if desc.r == 0 */
     const void *Bt;         /* NULL if desc.r == 0 */
     void *y;                /* device [M, N] fp16, overwritten */
-    void *workspace;        /* as for fbq_linear; one per layer */
+    void *workspace;        /* as for fbq_linear; one per layer, never shared or overlapping */
     size_t workspace_bytes;
 } fbq_layer_call;
 
@@ -173,7 +180,8 @@ typedef struct {
  * none) share one launch, up to 4 layers.  Anything else, and every layer when M > 16, is launched
  * on its own.
  *   calls host array of n layers (read during the call only); M tokens, the same for all layers
- * Errors: those of fbq_linear for any layer, reported before ANY launch.
+ * Errors: those of fbq_linear for any layer, and FBQ_ERR_WORKSPACE if the workspaces of two layers
+ * overlap, reported before ANY launch.
  */
 fbq_status fbq_linear_group(const fbq_layer_call *calls, int n, int M, fbq_stream stream);
 

@@ -3,7 +3,7 @@
 // (a one-off layout conversion that is off the hot path by definition).
 #include <string.h>
 
-#include <cstdlib>
+#include <atomic>
 
 #include "fbq_internal.h"
 
@@ -46,8 +46,9 @@ extern "C" size_t fbq_workspace_bytes(const fbq_desc *d, int M)
 {
     if (fbq_check_desc(d) != FBQ_OK || M < 1) return 0;
     if (M <= kPerTokenMaxM) return d->r == 0 ? 0 : decode_workspace_bytes(M, d->K, d->r);
-    if (M <= kDecodeMaxM) return small_m_workspace_bytes(d->K, d->r);   // holds the activations in operand order even when r == 0
-    if (M <= kChunkedMaxM) return std::max(small_m_workspace_bytes(d->K, d->r), prefill_workspace_bytes(M, d->N, d->K, d->r));
+    // up to 64 tokens go through the few-token kernel 16 at a time (one or two left over through the GEMV, whose
+    // hand-over words fit the same space); nothing to hand over without a sub-branch
+    if (M <= kChunkedMaxM) return small_m_workspace_bytes(d->K, d->r);
     return prefill_workspace_bytes(M, d->N, d->K, d->r);      // holds the re-ordered activations even when r == 0
 }
 
@@ -161,8 +162,8 @@ static hipError_t launch_prefill(const LinearArgs &a, hipStream_t s)
     return e;
 }
 
-// Up to three tokens: streaming GEMV, one pass per token, with the down-projection inside the launch.
-// 4..16 tokens: one pass over the packed words against a matrix-core tile of tokens.  17..64 tokens:
+// One or two tokens: streaming GEMV, one pass per token, with the down-projection inside the launch.
+// 3..16 tokens: one pass over the packed words against a matrix-core tile of tokens.  17..64 tokens:
 // the same, 16 tokens at a time (the prefill GEMM has too few tiles to fill the GPU there: 103 us
 // against 4 x 11 us for a 4096 x 4096 layer at 64 tokens).  More: the prefill GEMM.
 hipError_t launch_one(const LinearArgs &a, hipStream_t s)
@@ -209,6 +210,18 @@ extern "C" fbq_status fbq_linear_group(const fbq_layer_call *calls, int n, int M
         const fbq_status st = check_layer(&c.desc, M, c.x, c.qweight, c.scales, c.zeros, c.At, c.Bt, c.y, c.workspace,
                                           c.workspace_bytes, &args[i]);
         if (st != FBQ_OK) return st;
+    }
+    // Layers that share a launch carry the same launch tag: two of them writing their hand-over words into the same
+    // memory would accept each other's t.  Workspaces must not overlap.
+    for (int i = 0; i < n; ++i) {
+        const size_t ni = fbq_workspace_bytes(&calls[i].desc, M);
+        if (!ni) continue;
+        const uintptr_t ai = (uintptr_t)calls[i].workspace;
+        for (int j = i + 1; j < n; ++j) {
+            const size_t nj = fbq_workspace_bytes(&calls[j].desc, M);
+            const uintptr_t aj = (uintptr_t)calls[j].workspace;
+            if (nj && ai < aj + nj && aj < ai + ni) return FBQ_ERR_WORKSPACE;
+        }
     }
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
@@ -273,12 +286,15 @@ extern "C" fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, co
 }
 
 namespace fbq {
-int spin_limit()
-{
-    const char *v = getenv("FBQ_SPIN_LIMIT");
-    return v && *v ? atoi(v) : kDefaultSpinLimit;
-}
+static std::atomic<int> g_spin_limit{kDefaultSpinLimit};
+int spin_limit() { return g_spin_limit.load(std::memory_order_relaxed); }
 }  // namespace fbq
+
+extern "C" int fbq_test_set_spin_limit(int polls)
+{
+    const int clamped = polls < 0 ? -1 : std::min(polls, kDefaultSpinLimit);
+    return g_spin_limit.exchange(clamped, std::memory_order_relaxed);
+}
 
 extern "C" size_t fbq_train_workspace_bytes(const fbq_desc *d, int T)
 {

@@ -1,9 +1,9 @@
-// Decode path for one to three tokens: the fused kernel of Sec. 4.3 as a memory-streaming GEMV for gfx950.
+// Decode path for one or two tokens: the fused kernel of Sec. 4.3 as a memory-streaming GEMV for gfx950.
 //
-//   down-projection   t = x.A            a few producer blocks at the front of the SAME launch, each
-//                                        owning four columns of A over all of K (the paper keeps
-//                                        it a separate small kernel; on this GPU a launch costs as
-//                                        much as streaming a 4096^2 layer, so it rides along)
+//   down-projection   t = x.A            inside the SAME launch: each of the first r blocks takes one
+//                                        column of A as a small job before its first tile (the paper keeps it a separate small kernel;
+//                                        on this GPU a launch costs as much as streaming a 4096^2
+//                                        layer, so it rides along, and it holds no block slot)
 //   fused kernel      y = x.Wq^T + t.B   one pass over the packed codes; de-quantization, main
 //                                        projection and up-projection share one fp32 accumulator
 //                                        and y is written once.  t is needed only for the second
@@ -85,10 +85,10 @@ struct XFrag {
     half2_t p[16];
     float sum;
 
-    // raw: 32 consecutive fp16 activations as loaded; valid == false gives an all-zero fragment
-    __device__ __forceinline__ void arrange(const uint4 (&raw)[4], bool valid)
+    // 32 consecutive fp16 values as loaded -> the 16 pairs in extraction order (also used for a column of A,
+    // so that its dot product with the activations can run on the pairs the wave already holds)
+    static __device__ __forceinline__ void pairs(const uint4 (&raw)[4], bool valid, half2_t (&p)[16], half_t (&v)[32])
     {
-        half_t v[32];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
@@ -99,10 +99,6 @@ struct XFrag {
                 v[i * 8 + j * 2 + 1] = h.y;
             }
         }
-        float s = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 32; ++i) s += (float)v[i];
-        sum = s;
         if (BITS == 4) {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -115,6 +111,17 @@ struct XFrag {
                 for (int f = 0; f < 5; ++f) p[w * 5 + f] = half2_t{v[10 * w + f], v[10 * w + f + 5]};
             p[15] = half2_t{v[30], v[31]};
         }
+    }
+
+    // raw: 32 consecutive fp16 activations as loaded; valid == false gives an all-zero fragment
+    __device__ __forceinline__ void arrange(const uint4 (&raw)[4], bool valid)
+    {
+        half_t v[32];
+        pairs(raw, valid, p, v);
+        float s = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) s += (float)v[i];
+        sum = s;
     }
 };
 
@@ -187,9 +194,8 @@ struct LayerParams {
     int N, K, r;
     int row_words;        // words per packed row
     int G;                // groups per row
-    int tslices;          // K slices of the down-projection (1..kMaxTSlices); consumers add the partial sums
-    int producers;        // producer blocks in front of this layer's consumer blocks (0 when r == 0)
-    int blocks;           // consumer blocks of this layer
+    int tslices;          // K slices of the down-projection = waves of a block that split K (1, 2 or 4); consumers add the partial sums
+    int blocks;           // blocks of this layer
     int spin_limit;       // polls for t before a wave computes it itself; negative: at once (test hook)
 };
 
@@ -197,8 +203,6 @@ struct GemvGroup {
     LayerParams layer[kMaxGroup];
 };
 
-constexpr int kProdCols = 4;          // columns of A per producer block
-constexpr int kProdPasses = 4;        // passes of 2048 activations a producer block makes at most (all loads issued up front)
 constexpr int kCacheSc1 = 16 | (1 << 31);   // buffer-load policy: device scope (sc1), and volatile so that a poll is never hoisted or merged
 
 extern "C" __device__ unsigned long long fbq_llvm_dispatch_id(void) __asm("llvm.amdgcn.dispatch.id");
@@ -215,61 +219,6 @@ __device__ __forceinline__ uint32_t launch_tag()
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t dev_buffer(const void *p, int bytes)
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
-}
-
-// Producer block b of token m: partial sums of t[j] for kProdCols columns over one K slice of at most
-// kProdPasses * 2048 activations, lanes along K like the main kernel; every load is issued up front.
-__device__ void produce_t(const LayerParams &p, int m, int b, uint32_t tag, float *lds)
-{
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint16_t *xrow = p.x + (size_t)m * p.K;
-    const int col_blocks = (p.r + kProdCols - 1) / kProdCols;
-    const int slice = b / col_blocks;
-    const int j0 = (b - slice * col_blocks) * kProdCols;
-    const int kbeg = slice * (kProdPasses * 2048);
-    const int kend = min(p.K, kbeg + kProdPasses * 2048);
-
-    uint4 xv[kProdPasses], av[kProdPasses][kProdCols];
-    bool valid[kProdPasses];
-#pragma unroll
-    for (int i = 0; i < kProdPasses; ++i) {
-        const int k0 = kbeg + (i * 256 + tid) * 8;
-        valid[i] = k0 < kend;
-        const int kk = valid[i] ? k0 : kbeg;            // clamped: loaded, then ignored
-        xv[i] = *reinterpret_cast<const uint4 *>(xrow + kk);
-#pragma unroll
-        for (int c = 0; c < kProdCols; ++c) {
-            const int j = min(j0 + c, p.r - 1);         // r is a multiple of 8: never clamps
-            av[i][c] = *reinterpret_cast<const uint4 *>(p.At + (size_t)j * p.K + kk);
-        }
-    }
-    float acc[kProdCols];
-#pragma unroll
-    for (int c = 0; c < kProdCols; ++c) acc[c] = 0.0f;
-#pragma unroll
-    for (int i = 0; i < kProdPasses; ++i) {
-        const uint32_t x0 = valid[i] ? xv[i].x : 0u, x1 = valid[i] ? xv[i].y : 0u, x2 = valid[i] ? xv[i].z : 0u,
-                       x3 = valid[i] ? xv[i].w : 0u;
-#pragma unroll
-        for (int c = 0; c < kProdCols; ++c) {
-            acc[c] = dot2(av[i][c].x, as_h2(x0), acc[c]);
-            acc[c] = dot2(av[i][c].y, as_h2(x1), acc[c]);
-            acc[c] = dot2(av[i][c].z, as_h2(x2), acc[c]);
-            acc[c] = dot2(av[i][c].w, as_h2(x3), acc[c]);
-        }
-    }
-#pragma unroll
-    for (int c = 0; c < kProdCols; ++c) {
-        const float s = wave_sum(acc[c]);
-        if (lane == 0) lds[wave * kProdCols + c] = s;
-    }
-    __syncthreads();
-    if (tid < kProdCols && j0 + tid < p.r) {
-        const float s = (lds[tid] + lds[kProdCols + tid]) + (lds[2 * kProdCols + tid] + lds[3 * kProdCols + tid]);
-        const uint64_t word = (uint64_t)__builtin_bit_cast(uint32_t, s) | ((uint64_t)tag << 32);
-        __hip_atomic_store(p.ttag + ((size_t)m * p.tslices + slice) * p.r + j0 + tid, word, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
-    }
 }
 
 // Everything one wave loads for one tile of ROWS rows.  All loads are buffer loads: the row base is a
@@ -338,32 +287,23 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     constexpr int kRowSets = kWaves / KS;               // row sets per block
     constexpr int kRI = RI > 0 ? RI : 1;
     constexpr int kXChunks = CPW * KS;                  // chunks of 2048 activations the block covers
-    __shared__ float red[kWaves * (ROWS > kProdCols ? ROWS : kProdCols)];   // K-split sums, or the producer's wave sums
-    __shared__ float t_lds[RI > 0 ? RI * 128 : 1];                          // t as wave 0 received it
+    __shared__ float red[kWaves * ROWS];                                    // K-split sums
     __shared__ uint4 x_lds[kXChunks * 256];                                 // the token's activations, 16-byte pieces swizzled
 
-    // Grid: x = block of a layer (producers first, then consumers), y = layer of the group, z = token.
+    // Grid: x = layer of the group, y = block of the layer, z = token: blocks are dispatched x first, so the first
+    // blocks of every layer - the ones with a share of the down-projection - start before anybody's later blocks.
     // The layer comes from the block index, not from a table in the kernel arguments: its parameters
     // are then fetched in one go with everything else (a second, dependent round trip to the kernel
     // arguments costs more than half a microsecond here).  Layers with fewer blocks than the widest
     // one of the group leave the surplus blocks at once.
     const int m = blockIdx.z;
-    const LayerParams p = g.layer[blockIdx.y];
+    const LayerParams p = g.layer[blockIdx.x];
     // (all of them before the first branch: left alone, the compiler fetches only what the branch needs first)
     asm volatile("" :: "s"(p.qw), "s"(p.scales), "s"(p.zeros), "s"(p.x), "s"(p.y), "s"(p.N), "s"(p.K), "s"(p.row_words), "s"(p.G));
     if (RI > 0) asm volatile("" :: "s"(p.At), "s"(p.Bt), "s"(p.ttag), "s"(p.r), "s"(p.tslices), "s"(p.spin_limit));
-    int bx = blockIdx.x;
-    if (bx >= p.producers + p.blocks) return;
-    uint32_t tag = 0;
-    if (RI > 0) {
-        tag = launch_tag();
-        if (bx < p.producers) {                         // block-uniform: producer blocks only produce
-            __builtin_amdgcn_s_setprio(3);              // every consumer waits for them
-            produce_t(p, m, bx, tag, red);
-            return;
-        }
-        bx -= p.producers;
-    }
+    const int bx = blockIdx.y;
+    if (bx >= p.blocks) return;
+    const uint32_t tag = RI > 0 ? launch_tag() : 0u;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -372,7 +312,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     const int rs = wave / KS;                           // which row set of the block
     const int ntiles = (p.N + ROWS - 1) / ROWS;
     const int tstride = p.blocks * kRowSets;
-    const int trips = (ntiles - bx * kRowSets + tstride - 1) / tstride;   // block-uniform (>= 1 by construction)
+    const int trips = (ntiles - bx * kRowSets + tstride - 1) / tstride;   // block-uniform; < 1 only in blocks launched for their share of the down-projection alone
     int tile = bx * kRowSets + rs;
 
     // The token's activations: the block fetches them once (each thread 16 bytes per chunk) ...
@@ -384,14 +324,15 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
         xin[i] = k < p.K ? *reinterpret_cast<const uint4 *>(xrow + k) : make_uint4(0u, 0u, 0u, 0u);
     }
 
-    // ... and right behind them the first two tiles go out, before anything waits.
-    int qoff[CPW], goff[CPW];
+    // ... and right behind them the first tile goes out, before anything waits.
+    int qoff[CPW], goff[CPW], koff[CPW];
     bool kv[CPW];
 #pragma unroll
     for (int c = 0; c < CPW; ++c) {
         const int k0 = ((ks * CPW + c) * 64 + lane) * kLaneCodes;
         kv[c] = k0 < p.K;
         const int kc = kv[c] ? k0 : 0;
+        koff[c] = kc * 2;                               // the same position in a row of fp16 values (a column of A)
         qoff[c] = (kc / kLaneCodes) * RowTile<BITS, CPW, ROWS>::kLaneWords * 4;
         goff[c] = (kc / kGroup) * 2;
     }
@@ -402,6 +343,26 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
         const int j = (q * 64 + lane) * 2;
         jv[q] = RI > 0 && j < p.r;
         joff[q] = jv[q] ? j * 2 : 0;
+    }
+    // Down-projection.  Column j of A is a job for block j of the layer: the waves of its first row set take it,
+    // each over its own K range.  So the first r blocks of a layer - the first in dispatch order - do all of it, a
+    // sliver each, and nobody holds a block slot for it.  (A compute unit fetches at its share of the memory
+    // system's pace, about 20 KB per microsecond when the whole GPU streams: four columns of a 4096-wide A on one
+    // compute unit would keep t back by more than a microsecond, one column does not.)  The column's words are
+    // asked for BEFORE the first tile: loads come back in the order they were made, and every other block waits
+    // for t.
+    const int jcol = bx;
+    const bool has_job = RI > 0 && rs == 0 && jcol < p.r;   // wave-uniform
+    uint4 acol[CPW][4];
+    if (has_job) {
+        const __amdgpu_buffer_rsrc_t abuf = dev_buffer(p.At, p.r * p.K * 2);
+#pragma unroll
+        for (int c = 0; c < CPW; ++c)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(abuf, koff[c] + i * 16, jcol * p.K * 2, 0);
+                acol[c][i] = make_uint4(v.x, v.y, v.z, v.w);
+            }
     }
     RowTile<BITS, CPW, ROWS> cur, nxt;                  // even and odd trips
     uint32_t bt0[ROWS][kRI], bt1[ROWS][kRI];            // their rows of Bt
@@ -428,6 +389,31 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
         }
         xf[c].arrange(raw, kv[c]);
     }
+    // The job: t[jcol] over this wave's K range, on the pairs the wave holds anyway (lanes past K hold zeros),
+    // summed over the wave in a fixed order and handed over as one tagged word.
+    const int tslices = RI > 0 ? p.tslices : 1;
+    auto t_partial = [&](const uint4 (&col)[CPW][4]) __attribute__((always_inline)) {
+        float tj = 0.0f;
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) {
+            half2_t ap[16];
+            half_t unused[32];
+            XFrag<BITS>::pairs(col[c], true, ap, unused);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) tj = __builtin_amdgcn_fdot2(ap[q], xf[c].p[q], tj, false);
+        }
+        return wave_sum(tj);
+    };
+    auto hand_over = [&](int j, float tj) __attribute__((always_inline)) {
+        if (lane == 0) {
+            const uint64_t word = (uint64_t)__builtin_bit_cast(uint32_t, tj) | ((uint64_t)tag << 32);
+            __hip_atomic_store(p.ttag + ((size_t)m * tslices + ks) * p.r + j, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+    if (RI > 0) {
+        if (has_job) hand_over(jcol, t_partial(acol));
+        if (trips <= 0) return;                         // a block that exists for its job only (a layer with a handful of rows)
+    }
     // The second tile goes out only now: the memory pipeline serves a compute unit's requests in the
     // order they were made, and the first tiles of all its waves should come before any second tile.
 #pragma unroll
@@ -438,7 +424,6 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
 
     // t: a lane needs t[j], t[j+1]: one 16-byte device-scope load {value, tag, value, tag}.  With several
     // K slices there is one such word pair per slice, and the lane adds the partial sums.
-    const int tslices = RI > 0 ? p.tslices : 1;
     const __amdgpu_buffer_rsrc_t tbuf = dev_buffer(p.ttag + (size_t)m * tslices * p.r, (RI > 0 ? tslices * p.r : 1) * 8);
     uint4_t tw[kRI][kMaxTSlices];
     float t0[kRI], t1[kRI];
@@ -461,14 +446,23 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
         return (bool)__all(ok);
     };
 
-    // Block-uniform.  Wave 0 takes t (requested one tile earlier, see below), waiting if it is not there
-    // yet, and passes it to the other waves through LDS.
+    // Every wave that applies the up-projection (the K-slice-0 wave of each row set) takes t for itself - asked for
+    // one tile earlier, see below - and waits if it is not there yet: no barrier, so a wave whose tiles come early
+    // is not held back to the pace of the slowest wave of its block.
+    const bool needs_t = RI > 0 && ks == 0;             // wave-uniform
     auto take_t = [&]() __attribute__((always_inline)) {
-        if (wave == 0) {
+        if (needs_t) {
             bool ready = p.spin_limit >= 0 && t_arrived();
+            // Not there yet: every wave of the launch would now ask for the same few hundred bytes over and over, and
+            // the one memory channel that holds them also serves its share of everybody's weights.  So a poll asks
+            // for a single word - the one stored by the last wave in dispatch order that has a job - and only when
+            // that has come is all of t asked for again.
             for (int spin = 0; spin < p.spin_limit && !ready; ++spin) {
-                request_t();
-                ready = t_arrived();
+                const uint32_t probe_tag = __builtin_amdgcn_raw_buffer_load_b32(tbuf, 0, (tslices * p.r - 1) * 8 + 4, kCacheSc1);
+                if (probe_tag == tag) {
+                    request_t();
+                    ready = t_arrived();
+                }
                 if (!ready) __builtin_amdgcn_s_sleep(4);
             }
 #pragma unroll
@@ -483,7 +477,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
                             u1 += __builtin_bit_cast(float, v1);
                         }
                     }
-                } else {                            // producers never showed up in time: do it here
+                } else {                            // the words never showed up in time: do it here
                     const uint16_t *a0 = p.At + (size_t)(joff[q] / 2) * p.K, *a1 = a0 + p.K;
                     for (int k = 0; k < p.K; ++k) {
                         const float xv = (float)__builtin_bit_cast(half_t, xrow[k]);
@@ -491,15 +485,9 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
                         u1 = fmaf(xv, (float)__builtin_bit_cast(half_t, a1[k]), u1);
                     }
                 }
-                t_lds[(q * 64 + lane) * 2] = jv[q] ? u0 : 0.0f;
-                t_lds[(q * 64 + lane) * 2 + 1] = jv[q] ? u1 : 0.0f;
+                t0[q] = jv[q] ? u0 : 0.0f;
+                t1[q] = jv[q] ? u1 : 0.0f;
             }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < RI; ++q) {
-            t0[q] = t_lds[(q * 64 + lane) * 2];
-            t1[q] = t_lds[(q * 64 + lane) * 2 + 1];
         }
         have_t = true;
     };
@@ -542,7 +530,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     // One trip.  The tile's registers are refilled (with the tile two trips ahead, or with nothing) as
     // soon as the arithmetic has consumed them.  With a sub-branch the second half of a tile is
     // postponed by one trip: t is requested when the next tile's arithmetic starts and taken when it
-    // ends, so waiting for the producers hides behind a whole tile of the weight stream (a wave with a
+    // ends, so waiting for the down-projection hides behind a whole tile of the weight stream (a wave with a
     // single trip has nothing to hide behind and waits at once).  Even trips use (cur, bt0, acc0), odd
     // trips (nxt, bt1, acc1): the rows of Bt for trip j + 1 are fetched in trip j, when the previous
     // owner of that buffer, trip j - 1, has been finished.
@@ -554,7 +542,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
         for (int i = 0; i < ROWS; ++i) {
             // t is asked for as late as possible - when the tile's first row has arrived and its arithmetic
             // is about to start - so that the answer is still fresh when the tile is done
-            if (i == 1 && RI > 0 && wave == 0 && !have_t && (j > 0 || trips == 1)) {
+            if (i == 1 && needs_t && !have_t && (j > 0 || trips == 1)) {
                 asm volatile("" : "+v"(acc[0]));
                 __builtin_amdgcn_sched_barrier(0);
                 request_t();
@@ -673,10 +661,9 @@ static hipError_t launch_bits(const GemvGroup &g, const Variant &v, int rows, di
     return hipErrorInvalidValue;   // K > 32768: rejected by the caller's shape check
 }
 
-static int t_slices_of(int K) { return ceil_div(K, kProdPasses * 2048); }
-
 static_assert((size_t)kPerTokenMaxM * kMaxTSlices * kMaxRank * sizeof(uint64_t) <= kStaticScratchBytes, "the static scratch must hold the largest GEMV hand-over");
-size_t decode_workspace_bytes(int M, int K, int r) { return (size_t)M * t_slices_of(K) * r * sizeof(uint64_t); }
+// One tagged word per token, K slice (= wave of a block along K) and column of A.
+size_t decode_workspace_bytes(int M, int K, int r) { return (size_t)M * variant_of(K, 4, r).ks * r * sizeof(uint64_t); }
 
 // Layers may share a launch when they need the same kernel variant.  A branch-free layer never joins
 // layers with a sub-branch: the fused kernel reads Bt unconditionally, and a branch-free layer has none.
@@ -698,17 +685,17 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
     }
     const int row_sets = 4 / v.ks;
     // Blocks to share out: two per CU keeps enough bytes in flight; a token dimension multiplies the grid.
-    const int budget = std::max(1, 2 * device_cu_count() / std::max(1, std::min(M, 2)));
+    int budget = std::max(1, 2 * device_cu_count() / std::max(1, std::min(M, 2)));
     // Tiles of 4 rows when that still leaves every wave at least one tile, and registers allow; else 2.
-    long tiles4 = 0;
+    long tiles4 = 0, tiles = 0;
     for (int i = 0; i < n_layers; ++i) tiles4 += ceil_div(layers[i].N, 4);
     const int rows = (v.cpw == 1 && tiles4 >= (long)budget * row_sets) ? 4 : 2;
-
-    // Persistent consumer blocks have fixed tile lists, so every one of them must be resident from the
-    // start: the producers take their block slots out of the same budget.
-    int producers_total = 0;
-    for (int i = 0; i < n_layers; ++i) producers_total += ceil_div(layers[i].r, kProdCols) * t_slices_of(layers[i].K);
-    const int consumer_budget = std::max(budget / 2, budget - producers_total);
+    // A launch in which no wave would get a second tile (one 4096 x 4096 layer) runs one block per CU instead, two
+    // tiles per wave: half as many blocks fetch and arrange the activations, and the wait for t - which a wave
+    // with a single tile has nothing to hide behind - disappears behind the second tile (5.0 -> 4.7 us with a
+    // sub-branch, 4.1 -> 3.7 us without).
+    for (int i = 0; i < n_layers; ++i) tiles += ceil_div(layers[i].N, rows);
+    if (tiles <= (long)budget * row_sets && tiles > (long)budget * row_sets / 2) budget = std::max(1, budget / 2);
 
     GemvGroup g;
     int widest = 0;
@@ -720,16 +707,16 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
         p.N = a.N; p.K = a.K; p.r = a.r;
         p.row_words = (int)row_words(a.K, a.bits);
         p.G = a.K / kGroup;
-        p.tslices = t_slices_of(a.K);
+        p.tslices = v.ks;
         p.spin_limit = spin_limit();
-        p.producers = ceil_div(a.r, kProdCols) * p.tslices;
         const int max_blocks = ceil_div(ceil_div(a.N, rows), row_sets);
-        const int share = (int)(consumer_budget * ((double)a.N * a.K / total_work));
-        p.blocks = std::max(1, std::min(max_blocks, share));
-        widest = std::max(widest, p.producers + p.blocks);
+        const int share = (int)(budget * ((double)a.N * a.K / total_work));
+        // every column of A needs a block: a layer with fewer row tiles than that gets blocks that only do their job
+        p.blocks = std::max({1, std::min(max_blocks, share), a.r});
+        widest = std::max(widest, p.blocks);
     }
-    for (int i = n_layers; i < kMaxGroup; ++i) g.layer[i] = g.layer[0];   // never indexed: grid.y stops at n_layers
-    const dim3 grid(widest, n_layers, M);
+    for (int i = n_layers; i < kMaxGroup; ++i) g.layer[i] = g.layer[0];   // never indexed: grid.x stops at n_layers
+    const dim3 grid(n_layers, widest, M);
     return v.bits == 4 ? launch_bits<4>(g, v, rows, grid, stream) : launch_bits<3>(g, v, rows, grid, stream);
 }
 

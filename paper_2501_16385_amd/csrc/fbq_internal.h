@@ -25,10 +25,10 @@ constexpr int kMaxSmallGroup = 4;    // ... for 4..16 tokens
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// How often a consumer polls for the down-projection's words before it computes them itself.  The
-// environment variable FBQ_SPIN_LIMIT is a test hook: a negative value makes every consumer take the
-// fall-back path at once (every kernel still runs to its end), so the path that a healthy run never
-// takes can be checked against the oracle.
+// How often a consumer polls for the down-projection's words before it computes them itself.  The value
+// in force is process-wide and only the test hook fbq_test_set_spin_limit changes it: a negative value
+// makes every consumer take the fall-back path at once (every kernel still runs to its end), so the
+// path that a healthy run never takes can be checked against the oracle.
 constexpr int kDefaultSpinLimit = 1 << 15;   // polls of about 0.3 us each
 int spin_limit();
 

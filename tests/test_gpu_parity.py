@@ -66,6 +66,11 @@ DECODE_CASES = [
     (11008, 256, 16, 16),
     # widest sub-branch on the longest K: more down-projection blocks (16 slices x 16 column tiles + 16) than compute units
     (64, 32768, 256, 16),
+    # one or two tokens, fewer blocks than columns of A: every wave's down-projection job plus the columns left over
+    (2, 128, 64, 1),
+    (8, 256, 256, 2),
+    (40, 20480, 96, 2),
+    (24, 32768, 256, 1),
 ]
 
 
@@ -312,18 +317,22 @@ def test_replayed_graph_follows_new_activations(bits, M):
 
 @pytest.mark.parametrize("bits", [4, 3])
 @pytest.mark.parametrize("N,K,r,M", [(300, 1408, 24, 1), (300, 1408, 24, 2), (130, 2304, 40, 5), (96, 1408, 24, 16)])
-def test_fallback_when_the_down_projection_never_arrives(monkeypatch, bits, N, K, r, M):
+def test_fallback_when_the_down_projection_never_arrives(bits, N, K, r, M):
     """Consumers wait a bounded number of polls for the words that carry t and then compute their share
-    themselves.  FBQ_SPIN_LIMIT < 0 (read by the library at every launch) makes them do so at once:
-    every kernel still runs to its end, and the result must be the same."""
+    themselves.  The test hook fbq_test_set_spin_limit(-1) makes them do so at once: every kernel still
+    runs to its end, and the result must be the same."""
     import torch
-    monkeypatch.setenv("FBQ_SPIN_LIMIT", "-1")
+    import paper_2501_16385_amd as fbq
     spec = spec_of(N, K, r, bits)
     L = make_oracle_layer(spec, config=21)
     dev = to_device_layer(L)
     x = fbq_synth.make_x(spec, M, 21, 0)
-    got = gpu_y(dev, x)
-    torch.cuda.synchronize()
+    before = fbq.load().fbq_test_set_spin_limit(-1)
+    try:
+        got = gpu_y(dev, x)
+        torch.cuda.synchronize()
+    finally:
+        assert fbq.load().fbq_test_set_spin_limit(before) == -1
     assert rel_l2(got, oracle_y(L, x)) <= Y_TOL
 
 

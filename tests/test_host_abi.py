@@ -29,6 +29,7 @@ def test_sizes_and_status_strings():
     assert fbq.workspace_bytes(d, 1) > 0 and fbq.workspace_bytes(fbq.Desc(4096, 4096, 0, 4), 1) == 0
     assert fbq.workspace_bytes(d, 16) >= 16 * 64 * 4
     assert fbq.workspace_bytes(fbq.Desc(4096, 4096, 0, 4), 100) >= 128 * 4096 * 2   # prefill keeps a copy of x
+    assert fbq.workspace_bytes(d, 40) == fbq.workspace_bytes(d, 9)                    # 17..64 tokens: the few-token kernel, 16 at a time
     assert fbq.workspace_bytes(d, 9) >= 4 * 16 * d.r * 8                               # tagged partial sums of t, one set per K slice
     assert fbq.workspace_bytes(fbq.Desc(4096, 4096, 0, 4), 9) == 0                      # nothing to hand over without a sub-branch
     assert fbq.workspace_bytes(d, 2) == 2 * fbq.workspace_bytes(d, 1)        # one set of tagged words per token
@@ -67,6 +68,25 @@ def test_linear_argument_errors_without_launch():
     assert lib.fbq_unpack_codes(ctypes.byref(d.c()), None, ok, None) == 1
     assert lib.fbq_reconstruct(ctypes.byref(d.c()), ok, ok, ok, None, ok, ok, None) == 1
     assert lib.fbq_quantize_feedback(ctypes.byref(d.c()), ok, ok, ok, odd, ok, ok, None) == 4
+
+
+def test_group_rejects_overlapping_workspaces_and_the_test_hook_clamps():
+    lib = fbq.load()
+    d = fbq.Desc(16, 256, 8, 4)
+    need = fbq.workspace_bytes(d, 1)
+    assert need > 0
+    ok = 0x10000
+    layer = lambda ws: fbq.fbq._CLayerCall(d.c(), ok, ok, ok, ok, ok, ok, ok, ws, need)
+    arr = (fbq.fbq._CLayerCall * 2)(layer(0x20000), layer(0x20000 + need - 16))
+    assert lib.fbq_linear_group(arr, 2, 1, None) == 5            # the second workspace starts inside the first
+    arr = (fbq.fbq._CLayerCall * 2)(layer(0x20000), layer(0x20000))
+    assert lib.fbq_linear_group(arr, 2, 1, None) == 5
+    # the poll limit: clamped to the default from above, any negative value means "fall back at once"
+    default = lib.fbq_test_set_spin_limit(1 << 30)
+    assert default == 1 << 15
+    assert lib.fbq_test_set_spin_limit(-7) == 1 << 15            # the huge value was clamped
+    assert lib.fbq_test_set_spin_limit(default) == -1
+    assert lib.fbq_test_set_spin_limit(default) == default
 
 
 def test_training_argument_errors_without_launch():
