@@ -203,6 +203,7 @@ struct GemvGroup {
     LayerParams layer[kMaxGroup];
 };
 
+constexpr int kNowhere = 1 << 30;     // a byte offset beyond any buffer a layer has
 constexpr int kCacheSc1 = 16 | (1 << 31);   // buffer-load policy: device scope (sc1), and volatile so that a poll is never hoisted or merged
 
 extern "C" __device__ unsigned long long fbq_llvm_dispatch_id(void) __asm("llvm.amdgcn.dispatch.id");
@@ -248,8 +249,8 @@ struct RowTile {
     CodeWords<BITS> cw[ROWS][CPW];
     uint32_t sc[ROWS][CPW], zp[ROWS][CPW];   // fp16 bits, one per register: packing two would stall the load stream
 
-    // Rows past the end re-read the last row (never stored); lanes past K re-read chunk 0 (their
-    // activations are zero).  qoff: byte offset of the lane's words inside a packed row, goff: of its
+    // Rows past the end re-read the last row (never stored); lanes past K aim beyond the buffer and get
+    // zeros (their activations are zero too).  qoff: byte offset of the lane's words inside a packed row, goff: of its
     // group's scale / zero inside a row of scales.
     __device__ __forceinline__ void load(const LayerParams &p, const TileBuffers &b, int n0, const int (&qoff)[CPW], const int (&goff)[CPW])
     {
@@ -266,7 +267,7 @@ struct RowTile {
     }
 };
 
-// The lane's two taps of each of the tile's ROWS rows of Bt (taps past r re-read tap 0; their t is zero).
+// The lane's two taps of each of the tile's ROWS rows of Bt (taps past r aim beyond the buffer and read as zero; their t is zero too).
 template <int ROWS, int RI>
 __device__ __forceinline__ void load_taps(uint32_t (&bt)[ROWS][RI], const LayerParams &p, const TileBuffers &b, int n0, const int (&joff)[RI])
 {
@@ -331,10 +332,11 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     for (int c = 0; c < CPW; ++c) {
         const int k0 = ((ks * CPW + c) * 64 + lane) * kLaneCodes;
         kv[c] = k0 < p.K;
-        const int kc = kv[c] ? k0 : 0;
-        koff[c] = kc * 2;                               // the same position in a row of fp16 values (a column of A)
-        qoff[c] = (kc / kLaneCodes) * RowTile<BITS, CPW, ROWS>::kLaneWords * 4;
-        goff[c] = (kc / kGroup) * 2;
+        // lanes past K aim beyond every buffer (no layer's codes reach 2^30 bytes): the buffer unit answers zero
+        // without touching memory, and the lane's activations are zero as well
+        koff[c] = kv[c] ? k0 * 2 : kNowhere;            // the same position in a row of fp16 values (a column of A)
+        qoff[c] = kv[c] ? (k0 / kLaneCodes) * RowTile<BITS, CPW, ROWS>::kLaneWords * 4 : kNowhere;
+        goff[c] = kv[c] ? (k0 / kGroup) * 2 : kNowhere;
     }
     int joff[kRI];
     bool jv[kRI];
@@ -342,7 +344,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     for (int q = 0; q < kRI; ++q) {
         const int j = (q * 64 + lane) * 2;
         jv[q] = RI > 0 && j < p.r;
-        joff[q] = jv[q] ? j * 2 : 0;
+        joff[q] = jv[q] ? j * 2 : kNowhere;
     }
     // Down-projection.  Column j of A is a job for block j of the layer: the waves of its first row set take it,
     // each over its own K range.  So the first r blocks of a layer - the first in dispatch order - do all of it, a
@@ -367,7 +369,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     RowTile<BITS, CPW, ROWS> cur, nxt;                  // even and odd trips
     uint32_t bt0[ROWS][kRI], bt1[ROWS][kRI];            // their rows of Bt
     cur.load(p, tile_buffers(p, true), min(tile, ntiles - 1) * ROWS, qoff, goff);
-    if (RI > 0) load_taps<ROWS, kRI>(bt0, p, tile_buffers(p, true), min(tile, ntiles - 1) * ROWS, joff);
+    if (RI > 0) load_taps<ROWS, kRI>(bt0, p, tile_buffers(p, ks == 0), min(tile, ntiles - 1) * ROWS, joff);   // only the K-slice-0 wave applies them
     __builtin_amdgcn_sched_barrier(0);
 
     // Activations into LDS (piece j at j ^ ((j >> 4) & 3): the 16 lanes of a quarter wave then read 16
@@ -478,7 +480,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
                         }
                     }
                 } else {                            // the words never showed up in time: do it here
-                    const uint16_t *a0 = p.At + (size_t)(joff[q] / 2) * p.K, *a1 = a0 + p.K;
+                    const uint16_t *a0 = p.At + (size_t)(jv[q] ? joff[q] / 2 : 0) * p.K, *a1 = a0 + p.K;   // lanes without a tap: column 0, ignored
                     for (int k = 0; k < p.K; ++k) {
                         const float xv = (float)__builtin_bit_cast(half_t, xrow[k]);
                         u0 = fmaf(xv, (float)__builtin_bit_cast(half_t, a0[k]), u0);
@@ -572,7 +574,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
             finish(acc_prev, bt_prev, tile - tstride);
         }
         __builtin_amdgcn_sched_barrier(0);
-        load_taps<ROWS, kRI>(bt_prev, p, tile_buffers(p, j + 1 < trips), min(tile + tstride, ntiles - 1) * ROWS, joff);
+        load_taps<ROWS, kRI>(bt_prev, p, tile_buffers(p, j + 1 < trips && ks == 0), min(tile + tstride, ntiles - 1) * ROWS, joff);
         __builtin_amdgcn_sched_barrier(0);
     };
 
