@@ -279,6 +279,45 @@ __device__ __forceinline__ void load_taps(uint32_t (&bt)[ROWS][RI], const LayerP
     }
 }
 
+// Where a wave covers four chunks of K the kernel has no registers to spare for a column of A next to its tiles:
+// there the first blocks of a layer do nothing but the down-projection (one column per row set of the block, each
+// wave over its own K range, everything in natural order straight from memory) and leave.
+template <int CPW, int KS>
+__device__ __forceinline__ void job_only_block(const LayerParams &p, int m, int bx, int wave, int lane, uint32_t tag)
+{
+    const int ks = wave % KS;
+    const int jcol = bx * (4 / KS) + wave / KS;          // one column per row set of the block
+    if (jcol >= p.r) return;
+    const __amdgpu_buffer_rsrc_t abuf = dev_buffer(p.At, p.r * p.K * 2);
+    const __amdgpu_buffer_rsrc_t xbuf = dev_buffer(p.x + (size_t)m * p.K, p.K * 2);
+    uint4_t xr[CPW][4], ar[CPW][4];
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) {
+        const int k0 = ((ks * CPW + c) * 64 + lane) * kLaneCodes;
+        const int off = k0 < p.K ? k0 * 2 : kNowhere;    // past K: zeros from both buffers
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            xr[c][i] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, off + i * 16, 0, 0);
+            ar[c][i] = __builtin_amdgcn_raw_buffer_load_b128(abuf, off + i * 16, jcol * p.K * 2, 0);
+        }
+    }
+    float tj = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CPW; ++c)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            tj = dot2(ar[c][i].x, as_h2(xr[c][i].x), tj);
+            tj = dot2(ar[c][i].y, as_h2(xr[c][i].y), tj);
+            tj = dot2(ar[c][i].z, as_h2(xr[c][i].z), tj);
+            tj = dot2(ar[c][i].w, as_h2(xr[c][i].w), tj);
+        }
+    tj = wave_sum(tj);
+    if (lane == 0) {
+        const uint64_t word = (uint64_t)__builtin_bit_cast(uint32_t, tj) | ((uint64_t)tag << 32);
+        __hip_atomic_store(p.ttag + ((size_t)m * p.tslices + ks) * p.r + jcol, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 // BITS: 3 or 4.  CPW: chunks (of 2048 codes) per wave.  KS: waves of a block that split K.
 // ROWS: rows per tile.  RI: ceil(r/128), 0 = branch-free twin.
 template <int BITS, int CPW, int KS, int ROWS, int RI>
@@ -302,13 +341,22 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     // (all of them before the first branch: left alone, the compiler fetches only what the branch needs first)
     asm volatile("" :: "s"(p.qw), "s"(p.scales), "s"(p.zeros), "s"(p.x), "s"(p.y), "s"(p.N), "s"(p.K), "s"(p.row_words), "s"(p.G));
     if (RI > 0) asm volatile("" :: "s"(p.At), "s"(p.Bt), "s"(p.ttag), "s"(p.r), "s"(p.tslices), "s"(p.spin_limit));
-    const int bx = blockIdx.y;
-    if (bx >= p.blocks) return;
+    constexpr bool kInlineJob = CPW <= 3;               // else: the first r blocks do the down-projection and nothing else
+    int bx = blockIdx.y;
+    const int job_blocks = RI > 0 && !kInlineJob ? (p.r + kRowSets - 1) / kRowSets : 0;
+    if (bx >= p.blocks + job_blocks) return;
     const uint32_t tag = RI > 0 ? launch_tag() : 0u;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in all lanes: lets row offsets live in scalar registers
+    if (RI > 0 && !kInlineJob) {
+        if (bx < job_blocks) {                          // block-uniform
+            job_only_block<CPW, KS>(p, blockIdx.z, bx, wave, lane, tag);
+            return;
+        }
+        bx -= job_blocks;
+    }
     const int ks = wave % KS;                           // which K slice
     const int rs = wave / KS;                           // which row set of the block
     const int ntiles = (p.N + ROWS - 1) / ROWS;
@@ -354,7 +402,7 @@ __global__ __launch_bounds__(256) void fbq_gemv_kernel(const GemvGroup g)
     // asked for BEFORE the first tile: loads come back in the order they were made, and every other block waits
     // for t.
     const int jcol = bx;
-    const bool has_job = RI > 0 && rs == 0 && jcol < p.r;   // wave-uniform
+    const bool has_job = RI > 0 && kInlineJob && rs == 0 && jcol < p.r;   // wave-uniform
     uint4 acol[CPW][4];
     if (has_job) {
         const __amdgpu_buffer_rsrc_t abuf = dev_buffer(p.At, p.r * p.K * 2);
@@ -699,6 +747,14 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
     for (int i = 0; i < n_layers; ++i) tiles += ceil_div(layers[i].N, rows);
     if (tiles <= (long)budget * row_sets && tiles > (long)budget * row_sets / 2) budget = std::max(1, budget / 2);
 
+    // Where the down-projection has blocks of its own (see job_only_block) they come out of the same budget: the
+    // other blocks have fixed tile lists and must all be resident from the start.
+    const bool inline_job = v.cpw <= 3;
+    if (!inline_job) {
+        int job_blocks = 0;
+        for (int i = 0; i < n_layers; ++i) job_blocks += ceil_div(layers[i].r, row_sets);
+        budget = std::max(budget / 2, budget - job_blocks);
+    }
     GemvGroup g;
     int widest = 0;
     for (int i = 0; i < n_layers; ++i) {
@@ -713,9 +769,14 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
         p.spin_limit = spin_limit();
         const int max_blocks = ceil_div(ceil_div(a.N, rows), row_sets);
         const int share = (int)(budget * ((double)a.N * a.K / total_work));
-        // every column of A needs a block: a layer with fewer row tiles than that gets blocks that only do their job
-        p.blocks = std::max({1, std::min(max_blocks, share), a.r});
-        widest = std::max(widest, p.blocks);
+        if (inline_job) {
+            // every column of A needs a block: a layer with fewer row tiles than that gets blocks that only do their job
+            p.blocks = std::max({1, std::min(max_blocks, share), a.r});
+            widest = std::max(widest, p.blocks);
+        } else {
+            p.blocks = std::max(1, std::min(max_blocks, share));
+            widest = std::max(widest, p.blocks + ceil_div(a.r, row_sets));  // blocks in front that only do the down-projection
+        }
     }
     for (int i = n_layers; i < kMaxGroup; ++i) g.layer[i] = g.layer[0];   // never indexed: grid.x stops at n_layers
     const dim3 grid(n_layers, widest, M);
