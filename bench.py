@@ -1,12 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the fused INT3/INT4 + low-rank linear layer on one MI355X.
 
-A step is one pass of the whole hot path (in-launch down-projection + fused kernel, every layer of
-the configuration) over one batch of seeded synthetic input.  Default workload: the
-Llama2-7B-shaped decode layer set at M = 1 (q/k/v/o 4096x4096, gate/up 4096->11008,
-down 11008->4096; INT4, group 128, rank 64).  Weights are quantized on the GPU by the library's
-own feedback quantizer; every step works on a different copy of the packed layer set, so that
-neither the L2s nor the 256 MB Infinity Cache can serve the weights (the copies rotate over > 2 GB).
+A step is one pass of the whole hot path (down-projection inside the launch + fused kernel, every
+layer of the workload) over one batch of seeded synthetic input.  Headline workload: the
+Llama2-7B-shaped decode layer set at one token (q/k/v/o 4096x4096, gate/up 4096->11008,
+down 11008->4096; INT4, group 128, rank 64).  Weights are quantized on the GPU by the library's own
+feedback quantizer; every step works on a different copy of the packed layer set, so that neither
+the L2s nor the 256 MB Infinity Cache can serve the weights (the copies rotate over > 2 GB).
 
 Three launch schedules are timed (all produce identical y):
   staged     layers that can run together in a decoder share a launch: {q,k,v} {o} {gate,up} {down}
@@ -14,7 +14,14 @@ Three launch schedules are timed (all produce identical y):
   per_layer  one fbq_linear launch per layer -> 7 launches per step.
   merged     every layer with the same K in one launch -> 2 launches per step (the layers of the
              benchmark have independent inputs, so this is legal here; a decoder cannot do it).
-Prints ONE JSON line (the design doc explains every field).
+Every timing is taken several times over (`batches`); `value` and `ms_per_step` are the median
+batch of exactly --steps steps, and mean and minimum are printed beside it.
+
+`configs` adds every other benchmark configuration (single 4096x4096 rank-32 layer; the same layer
+set in INT3 at 1, 4, 8 and 16 tokens; the two MLP shapes at 1024 tokens; the large-layer sweep at
+1, 16 and 256 tokens in both bit widths), each with its branch-free twin, and
+`measured_read_peak_GBps` what a kernel that only reads gets out of the memory system at the launch
+sizes of the decode path.  Prints ONE JSON line (the design doc explains every field).
 """
 from __future__ import annotations
 
@@ -33,6 +40,8 @@ sys.path.insert(0, ROOT)
 import fbq_synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0
+TRAFFIC_PROFILE = os.path.join("profiles", "decode_gemv_llama7b_int4_m1.md")
 
 
 def parse_args():
@@ -40,11 +49,10 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--config", type=int, default=1, help="index into the benchmark configurations")
-    ap.add_argument("--M", type=int, default=0, help="tokens (default: first M of the configuration)")
+    ap.add_argument("--batches", type=int, default=5, help="how often the --steps steps are timed (median, min and mean are reported)")
     ap.add_argument("--copies", type=int, default=0, help="distinct copies of the layer set (default: > 2 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-other-kernels", action="store_true", help="skip the context timings of the few-token and prefill kernels")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other benchmark configurations and kernel families")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()
 
@@ -95,6 +103,148 @@ class GroupCall:
             raise RuntimeError(f"fbq_linear_group failed with status {rc}")
 
 
+class LayerSetBench:
+    """The rotating copies of one layer set and the schedules timed over them."""
+
+    def __init__(self, torch, fbq, specs, config, M_max, copies=0):
+        from paper_2501_16385_amd.random_layers import branch_free_twin
+        self.torch, self.fbq, self.specs, self.twin = torch, fbq, specs, branch_free_twin
+        self.base, self.xs_full = build_layer_set(specs, config, M_max, torch, fbq)
+        self.stages = stages_of(specs)
+        # the layers of a stage read the same activations, as in a decoder (q/k/v: the normalised hidden state; gate/up alike)
+        for grp in self.stages:
+            for i in grp[1:]:
+                self.xs_full[i] = self.xs_full[grp[0]]
+        set_bytes = sum(fbq_synth.algorithmic_bytes(s.N, s.K, s.r, s.bits, 1, s.group) for s in specs)
+        self.copies = copies or max(2, int(np.ceil(2.2e9 / set_bytes)))
+        self.sets = [self.base] + [[clone_layer(l, fbq) for l in self.base] for _ in range(self.copies - 1)]
+        self.stream = torch.cuda.current_stream()
+        self.sp = ctypes.c_void_p(self.stream.cuda_stream)
+
+    def bytes_per_step(self, M, plain=False, layers=None):
+        idx = range(len(self.specs)) if layers is None else layers
+        return sum(fbq_synth.algorithmic_bytes(self.specs[i].N, self.specs[i].K, 0 if plain else self.specs[i].r,
+                                               self.specs[i].bits, M, self.specs[i].group) for i in idx)
+
+    def byte_floor(self, M, layers=None):
+        idx = range(len(self.specs)) if layers is None else layers
+        return sum(2 * self.specs[i].r * (self.specs[i].K + self.specs[i].N) for i in idx) / self.bytes_per_step(M, True, layers)
+
+    def schedule(self, groups, M, plain=False):
+        """One list of GroupCalls per copy of the layer set."""
+        torch, fbq = self.torch, self.fbq
+        xs = [x[:M].contiguous() for x in self.xs_full]
+        for grp in self.stages:
+            for i in grp[1:]:
+                xs[i] = xs[grp[0]]
+        ys = [torch.empty((M, s.N), dtype=torch.float16, device="cuda") for s in self.specs]
+        wss = [torch.zeros(max(16, fbq.workspace_bytes(l.desc, M)), dtype=torch.uint8, device="cuda") for l in self.base]
+        out = []
+        for ls in self.sets:
+            calls = []
+            for grp in groups:
+                lay = [self.twin(ls[i]) if plain else ls[i] for i in grp]
+                calls.append(GroupCall(fbq, lay, [xs[i] for i in grp], [ys[i] for i in grp],
+                                       [None if plain else wss[i] for i in grp], M, self.sp))
+            out.append(calls)
+        return out
+
+    def timed(self, sched, steps, warmup, batches, graph=False):
+        """`batches` times exactly `steps` steps between two events on the launch stream.  Returns ms per step
+        (median, min and mean over the batches) and the host wall clock per step of the median batch.
+        graph: the steps are replayed from one HIP graph holding a step on every copy (steps is rounded up to
+        whole replays): for launches shorter than the host needs to enqueue one."""
+        torch = self.torch
+        if graph:
+            side = torch.cuda.Stream()
+            gsp = ctypes.c_void_p(side.cuda_stream)
+            for call in sched[0]:
+                call()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for calls in sched:
+                    for call in calls:
+                        rc = call.fn(call.arr, call.args[1], call.args[2], gsp)
+                        if rc:
+                            raise RuntimeError(f"fbq_linear_group failed with status {rc} during capture")
+            replays = max(1, -(-steps // len(sched)))
+            for _ in range(max(1, warmup // len(sched))):
+                g.replay()
+            ms = []
+            for _ in range(batches):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(replays):
+                    g.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                ms.append(e0.elapsed_time(e1) / (replays * len(sched)))
+            ms.sort()
+            return {"median": ms[len(ms) // 2], "min": ms[0], "mean": sum(ms) / len(ms), "wall": None}
+        at = 0
+        for _ in range(warmup):
+            for call in sched[at % len(sched)]:
+                call()
+            at += 1
+        res = []
+        for _ in range(batches):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record(self.stream)
+            for _ in range(steps):
+                for call in sched[at % len(sched)]:
+                    call()
+                at += 1
+            e1.record(self.stream)
+            torch.cuda.synchronize()
+            res.append((e0.elapsed_time(e1) / steps, (time.perf_counter() - t0) / steps * 1e3))
+        res.sort()
+        ms = [r[0] for r in res]
+        return {"median": ms[len(ms) // 2], "min": ms[0], "mean": sum(ms) / len(ms), "wall": res[len(ms) // 2][1]}
+
+    def timed_graph_of_all_copies(self, sched, steps, warmup):
+        """The same launches replayed from one HIP graph holding one step per copy."""
+        torch = self.torch
+        side = torch.cuda.Stream()
+        gsp = ctypes.c_void_p(side.cuda_stream)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for calls in sched:
+                for call in calls:
+                    rc = call.fn(call.arr, call.args[1], call.args[2], gsp)
+                    if rc:
+                        raise RuntimeError(f"fbq_linear_group failed with status {rc} during capture")
+        for _ in range(max(1, warmup // len(sched))):
+            g.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        done = 0
+        while done < steps:
+            g.replay()
+            done += len(sched)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / done, done
+
+
+def best_of(lsb, sched, steps, warmup):
+    """Eager launches, and for launches short enough that the host may not keep up also a graph replay: the faster."""
+    t = lsb.timed(sched, steps, warmup, 3)
+    if t["median"] * 1e3 / len(sched[0]) < 9.0:
+        g = lsb.timed(sched, steps, warmup, 3, graph=True)
+        if g["median"] < t["median"]:
+            return g
+    return t
+
+
+def us3(t):
+    return {"us_median": round(t["median"] * 1e3, 3), "us_min": round(t["min"] * 1e3, 3), "us_mean": round(t["mean"] * 1e3, 3)}
+
+
 def cpu_baseline(specs, config, M, seconds):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
     from oracle import fbq_oracle as orc
@@ -123,6 +273,26 @@ def cpu_baseline(specs, config, M, seconds):
             "us_per_layer_extrapolated": round(el / reps * 1e6 * spec.N / rows, 1)}
 
 
+def layer_entry(perf, N, K, r, bits, M, iters, rotate=1.0e9):
+    """One isolated layer shape with its branch-free twin, as one entry of `configs`."""
+    t = perf.time_layer(N, K, r, bits, M, iters=iters, warmup=max(3, iters // 10), rotate_bytes=rotate, repeats=3, with_twin=True,
+                        graph="auto")
+    e = {"workload": f"{K}->{N} INT{bits} r={r} M={M}",
+         "mode": "isolated: one fbq_linear per call, back to back, copies rotated (launches under 9 us also replayed from a HIP graph, "
+                 "the faster counts: the host cannot enqueue a call every few microseconds)",
+         "us_median": t["us"], "us_min": t["us_min"], "us_mean": t["us_mean"]}
+    if M <= 64:
+        e.update({"bound": "hbm", "GBps": t["GBps"], "frac_of_hbm_peak": round(t["GBps"] / HBM_PEAK_GBS, 4),
+                  "branch_overhead_byte_floor_pct": round(200.0 * r * (K + N) / fbq_synth.algorithmic_bytes(N, K, 0, bits, M), 2)})
+    else:
+        e.update({"bound": "mfma", "TFLOPps": t["TFLOPps"], "frac_of_fp16_mfma_peak": round(t["TFLOPps"] / MFMA_F16_PEAK_TFLOPS, 4),
+                  "GBps": t["GBps"], "branch_overhead_flop_floor_pct": round(100.0 * r * (K + N) / (N * K), 2)})
+    if "us_branch_free" in t:
+        e["us_branch_free_median"] = t["us_branch_free"]
+        e["branch_overhead_pct"] = t["branch_overhead_pct"]
+    return e
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -130,192 +300,159 @@ def main():
         sys.exit(2)
     import torch
     import paper_2501_16385_amd as fbq
+    from paper_2501_16385_amd import perf
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; there is no CPU fallback", file=sys.stderr)
         sys.exit(3)
     fbq.load()
     torch.cuda.set_device(0)
+    K, W, R = args.steps, args.warmup, max(1, args.batches)
 
-    specs, Ms = fbq_synth.config_layers(args.config)
-    M = args.M or Ms[0]
-    if M > 16:
-        print("bench.py: the default benchmark times the decode path (M <= 16)", file=sys.stderr)
-        sys.exit(2)
-    base_layers, xs = build_layer_set(specs, args.config, M, torch, fbq)
-    # the layers of a stage read the same activations, as in a decoder (q/k/v: the normalised hidden state; gate/up alike)
-    for grp in stages_of(specs):
-        for i in grp[1:]:
-            xs[i] = xs[grp[0]]
-    nbytes = [fbq_synth.algorithmic_bytes(s.N, s.K, s.r, s.bits, M, s.group) for s in specs]
-    nbytes_plain = [fbq_synth.algorithmic_bytes(s.N, s.K, 0, s.bits, M, s.group) for s in specs]
-    set_bytes = sum(nbytes)
-    copies = args.copies or max(2, int(np.ceil(2.2e9 / set_bytes)))
-    sets = [base_layers] + [[clone_layer(l, fbq) for l in base_layers] for _ in range(copies - 1)]
+    # ---------------------------------------------------------------- headline: Llama2-7B decode set, INT4, rank 64, one token
+    CONFIG = 1                                               # seeds: position of this workload in the benchmark's list, from 0
+    specs, _ = fbq_synth.config_layers(CONFIG)
+    M = 1
+    lsb = LayerSetBench(torch, fbq, specs, CONFIG, M, args.copies)
+    staged, n_layers = lsb.stages, len(specs)
+    per_layer = [[i] for i in range(n_layers)]
+    merged = [list(range(n_layers))]                         # the library splits it by kernel variant itself
+    set_bytes = lsb.bytes_per_step(M)
 
-    stream = torch.cuda.current_stream()
-    sp = ctypes.c_void_p(stream.cuda_stream)
-    ys = [torch.empty((M, s.N), dtype=torch.float16, device="cuda") for s in specs]
-    wss = [torch.zeros(max(16, fbq.workspace_bytes(l.desc, M)), dtype=torch.uint8, device="cuda") for l in base_layers]
+    t_staged = lsb.timed(lsb.schedule(staged, M), K, W, R)
+    t_staged_plain = lsb.timed(lsb.schedule(staged, M, plain=True), K, W, R)
+    ms_graph_all, graph_steps = lsb.timed_graph_of_all_copies(lsb.schedule(staged, M), K, W)
+    t_layer = lsb.timed(lsb.schedule(per_layer, M), K, W, R)
+    t_layer_plain = lsb.timed(lsb.schedule(per_layer, M, plain=True), K, W, R)
+    t_merged = lsb.timed(lsb.schedule(merged, M), K, W, R)
+    t_merged_plain = lsb.timed(lsb.schedule(merged, M, plain=True), K, W, R)
 
-    def twin(l):     # branch-free twin (r = 0) of the same packed layer: the comparator of "branch overhead %"
-        return fbq.DeviceLayer(fbq.Desc(l.desc.N, l.desc.K, 0, l.desc.bits, l.desc.group), l.qweight, l.scales, l.zeros,
-                               None, None)
+    # every stage's launch alone, back to back on the stream (this includes the ~1.5 us the command processor needs
+    # between two dependent launches; launches under 9 us are also replayed from a HIP graph over all copies, because
+    # the host cannot enqueue a launch every 4 us, and the faster counts); the one that moves most bytes is the dominant kernel of `roofline`
+    stage_rows = []
+    for grp in staged:
+        tf, tp = (best_of(lsb, lsb.schedule([grp], M, plain=pl), max(K, 200), W) for pl in (False, True))
+        b = lsb.bytes_per_step(M, layers=grp)
+        stage_rows.append({"launch": "{" + ",".join(specs[i].name for i in grp) + "}", "bytes": b, **us3(tf),
+                           "GBps": round(b / tf["median"] / 1e6, 1), "frac_of_hbm_peak": round(b / tf["median"] / 1e6 / HBM_PEAK_GBS, 4),
+                           "us_branch_free_median": round(tp["median"] * 1e3, 3),
+                           "branch_overhead_pct": round((tf["median"] / tp["median"] - 1) * 100, 2),
+                           "branch_overhead_byte_floor_pct": round(lsb.byte_floor(M, grp) * 100, 2)})
+    dom = max(stage_rows, key=lambda r: r["bytes"])
 
-    def schedule(groups, plain=False):
-        """One list of GroupCalls per copy of the layer set."""
-        out = []
-        for ls in sets:
-            calls = []
-            for grp in groups:
-                lay = [twin(ls[i]) if plain else ls[i] for i in grp]
-                calls.append(GroupCall(fbq, lay, [xs[i] for i in grp], [ys[i] for i in grp],
-                                       [None if plain else wss[i] for i in grp], M, sp))
-            out.append(calls)
-        return out
-
-    def timed(sched, n, warm):
-        for s in range(warm):
-            for call in sched[s % len(sched)]:
-                call()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        e0.record(stream)
-        for s in range(n):
-            for call in sched[(warm + s) % len(sched)]:
-                call()
-        e1.record(stream)
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        return e0.elapsed_time(e1) / n, wall / n * 1e3      # ms per step: device events, host wall clock
-
-    def timed_graphs(sched, n, warm, steps_per_graph):
-        """The same launches replayed from HIP graphs of steps_per_graph consecutive steps each."""
-        graphs = []
-        side = torch.cuda.Stream()
-        gsp = ctypes.c_void_p(side.cuda_stream)
-        for g0 in range(0, len(sched), steps_per_graph):
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=side):
-                for calls in sched[g0:g0 + steps_per_graph]:
-                    for call in calls:
-                        rc = call.fn(call.arr, call.args[1], call.args[2], gsp)
-                        if rc:
-                            raise RuntimeError(f"fbq_linear_group failed with status {rc} during capture")
-            graphs.append((g, len(sched[g0:g0 + steps_per_graph])))
-        for i in range(max(1, warm // steps_per_graph)):
-            graphs[i % len(graphs)][0].replay()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        done, i = 0, 0
-        while done < n:
-            g, k = graphs[i % len(graphs)]
-            g.replay()
-            done += k
-            i += 1
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / done, done
-
-    staged = stages_of(specs)
-    per_layer = [[i] for i in range(len(specs))]
-    merged = [list(range(len(specs)))]                       # the library splits it by kernel variant itself
-
-    ms_staged, wall_staged = timed(schedule(staged), args.steps, args.warmup)
-    ms_staged_plain, _ = timed(schedule(staged, plain=True), args.steps, args.warmup)
-    ms_graph_all, graph_steps = timed_graphs(schedule(staged), args.steps, args.warmup, copies)
-    ms_layer, _ = timed(schedule(per_layer), args.steps, args.warmup)
-    ms_layer_plain, _ = timed(schedule(per_layer, plain=True), args.steps, args.warmup)
-    ms_merged, _ = timed(schedule(merged), args.steps, args.warmup)
-    ms_merged_plain, _ = timed(schedule(merged, plain=True), args.steps, args.warmup)
-
-    # dominant kernel: the fused GEMV launch that serves the widest stage (most bytes per launch).
-    # Its launches alone, back to back on the stream, bracketed by events: average duration per launch
-    # (this includes the ~1.5 us the command processor needs between two dependent launches).
-    dom = max(staged, key=lambda grp: sum(nbytes[i] for i in grp))
-    dom_bytes = sum(nbytes[i] for i in dom)
-    ms_dom, _ = timed(schedule([dom]), args.steps, args.warmup)
-    dom_gbps = dom_bytes / (ms_dom * 1e-3) / 1e9
-
-    # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (config 1 only)
     traffic = None
-    prof = os.path.join(ROOT, "profiles", "decode_gemv_llama7b_int4_m1.md")
-    if args.config == 1 and M == 1 and os.path.exists(prof):
+    prof = os.path.join(ROOT, TRAFFIC_PROFILE)
+    if os.path.exists(prof):
         for line in open(prof):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = int(line.split(":")[1])
 
-    n_layers = len(specs)
-    gbps = set_bytes / (ms_staged * 1e-3) / 1e9
-    floor = sum(2 * s.r * (s.K + s.N) for s in specs) / sum(nbytes_plain)
-    mode = lambda ms, ms_plain, launches: {
-        "launches_per_step": launches, "us_per_step": round(ms * 1e3, 3), "us_per_layer": round(ms * 1e3 / n_layers, 3),
-        "GBps": round(set_bytes / ms / 1e6, 1), "frac_of_hbm_peak": round(set_bytes / ms / 1e6 / HBM_PEAK_GBS, 4),
-        "us_per_layer_branch_free": round(ms_plain * 1e3 / n_layers, 3),
-        "branch_overhead_pct": round((ms / ms_plain - 1) * 100, 2)}
+    gbps = set_bytes / (t_staged["median"] * 1e-3) / 1e9
+    mode = lambda t, tp, launches: {
+        "launches_per_step": launches, "us_per_step": round(t["median"] * 1e3, 3), "us_per_step_min": round(t["min"] * 1e3, 3),
+        "us_per_step_mean": round(t["mean"] * 1e3, 3), "us_per_layer": round(t["median"] * 1e3 / n_layers, 3),
+        "GBps": round(set_bytes / t["median"] / 1e6, 1), "frac_of_hbm_peak": round(set_bytes / t["median"] / 1e6 / HBM_PEAK_GBS, 4),
+        "us_per_layer_branch_free": round(tp["median"] * 1e3 / n_layers, 3),
+        "branch_overhead_pct": round((t["median"] / tp["median"] - 1) * 100, 2)}
+    shapes = ", ".join(sorted({f"{s.K}->{s.N}" for s in specs}))
     out = {
         "metric": "fused W4/W3+low-rank linear: effective HBM GB/s (us/layer and branch overhead % alongside)",
-        "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_staged, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": round(gbps, 2), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(t_staged["median"], 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": f"int{specs[0].bits} codes, f16 in/out, f32 accumulate", "data": "synthetic",
-        "config": {"workload": f"config {args.config}: " + ", ".join(sorted({f'{s.K}->{s.N}' for s in specs})) +
-                   f"; {n_layers} layers/step, INT{specs[0].bits}, group 128, rank {specs[0].r}, M={M}",
-                   "layers_per_step": n_layers, "bytes_per_step": set_bytes, "copies_rotated": copies,
+        "config": {"workload": f"Llama2-7B-shaped decode layer set, {n_layers} linears per step ({shapes}), INT4, group 128, "
+                               f"rank 64, M=1 token", "layers_per_step": n_layers, "bytes_per_step": set_bytes,
+                   "copies_rotated": lsb.copies,
                    "launch_schedule": "staged: " + " ".join("{" + ",".join(specs[i].name for i in g) + "}" for g in staged)},
-        "us_per_layer": round(ms_staged * 1e3 / n_layers, 3),
-        "branch_overhead_pct": round((ms_staged / ms_staged_plain - 1) * 100, 2),
-        "branch_overhead_byte_floor_pct": round(floor * 100, 2),
+        "timing": {"batches": R, "steps_per_batch": K, "ms_per_step_median": round(t_staged["median"], 6),
+                   "ms_per_step_min": round(t_staged["min"], 6), "ms_per_step_mean": round(t_staged["mean"], 6),
+                   "clock": "HIP events on the launch stream; GPU clocks as found"},
+        "us_per_layer": round(t_staged["median"] * 1e3 / n_layers, 3),
+        "branch_overhead_pct": round((t_staged["median"] / t_staged_plain["median"] - 1) * 100, 2),
+        "branch_overhead_byte_floor_pct": round(lsb.byte_floor(M) * 100, 2),
         "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBS, 4),
-        "wall_ms_per_step": round(wall_staged, 6),
-        "schedules": {"staged": mode(ms_staged, ms_staged_plain, len(staged)),
+        "wall_ms_per_step": round(t_staged["wall"], 6),
+        "schedules": {"staged": mode(t_staged, t_staged_plain, len(staged)),
                       "staged_graph_of_all_copies": {"us_per_step": round(ms_graph_all * 1e3, 3), "steps_timed": graph_steps,
                                                      "GBps": round(set_bytes / ms_graph_all / 1e6, 1)},
-                      "per_layer": mode(ms_layer, ms_layer_plain, len(per_layer)),
-                      "merged": mode(ms_merged, ms_merged_plain, 2)},
-        "roofline": {"bound": "hbm", "kernel": ("fbq_gemv_kernel" if M <= 2 else "fbq_small_m_kernel") + ", the launch serving {" +
-                     ",".join(specs[i].name for i in dom) + "}", "achieved": round(dom_gbps, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(dom_gbps / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "avg_launch_us": round(ms_dom * 1e3, 3), "bytes_per_launch": dom_bytes},
+                      "per_layer": mode(t_layer, t_layer_plain, len(per_layer)),
+                      "merged": mode(t_merged, t_merged_plain, 2)},
+        "launches_of_the_staged_schedule": stage_rows,
+        "roofline": {"bound": "hbm", "kernel": "fbq_gemv_kernel, the launch serving " + dom["launch"],
+                     "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["frac_of_hbm_peak"],
+                     "traffic": traffic, "traffic_source": f"quoted from the committed rocprofv3 summary {TRAFFIC_PROFILE} "
+                                                           "(FETCH_SIZE + WRITE_SIZE of this launch), not measured in this run",
+                     "avg_launch_us": dom["us_mean"], "median_launch_us": dom["us_median"], "min_launch_us": dom["us_min"],
+                     "bytes_per_launch": dom["bytes"]},
     }
-    if not args.no_other_kernels:
-        # Context, not part of `value`: the other two kernel families on the widest layer shape of the set
-        # (random packed words, same rotation protocol; see paper_2501_16385_amd/perf.py).
-        from paper_2501_16385_amd import perf
-        wide = max(specs, key=lambda s: s.N * s.K)
-        fam = {}
-        if len(staged) < len(specs):
-            # the same staged layer set with 16 tokens: the layers of a stage share their activations, as in a decoder
-            M16 = 16
-            xs16 = {}
-            for grp in staged:
-                shared = torch.randn((M16, specs[grp[0]].K), device="cuda").half()
-                for i in grp:
-                    xs16[i] = shared
-            ys16 = [torch.empty((M16, s.N), dtype=torch.float16, device="cuda") for s in specs]
-            ws16 = [torch.zeros(max(16, fbq.workspace_bytes(l.desc, M16)), dtype=torch.uint8, device="cuda") for l in base_layers]
-            sched16 = [[GroupCall(fbq, [ls[i] for i in grp], [xs16[i] for i in grp], [ys16[i] for i in grp],
-                                  [ws16[i] for i in grp], M16, sp) for grp in staged] for ls in sets]
-            ms16, _ = timed(sched16, max(50, args.steps // 4), max(5, args.warmup // 4))
-            bytes16 = sum(fbq_synth.algorithmic_bytes(s.N, s.K, s.r, s.bits, M16, s.group) for s in specs)
-            fam["few_token_M16_staged_layer_set"] = {"launches_per_step": len(staged), "us_per_step": round(ms16 * 1e3, 2),
-                                                     "us_per_layer": round(ms16 * 1e3 / n_layers, 3),
-                                                     "GBps": round(bytes16 / ms16 / 1e6, 1),
-                                                     "frac_of_hbm_peak": round(bytes16 / ms16 / 1e6 / HBM_PEAK_GBS, 4)}
-            del sched16
-        del sets
+
+    # ---------------------------------------------------------------- what a kernel that only reads gets at these launch sizes
+    dom_bytes = dom["bytes"]
+    del lsb
+    torch.cuda.empty_cache()
+    sizes = {"one 4096x4096 INT4 r=64 layer": fbq_synth.algorithmic_bytes(4096, 4096, 64, 4, 1),
+             "{q,k,v} launch": stage_rows[0]["bytes"], "{gate,up} launch": dom_bytes,
+             "one 8192->28672 INT4 r=128 layer": fbq_synth.algorithmic_bytes(28672, 8192, 128, 4, 1), "1 GiB": 1 << 30}
+    peak = {}
+    for name, nb in sizes.items():
+        t = perf.time_read_stream(nb, iters=200 if nb < (1 << 28) else 20, warmup=10)
+        peak[name] = {"bytes": t["bytes"], "us": t["us"], "GBps": t["GBps"]}
+    perf.free_read_pool()
+    torch.cuda.empty_cache()
+    out["measured_read_peak_GBps"] = {"kernel": "fbq_read_stream_kernel: reads each byte once, writes nothing; launches back to back, "
+                                                "every launch on another part of a 3 GiB pool", "by_launch_size": peak}
+    out["roofline"]["frac_of_measured_read_peak_at_this_size"] = round(dom["GBps"] / peak["{gate,up} launch"]["GBps"], 4)
+
+    if not args.no_configs:
+        cfgs = []
+        # single 4096 x 4096 layer, INT4, rank 32, one token
+        cfgs.append(layer_entry(perf, 4096, 4096, 32, 4, 1, 400))
+        # the same layer set in INT3 at 1, 4, 8 and 16 tokens, staged schedule
+        CFG3 = 2
+        specs3, Ms3 = fbq_synth.config_layers(CFG3)
+        lsb3 = LayerSetBench(torch, fbq, specs3, CFG3, max(Ms3), args.copies)
+        for m in Ms3:
+            tf = lsb3.timed(lsb3.schedule(lsb3.stages, m), 300, 30, 3)
+            tp = lsb3.timed(lsb3.schedule(lsb3.stages, m, plain=True), 300, 30, 3)
+            b = lsb3.bytes_per_step(m)
+            cfgs.append({"workload": f"Llama2-7B-shaped decode layer set, 7 linears per step, INT3, rank 64, M={m}",
+                         "mode": "stream: staged schedule, 4 launches per step, copies rotated", "bound": "hbm",
+                         "us_per_step_median": round(tf["median"] * 1e3, 3), "us_per_step_min": round(tf["min"] * 1e3, 3),
+                         "us_per_step_mean": round(tf["mean"] * 1e3, 3), "us_per_layer": round(tf["median"] * 1e3 / 7, 3),
+                         "GBps": round(b / tf["median"] / 1e6, 1), "frac_of_hbm_peak": round(b / tf["median"] / 1e6 / HBM_PEAK_GBS, 4),
+                         "us_per_step_branch_free_median": round(tp["median"] * 1e3, 3),
+                         "branch_overhead_pct": round((tf["median"] / tp["median"] - 1) * 100, 2),
+                         "branch_overhead_byte_floor_pct": round(lsb3.byte_floor(m) * 100, 2)})
+        del lsb3
         torch.cuda.empty_cache()
-        for name, m in (("few_token_M16", 16), ("few_token_M4", 4), ("prefill_M1024", 1024)):
-            t = perf.time_layer(wide.N, wide.K, wide.r, wide.bits, m, iters=200 if m <= 16 else 50, warmup=20)
-            fam[name] = {"shape": f"{wide.K}->{wide.N}", "us": t["us"], "GBps": t["GBps"], "TFLOPps": t["TFLOPps"],
-                         "frac_of_hbm_peak": round(t["GBps"] / HBM_PEAK_GBS, 4),
-                         "frac_of_fp16_mfma_peak": round(t["TFLOPps"] / 2500.0, 4)}
+        # the staged INT4 set at 16 tokens (few-token kernel), for comparison with the round before
+        lsb16 = LayerSetBench(torch, fbq, specs, CONFIG, 16, args.copies)
+        t16 = lsb16.timed(lsb16.schedule(lsb16.stages, 16), 300, 30, 3)
+        b16 = lsb16.bytes_per_step(16)
+        few16 = {"launches_per_step": 4, "us_per_step": round(t16["median"] * 1e3, 2), "us_per_step_min": round(t16["min"] * 1e3, 2),
+                 "us_per_layer": round(t16["median"] * 1e3 / 7, 3), "GBps": round(b16 / t16["median"] / 1e6, 1),
+                 "frac_of_hbm_peak": round(b16 / t16["median"] / 1e6 / HBM_PEAK_GBS, 4)}
+        del lsb16
+        torch.cuda.empty_cache()
+        # prefill: 1024 tokens through the two MLP shapes, INT4, rank 64
+        for (n, k) in ((11008, 4096), (4096, 11008)):
+            cfgs.append(layer_entry(perf, n, k, 64, 4, 1024, 40))
+        # large-layer sweep, rank 128, both bit widths, 1 / 16 / 256 tokens
+        for bits in (4, 3):
+            for (n, k) in ((13824, 5120), (5120, 13824), (28672, 8192), (8192, 28672)):
+                for m in (1, 16, 256):
+                    cfgs.append(layer_entry(perf, n, k, 128, bits, m, 100 if m <= 16 else 30))
+        out["configs"] = cfgs
+        fam = {"few_token_M16_staged_layer_set": few16}
+        for name, m in (("few_token_M16", 16), ("few_token_M4", 4)):
+            t = perf.time_layer(11008, 4096, 64, 4, m, iters=200, warmup=20, graph="auto")
+            fam[name] = {"shape": "4096->11008", "us": t["us"], "us_min": t["us_min"], "GBps": t["GBps"],
+                         "frac_of_hbm_peak": round(t["GBps"] / HBM_PEAK_GBS, 4)}
         # layer-wise reconstruction (Alg. 1) on the 4096 x 4096 shape of the set, 2048 calibration tokens
-        sq = min(specs, key=lambda s: s.N * s.K)
-        fam["reconstruction_step"] = perf.time_train_step(sq.N, sq.K, sq.r, sq.bits, 2048, iters=20, warmup=3)
+        fam["reconstruction_step"] = perf.time_train_step(4096, 4096, 64, 4, 2048, iters=20, warmup=3)
         out["other_kernel_families"] = fam
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(specs, args.config, M, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(specs, CONFIG, M, args.cpu_seconds)
     print(json.dumps(out))
 
 

@@ -209,6 +209,17 @@ fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, const void *A
                                  void *qweight_out, void *scales_out, void *zeros_out, fbq_stream stream);
 
 /*
+ * fbq_measure_read_stream - measurement aid, not part of the method.  One launch that reads every
+ * 16-byte piece of buf[0, bytes) once and writes nothing.  Timed like the decode kernels (back to back
+ * on a stream, over buffers no cache holds) it gives what the memory system delivers to a launch of
+ * that size on this GPU: the ceiling the decode path's GB/s is quoted against beside the nominal HBM
+ * peak (Sec. 1 names weight loading as the bottleneck the quantized layer is up against).
+ *   buf device, 16-byte aligned, bytes >= 16 (a tail of less than 16 bytes is not read).
+ * Errors: FBQ_ERR_NULL, FBQ_ERR_SHAPE (bytes < 16), FBQ_ERR_ALIGN before the launch; FBQ_ERR_HIP.
+ */
+fbq_status fbq_measure_read_stream(const void *buf, size_t bytes, fbq_stream stream);
+
+/*
  * Layer-wise reconstruction (Alg. 1, Sec. 4.2): gradient descent on the sub-branch of one layer so
  * that the quantized layer reproduces the fp16 layer's outputs on calibration activations X [T,K].
  * Loss and gradient depend on X only through H = X^T X (Sec. 4.2: L = tr(Delta_F H Delta_F^T) with

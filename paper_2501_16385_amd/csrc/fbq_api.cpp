@@ -296,6 +296,14 @@ extern "C" int fbq_test_set_spin_limit(int polls)
     return g_spin_limit.exchange(clamped, std::memory_order_relaxed);
 }
 
+extern "C" fbq_status fbq_measure_read_stream(const void *buf, size_t bytes, fbq_stream stream)
+{
+    if (!buf) return FBQ_ERR_NULL;
+    if (bytes < 16) return FBQ_ERR_SHAPE;
+    if (misaligned(buf)) return FBQ_ERR_ALIGN;
+    return hip_status(launch_read_stream(buf, bytes, (hipStream_t)stream));
+}
+
 extern "C" size_t fbq_train_workspace_bytes(const fbq_desc *d, int T)
 {
     if (fbq_check_desc(d) != FBQ_OK || d->r < 1 || T < 1) return 0;

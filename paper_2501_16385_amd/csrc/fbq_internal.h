@@ -63,6 +63,8 @@ hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t 
                            uint16_t *scales, uint16_t *zeros, hipStream_t stream, uint16_t *D16 = nullptr,
                            uint16_t *Dt16 = nullptr, int ldt = 0, float gain = 0.0f);
 
+hipError_t launch_read_stream(const void *buf, size_t bytes, hipStream_t stream);
+
 // Arguments of one reconstruction iteration (validated): see fbq_train_step.
 struct TrainArgs {
     fbq_desc d;

@@ -256,4 +256,34 @@ hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t 
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ read-stream yardstick
+
+// Reads every 16-byte piece of a buffer once and writes nothing: what the memory system delivers to a
+// launch of a given size, measured with the same launch protocol as the decode kernels, is the
+// ceiling they are judged against beside the nominal HBM peak.  Eight loads per thread in flight.
+__global__ __launch_bounds__(256) void fbq_read_stream_kernel(const uint4 *__restrict__ p, unsigned long long n16)
+{
+    constexpr int kUnroll = 8;
+    unsigned long long i = ((unsigned long long)blockIdx.x * kUnroll) * 256 + threadIdx.x;
+    const unsigned long long stride = (unsigned long long)gridDim.x * kUnroll * 256;
+    for (; i < n16; i += stride) {
+        uint4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const unsigned long long j = i + (unsigned long long)u * 256;
+            v[u] = p[j < n16 ? j : n16 - 1];             // past the end: the last piece again, never out of bounds
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) asm volatile("" ::"v"(v[u].x), "v"(v[u].y), "v"(v[u].z), "v"(v[u].w));   // keeps the loads alive
+    }
+}
+
+hipError_t launch_read_stream(const void *buf, size_t bytes, hipStream_t stream)
+{
+    const unsigned long long n16 = bytes / 16;
+    const int blocks = (int)std::min<unsigned long long>(1024, (n16 + 2047) / 2048);
+    hipLaunchKernelGGL(fbq_read_stream_kernel, dim3(blocks), dim3(256), 0, stream, (const uint4 *)buf, n16);
+    return hipGetLastError();
+}
+
 }  // namespace fbq

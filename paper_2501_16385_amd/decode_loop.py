@@ -23,11 +23,16 @@ from __future__ import annotations
 import argparse
 import ctypes
 import json
+import os
+import sys
 
 import torch
 
 from . import fbq
-from .perf import random_layer
+from .random_layers import random_layer
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+import fbq_synth  # noqa: E402  (byte accounting)
 
 NAMES = ("q", "k", "v", "o", "gate", "up", "down")
 
@@ -130,8 +135,7 @@ def main():
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) / a.tokens * 1e3
     shapes = layer_shapes(a.hidden, a.inter)
-    from .perf import algorithmic_bytes
-    nbytes = a.layers * sum(algorithmic_bytes(N, K, a.r, a.bits, a.batch) for N, K in shapes.values())
+    nbytes = a.layers * sum(fbq_synth.algorithmic_bytes(N, K, a.r, a.bits, a.batch) for N, K in shapes.values())
     print(json.dumps({"tokens_per_s": round(a.batch * 1e6 / us, 1), "us_per_step": round(us, 1), "batch": a.batch, "layers": a.layers,
                       "fused_launches_per_step": 4 * a.layers, "GBps_over_linear_layers": round(nbytes / us / 1e3, 1),
                       "bits": a.bits, "r": a.r, "hidden": a.hidden, "inter": a.inter, "tokens_timed": a.tokens,

@@ -19,7 +19,8 @@ _lib: Optional[ctypes.CDLL] = None
 
 EXPORTED_SYMBOLS = ["fbq_status_string", "fbq_check_desc", "fbq_packed_bytes", "fbq_workspace_bytes", "fbq_pack",
                     "fbq_linear", "fbq_linear_static", "fbq_linear_group", "fbq_reconstruct", "fbq_unpack_codes", "fbq_quantize_feedback",
-                    "fbq_train_workspace_bytes", "fbq_gram", "fbq_train_step", "fbq_test_set_spin_limit"]
+                    "fbq_train_workspace_bytes", "fbq_gram", "fbq_train_step", "fbq_test_set_spin_limit",
+                    "fbq_measure_read_stream"]
 
 
 class FbqError(RuntimeError):
@@ -78,6 +79,8 @@ def load() -> ctypes.CDLL:
         lib.fbq_linear.argtypes = [dp, i32] + [vp] * 8 + [sz, vp]
         lib.fbq_linear_static.restype = i32
         lib.fbq_linear_static.argtypes = [dp, i32] + [vp] * 8
+        lib.fbq_measure_read_stream.restype = i32
+        lib.fbq_measure_read_stream.argtypes = [vp, sz, vp]
         lib.fbq_test_set_spin_limit.restype = i32
         lib.fbq_test_set_spin_limit.argtypes = [i32]
         lib.fbq_linear_group.restype = i32

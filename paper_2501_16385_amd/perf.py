@@ -11,37 +11,44 @@ import argparse
 import ctypes
 import json
 
+import os
+import sys
+
 import torch
 
 from . import fbq
+from .random_layers import branch_free_twin, random_layer
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+import fbq_synth  # noqa: E402  (byte and flop accounting: the one copy, pinned by the tests against the paper's MAC ratio)
 
 
-def algorithmic_bytes(N, K, r, bits, M):
-    return N * K * bits // 8 + 4 * N * (K // 128) + 2 * r * (K + N) + 2 * M * (K + N)
+kHostBoundUs = 9.0     # below this a Python loop of ctypes calls may not keep the stream fed: such launches are also timed from a HIP graph
 
 
-def algorithmic_flops(N, K, r, M):
-    return 2 * M * N * K + 2 * M * r * (K + N)
+def event_stats(run, iters, warmup, repeats=5):
+    """run(n) enqueues n calls on the current stream.  Times `repeats` batches of `iters` calls each with HIP
+    events; returns microseconds per call: mean over all batches, median and minimum over the batches."""
+    run(warmup)
+    torch.cuda.synchronize()
+    per_call = []
+    for _ in range(repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run(iters)
+        e1.record()
+        torch.cuda.synchronize()
+        per_call.append(e0.elapsed_time(e1) / iters * 1e3)
+    per_call.sort()
+    return {"us_mean": round(sum(per_call) / len(per_call), 3), "us_median": round(per_call[len(per_call) // 2], 3),
+            "us_min": round(per_call[0], 3), "batches": repeats, "calls_per_batch": iters}
 
 
-def random_layer(d: fbq.Desc, gen, gain=None) -> fbq.DeviceLayer:
-    """Uniformly random codes; gain: if given, scales are chosen so that |y| is about gain * |x| for random x."""
-    words = fbq.packed_bytes(d) // 4 // d.N
-    qmax = 2**d.bits - 1
-    qw = torch.randint(-2**31, 2**31 - 1, (d.N, words), dtype=torch.int32, device="cuda", generator=gen)
-    s = torch.rand(d.N, d.K // 128, device="cuda", generator=gen) * 0.01 + 0.001
-    if gain is not None:                  # codes uniform on 0..qmax around a zero point near the middle: std (qmax + 1) / sqrt(12)
-        s = s * (gain / (0.006 * (qmax + 1) / 12 ** 0.5 * d.K ** 0.5))
-    s = s.half().view(torch.int16)
-    z = (torch.rand(d.N, d.K // 128, device="cuda", generator=gen) + 0.5 * (qmax - 1)).half().view(torch.int16)
-    At = Bt = None
-    if d.r:
-        At = (torch.randn(d.r, d.K, device="cuda", generator=gen) * 0.01).half().view(torch.int16)
-        Bt = (torch.randn(d.N, d.r, device="cuda", generator=gen) * 0.01).half().view(torch.int16)
-    return fbq.DeviceLayer(d, qw, s, z, At, Bt)
-
-
-def time_layer(N, K, r, bits, M, iters=100, warmup=10, rotate_bytes=1.0e9):
+def time_layer(N, K, r, bits, M, iters=100, warmup=10, rotate_bytes=1.0e9, repeats=3, with_twin=False, graph=False):
+    """One layer shape, isolated: the same call back to back on the stream, every call on another copy of the
+    packed layer.  with_twin also times the branch-free twin (r = 0) on the same packed weights.  graph: the calls
+    are replayed from one HIP graph over all copies (for launches shorter than the host needs to enqueue one);
+    "auto": eager first, and where that comes out below kHostBoundUs the graph as well, the faster of the two counts."""
     lib = fbq.load()
     d = fbq.Desc(N, K, r, bits)
     gen = torch.Generator(device="cuda")
@@ -50,30 +57,90 @@ def time_layer(N, K, r, bits, M, iters=100, warmup=10, rotate_bytes=1.0e9):
     layers = [random_layer(d, gen) for _ in range(copies)]
     x = torch.randn(M, K, device="cuda", generator=gen).half()
     y = torch.empty(M, N, dtype=torch.float16, device="cuda")
-    ws = torch.zeros(max(16, fbq.workspace_bytes(d, M)), dtype=torch.uint8, device="cuda")
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     ptr = lambda t: ctypes.c_void_p(0 if t is None else t.data_ptr())
-    descs = [l.desc.c() for l in layers]
-    calls = [(ctypes.byref(descs[i]), M, ptr(x), ptr(l.qweight), ptr(l.scales), ptr(l.zeros), ptr(l.At), ptr(l.Bt),
-              ptr(y), ptr(ws), ctypes.c_size_t(ws.numel()), stream) for i, l in enumerate(layers)]
+
+    def timed(ls):
+        dd = ls[0].desc
+        ws = torch.zeros(max(16, fbq.workspace_bytes(dd, M)), dtype=torch.uint8, device="cuda")
+        descs = [l.desc.c() for l in ls]
+        calls = [(ctypes.byref(descs[i]), M, ptr(x), ptr(l.qweight), ptr(l.scales), ptr(l.zeros), ptr(l.At), ptr(l.Bt),
+                  ptr(y), ptr(ws), ctypes.c_size_t(ws.numel()), stream) for i, l in enumerate(ls)]
+
+        def run(n):
+            for i in range(n):
+                rc = lib.fbq_linear(*calls[i % copies])
+                if rc != 0:
+                    raise RuntimeError(f"fbq_linear: {fbq.status_string(rc)}")
+        eager = None
+        if graph != True:
+            eager = event_stats(run, iters, warmup, repeats)
+            if not graph or eager["us_median"] > kHostBoundUs:
+                return eager
+        # one HIP graph holding a call on every copy: the host enqueues one graph instead of a call every few microseconds
+        side = torch.cuda.Stream()
+        gstream = ctypes.c_void_p(side.cuda_stream)
+        run(2)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for c in calls:
+                rc = lib.fbq_linear(*(c[:-1] + (gstream,)))
+                if rc != 0:
+                    raise RuntimeError(f"fbq_linear: {fbq.status_string(rc)} during capture")
+        replays = max(1, -(-iters // copies))
+        st = event_stats(lambda n: [g.replay() for _ in range(n)], replays, max(1, warmup // copies), repeats)
+        for k in ("us_mean", "us_median", "us_min"):
+            st[k] = round(st[k] / copies, 3)
+        return st if eager is None or st["us_median"] < eager["us_median"] else eager
+
+    st = timed(layers)
+    us = st["us_median"]
+    out = {"N": N, "K": K, "r": r, "bits": bits, "M": M, "us": us, "us_min": st["us_min"], "us_mean": st["us_mean"],
+           "GBps": round(fbq_synth.algorithmic_bytes(N, K, r, bits, M) / us / 1e3, 1),
+           "TFLOPps": round(fbq_synth.algorithmic_flops(N, K, r, M) / us / 1e6, 2), "copies": copies, "iters": iters,
+           "batches": repeats}
+    if with_twin and r:
+        tw = timed([branch_free_twin(l) for l in layers])
+        out["us_branch_free"] = tw["us_median"]
+        out["branch_overhead_pct"] = round((us / tw["us_median"] - 1) * 100, 2)
+    return out
+
+
+def time_read_stream(nbytes, iters=200, warmup=20, pool_bytes=3 << 30, repeats=3):
+    """The read-only yardstick kernel on launches of nbytes each, back to back, every launch on another part of
+    a pool no cache holds.  Returns microseconds per launch (median of the batches) and GB/s."""
+    lib = fbq.load()
+    nbytes = (int(nbytes) + 4095) // 4096 * 4096
+    pool = _read_pool(max(pool_bytes, 2 * nbytes))
+    copies = pool.numel() // nbytes
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    base = pool.data_ptr()
 
     def run(n):
         for i in range(n):
-            rc = lib.fbq_linear(*calls[i % copies])
+            rc = lib.fbq_measure_read_stream(ctypes.c_void_p(base + (i % copies) * nbytes), ctypes.c_size_t(nbytes), stream)
             if rc != 0:
-                raise RuntimeError(f"fbq_linear: {fbq.status_string(rc)}")
+                raise RuntimeError(f"fbq_measure_read_stream: {fbq.status_string(rc)}")
+    st = event_stats(run, iters, warmup, repeats)
+    return {"bytes": nbytes, "us": st["us_median"], "us_min": st["us_min"], "GBps": round(nbytes / st["us_median"] / 1e3, 1)}
 
-    run(warmup)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    run(iters)
-    e1.record()
-    torch.cuda.synchronize()
-    us = e0.elapsed_time(e1) / iters * 1e3
-    return {"N": N, "K": K, "r": r, "bits": bits, "M": M, "us": round(us, 2),
-            "GBps": round(algorithmic_bytes(N, K, r, bits, M) / us / 1e3, 1),
-            "TFLOPps": round(algorithmic_flops(N, K, r, M) / us / 1e6, 2), "copies": copies, "iters": iters}
+
+_POOL = None
+
+
+def _read_pool(nbytes):
+    global _POOL
+    if _POOL is None or _POOL.numel() < nbytes:
+        _POOL = None
+        _POOL = torch.empty(int(nbytes), dtype=torch.uint8, device="cuda")
+        _POOL.view(torch.int32).random_()
+    return _POOL
+
+
+def free_read_pool():
+    global _POOL
+    _POOL = None
 
 
 def time_train_step(N, K, r, bits, T, iters=20, warmup=3):
@@ -117,19 +184,25 @@ def time_train_step(N, K, r, bits, T, iters=20, warmup=3):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--N", type=int, required=True)
-    ap.add_argument("--K", type=int, required=True)
+    ap.add_argument("--N", type=int, default=4096)
+    ap.add_argument("--K", type=int, default=4096)
     ap.add_argument("--r", type=int, default=0)
     ap.add_argument("--bits", type=int, default=4)
     ap.add_argument("--M", type=int, default=1)
     ap.add_argument("--iters", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--train-tokens", type=int, default=0, help="time the reconstruction step on this many calibration tokens instead")
+    ap.add_argument("--graph", action="store_true", help="replay the calls from one HIP graph over all copies")
+    ap.add_argument("--twin", action="store_true", help="also time the branch-free twin (r = 0) on the same packed weights")
+    ap.add_argument("--read-bytes", type=float, default=0, help="time the read-only yardstick kernel on launches of this many bytes instead")
     a = ap.parse_args()
     if a.train_tokens:
         print(json.dumps(time_train_step(a.N, a.K, a.r, a.bits, a.train_tokens, a.iters, a.warmup)), flush=True)
         return
-    print(json.dumps(time_layer(a.N, a.K, a.r, a.bits, a.M, a.iters, a.warmup)), flush=True)
+    if a.read_bytes:
+        print(json.dumps(time_read_stream(a.read_bytes, a.iters, a.warmup)), flush=True)
+        return
+    print(json.dumps(time_layer(a.N, a.K, a.r, a.bits, a.M, a.iters, a.warmup, with_twin=a.twin, graph=a.graph)), flush=True)
 
 
 if __name__ == "__main__":
