@@ -156,8 +156,7 @@ fbq_status check_layer(const fbq_desc *d, int M, const void *x, const void *qwei
 
 static hipError_t launch_prefill(const LinearArgs &a, hipStream_t s)
 {
-    hipError_t e = launch_arrange_x_prefill(a, s);
-    if (e == hipSuccess && a.r > 0) e = launch_down_proj_prefill(a, s);
+    hipError_t e = launch_prepass_prefill(a, s);
     if (e == hipSuccess) e = launch_gemm_prefill(a, s);
     return e;
 }

@@ -52,8 +52,7 @@ hipError_t launch_gemv_decode(const LinearArgs *layers, int n_layers, hipStream_
 bool decode_group_compatible(const LinearArgs &a, const LinearArgs &b);
 hipError_t launch_gemv_small_m(const LinearArgs *layers, int n_layers, hipStream_t stream);
 bool small_m_group_compatible(const LinearArgs &a, const LinearArgs &b);
-hipError_t launch_arrange_x_prefill(const LinearArgs &a, hipStream_t stream);
-hipError_t launch_down_proj_prefill(const LinearArgs &a, hipStream_t stream);
+hipError_t launch_prepass_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream);
 hipError_t launch_unpack(const fbq_desc &d, const uint32_t *qw, uint8_t *codes, hipStream_t stream);
 hipError_t launch_reconstruct(const fbq_desc &d, const uint32_t *qw, const uint16_t *scales, const uint16_t *zeros,

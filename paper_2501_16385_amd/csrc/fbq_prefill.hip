@@ -1,18 +1,23 @@
-// Prefill path (M > 16 tokens): the fused kernel of Sec. 4.3 as an fp16 MFMA GEMM for gfx950.
+// Prefill path (more than 64 tokens): the fused kernel of Sec. 4.3 as an fp16 MFMA GEMM for gfx950.
 //
 //   y[M,N] = x[M,K] . Wq[N,K]^T + t[M,r] . B[r,N],   t = x . A
 //
-// Two launches: the down-projection t = x.A (a small MFMA GEMM, "requires relatively minimal time"
-// in the paper's words) and the fused kernel, which de-quantizes in registers, multiplies on the
-// matrix cores and folds the up-projection into the same accumulators as 2r extra K columns, so y
-// is written once.
+// Three launches (two without a sub-branch): the down-projection t = x.A as a small MFMA GEMM over K slices
+// ("requires relatively minimal time" in the paper's words; its blocks also write the re-ordered copy of x the
+// fused kernel wants), the slices' sums as t_hi | t_lo, and the fused kernel, which de-quantizes in registers,
+// multiplies on the matrix cores and folds the up-projection into the same accumulators as 2r extra K columns,
+// so y is written once.  Three super-steps of K are under way at any time (one multiplied, two on their way from
+// memory).  Tiles are 64, 96 or 128 rows high, whichever fills the compute units most evenly; a layer with at
+// most one tile per CU runs blocks of eight waves, two groups that split K and meet in LDS; only a layer with
+// fewer tiles than half the CUs (256 tokens into a few thousand outputs) still splits K over blocks, through fp32
+// partial results and a small summing launch.
 //
-// Fused kernel.  Block = 4 waves side by side along N; block tile (32 TM) x 256 (TM = 4, or 2 when
-// that is needed to give every CU a block); a wave owns TM x 2 tiles of v_mfma_f32_32x32x16_f16.
+// Fused kernel.  Block = 4 waves (or two groups of 4) side by side along N; block tile (32 TM) x 256, TM = 2, 3
+// or 4; a wave owns TM x 2 tiles of v_mfma_f32_32x32x16_f16.
 // K advances in super-steps of 128 (one quantization group):
 //   * activations: a small pre-pass rewrites x once into the order the kernel wants (see below);
 //     from there a (32 TM) x 128 fp16 tile per super-step is copied straight into LDS by
-//     global_load_lds_dwordx4 (no registers, double buffered); every wave reads all of it
+//     global_load_lds_dwordx4 (no registers, three buffers); every wave reads all of it
 //     (TM fragments per K step of 16);
 //   * weights never touch LDS: lane (n = lane % 32, h = lane / 32) loads, for each half c of the
 //     super-step, the 32 codes k = 128u + 64c + 32h .. +31 of row n (INT4: one 16-byte load, INT3:
@@ -29,6 +34,9 @@
 // The sub-branch enters as t = t_hi + t_lo (two fp16 halves, ~22 bits) against B^T rows.
 #include <hip/hip_fp16.h>
 
+#include <cstdlib>
+#include <type_traits>
+
 #include "fbq_internal.h"
 
 namespace fbq {
@@ -37,6 +45,8 @@ typedef _Float16 half_t;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t uint4v_t __attribute__((ext_vector_type(4)));
+typedef uint32_t uint3v_t __attribute__((ext_vector_type(3)));
 
 constexpr int kTN = 2;               // 32-column MFMA tiles per wave along N
 constexpr int kWavesN = 4;           // waves per block, side by side along N
@@ -44,7 +54,8 @@ constexpr int kBN = kWavesN * kTN * 32;   // 256
 constexpr int kBK = 128;             // K per super-step: one quantization group
 constexpr int kLdsRow = 256;         // bytes per activation row in LDS: 16 chunks of 8 fp16, chunk l at l ^ (m % 16)
 constexpr int kXcds = 8;             // accelerator dies, each with its own L2
-constexpr int kRowPad = 128;         // the arranged copy of x has its row count rounded up to this
+constexpr int kStages = 3;           // super-steps in flight: the one worked on and the next two on their way from memory
+constexpr int kRowPad = 128;         // the arranged copy of x has its row count rounded up to this, plus one more (a 96-row tiling overshoots a multiple of 128)
 
 __device__ __forceinline__ half2_t h2_of(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
 __device__ __forceinline__ half2_t h2_splat(half_t v) { return half2_t{v, v}; }
@@ -60,7 +71,10 @@ struct PrefillParams {
     int M, N, K, r;
     int row_words, G;
     int row_blocks;        // ceil(M / block tile rows)
-    int ksplit;            // blocks that split K for the same tile (1: none)
+    int full_slots;        // tiles per XCD that belong to column blocks this XCD has to itself: (column blocks / 8) * row_blocks
+    int full_cols;         // column blocks dealt out whole, eight at a time: (column blocks / 8) * 8
+    int rem_tiles;         // tiles of the column blocks left over, dealt out singly over the XCDs
+    int ksplit;            // blocks that split K for the same tile (1: none; more only where there are too few tiles for half the CUs)
     float *ypart;          // ksplit > 1 only: [ksplit][M][N] fp32 partial results, added up by fbq_sum_parts_kernel
 };
 
@@ -84,15 +98,16 @@ struct WeightRegs {
     static constexpr int kWords = BITS == 4 ? 4 : 3;
     uint32_t w[kWords];
 
-    // block index b = k / 32 of the row
-    __device__ __forceinline__ void load(const uint32_t *row, int b)
+    // The 32 codes at byte offset `off` of the packed buffer: exactly one load instruction (the kernel counts the
+    // loads it has in flight).
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t qbuf, int off)
     {
-        const uint32_t *p = row + b * kWords;
-        if (BITS == 4) {
-            const uint4 q = *reinterpret_cast<const uint4 *>(p);
+        if constexpr (BITS == 4) {
+            const uint4v_t q = __builtin_amdgcn_raw_buffer_load_b128(qbuf, off, 0, 0);
             w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
         } else {
-            w[0] = p[0]; w[1] = p[1]; w[2] = p[2];
+            const uint3v_t q = __builtin_amdgcn_raw_buffer_load_b96(qbuf, off, 0, 0);
+            w[0] = q.x; w[1] = q.y; w[2] = q.z;
         }
     }
 
@@ -167,36 +182,53 @@ __device__ __forceinline__ half8_t pack8(half2_t a, half2_t b, half2_t c, half2_
     return half8_t{a.x, a.y, b.x, b.y, c.x, c.y, d.x, d.y};
 }
 
-template <int BITS, int TM>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void fbq_gemm_kernel(const PrefillParams p)
+// KG: groups of four waves that split K for the same tile inside one block (1 or 2).  A layer with too few tiles
+// to give every CU two blocks of four waves runs one block of eight waves per CU instead: the groups take
+// alternate halves of K and group 1 hands its accumulators to group 0 through LDS at the end, so nothing but y
+// is ever written.
+// PAIRS: the number of groups per row is even, so scale and zero of two consecutive super-steps are one aligned dword.
+template <int BITS, int TM, int KG, bool PAIRS>
+__global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))) void fbq_gemm_kernel(const PrefillParams p)
 {
     constexpr int kBM = 32 * TM;
     constexpr int kCopies = kBM / 16;                   // 1 KiB wave copies (4 rows each) per wave and super-step
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[2][kBM * kLdsRow];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_all[KG][kStages][kBM * kLdsRow];
+    static_assert(sizeof(lds_all) <= 160 * 1024, "a block's activation buffers must fit the CU's LDS");
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int kg = __builtin_amdgcn_readfirstlane(tid >> 8);       // K group of this wave
+    const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // its position along N
     const int col = lane & 31, h = lane >> 5;
     // Workgroups go to the eight XCDs round-robin by linear id, and each XCD has its own L2.  Give
     // every XCD its own column blocks (all row blocks of one column block run on the same XCD, one
     // after the other in id order), so that a weight tile is fetched into one L2 only.
     // Where a launch would have fewer blocks than the CUs can hold, ksplit blocks share a tile and split
     // K; their fp32 partial results are added by a small launch afterwards.
+    // Column blocks are dealt out whole, eight at a time; the tiles of the ones left over (fewer than eight) go to
+    // the XCDs one by one, so that every XCD has the same number of tiles whatever the column count.
     const int xcd = blockIdx.x % kXcds, slot = (blockIdx.x / kXcds) / p.ksplit, part = (blockIdx.x / kXcds) % p.ksplit;
-    const int bm = slot % p.row_blocks, bn = (slot / p.row_blocks) * kXcds + xcd;
-    if (bn * kBN >= p.N) return;                        // block-uniform
+    int bm, bn;
+    if (slot < p.full_slots) {
+        bm = slot % p.row_blocks;
+        bn = (slot / p.row_blocks) * kXcds + xcd;
+    } else {
+        const int q = (slot - p.full_slots) * kXcds + xcd;
+        if (q >= p.rem_tiles) return;                   // block-uniform
+        bm = q % p.row_blocks;
+        bn = p.full_cols + q / p.row_blocks;
+    }
     const int m0 = bm * kBM;
     const int nw = bn * kBN + wave * (kTN * 32);
-    const int U_all = p.K / kBK, U_part = (U_all + p.ksplit - 1) / p.ksplit;
-    const int u0 = part * U_part, U = min(U_all, u0 + U_part);   // this block's super-steps: u0 .. U - 1
+    const int U_all = p.K / kBK;
+    const int shares = KG * p.ksplit;                   // K is shared out over the groups of a block and, for a layer with very few tiles, over blocks
+    int U_part = (U_all + shares - 1) / shares;
+    if (PAIRS) U_part = (U_part + 1) & ~1;              // an even first super-step: scale and zero come in pairs
+    const int u0 = (part * KG + kg) * U_part, U = min(U_all, u0 + U_part);   // this group's super-steps: u0 .. U - 1 (at most U_part)
 
     // this lane's weight rows (clamped: columns past N are computed on a valid row and never stored)
-    const uint32_t *wrow[kTN];
     int nrow[kTN];
 #pragma unroll
-    for (int tn = 0; tn < kTN; ++tn) {
-        nrow[tn] = min(nw + tn * 32 + col, p.N - 1);
-        wrow[tn] = p.qw + (size_t)nrow[tn] * p.row_words;
-    }
+    for (int tn = 0; tn < kTN; ++tn) nrow[tn] = min(nw + tn * 32 + col, p.N - 1);
 
     // activation tile: wave w copies rows [w kBM/4, (w+1) kBM/4) of the tile, four rows (1 KiB) per
     // instruction; lane l moves chunk l % 16 of row l / 16 and the hardware puts it at LDS base + 16 l.
@@ -205,7 +237,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int j = 0; j < kCopies; ++j)
             __builtin_amdgcn_global_load_lds(xsrc + (size_t)(4 * j) * p.K + u * kBK,
-                                             (__attribute__((address_space(3))) void *)&lds[buf][(wave * (kBM / 4) + 4 * j) * kLdsRow],
+                                             (__attribute__((address_space(3))) void *)&lds_all[kg][buf][(wave * (kBM / 4) + 4 * j) * kLdsRow],
                                              16, 0, 0);
     };
     // this lane's fragment address within a tile for K step 0 of row block 0; K step s = 4 c + i is
@@ -220,32 +252,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.0f;
 
-    // weights, scale and zero of one super-step: two code blocks (k halves) per N tile
+    // The packed words of one super-step (two code blocks, the k halves, per N tile), and scale and zero: fp16 bits,
+    // one per register.  Scale and zero are 2-byte loads of 32 different rows, as expensive for the load path as the
+    // 16-byte weight loads; with an even number of groups per row the pair of an even and the following odd
+    // super-step is one aligned dword, fetched with the even step.
     struct StepRegs {
         WeightRegs<BITS> w[kTN][2];
-        uint32_t s[kTN], z[kTN];                        // fp16 bits (with an even G: of super-steps u & ~1 and u | 1)
     };
-    // Scale and zero are 2-byte loads of 32 different rows: as expensive for the load path as the 16-byte weight
-    // loads.  With an even number of groups per row the pair of an even and the following odd super-step is one
-    // aligned dword: fetched on the even step, handed on to the odd one.
-    const bool pairs = (p.G & 1) == 0;                  // block-uniform
-    auto step_load = [&](StepRegs &sr, int u, const StepRegs &before, bool has_before) __attribute__((always_inline)) {
+    struct SzRegs {
+        uint32_t s[kTN], z[kTN];
+    };
+    constexpr bool pairs = PAIRS;
+    const __amdgpu_buffer_rsrc_t qbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(p.qw), 0, (int)((size_t)p.N * p.row_words * 4), 0x00020000);
+    const int sz_bytes = (p.N * p.G * 2 + 3) & ~3;      // whole dwords: the range check is per dword
+    const __amdgpu_buffer_rsrc_t sbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(p.scales), 0, sz_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t zbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(p.zeros), 0, sz_bytes, 0x00020000);
+    int woff[kTN], goff[kTN];
+#pragma unroll
+    for (int tn = 0; tn < kTN; ++tn) {
+        woff[tn] = nrow[tn] * p.row_words * 4 + h * WeightRegs<BITS>::kWords * 4;
+        goff[tn] = nrow[tn] * p.G * 2;
+    }
+    // loads per super-step, each one instruction: the wait before a barrier names how many younger loads may stay in flight
+    constexpr int kLoadsW = kTN * 2, kLoadsSZ = kTN * 2, kLoadsX = kBM / 16;
+    auto load_weights = [&](StepRegs &sr, int u) __attribute__((always_inline)) {
+#pragma unroll
+        for (int tn = 0; tn < kTN; ++tn)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) sr.w[tn][c].load(qbuf, woff[tn] + (4 * u + 2 * c) * (WeightRegs<BITS>::kWords * 4));
+    };
+    auto load_sz_pair = [&](SzRegs &r, int u) __attribute__((always_inline)) {      // u even: the dword holds u and u + 1
 #pragma unroll
         for (int tn = 0; tn < kTN; ++tn) {
+            r.s[tn] = __builtin_amdgcn_raw_buffer_load_b32(sbuf, goff[tn] + u * 2, 0, 0);
+            r.z[tn] = __builtin_amdgcn_raw_buffer_load_b32(zbuf, goff[tn] + u * 2, 0, 0);
+        }
+    };
+    auto load_sz_single = [&](SzRegs &r, int u) __attribute__((always_inline)) {
 #pragma unroll
-            for (int c = 0; c < 2; ++c) sr.w[tn][c].load(wrow[tn], 4 * u + 2 * c + h);
-            if (pairs) {
-                if ((u & 1) && has_before) {
-                    sr.s[tn] = before.s[tn];
-                    sr.z[tn] = before.z[tn];
-                } else {
-                    sr.s[tn] = *reinterpret_cast<const uint32_t *>(p.scales + (size_t)nrow[tn] * p.G + (u & ~1));
-                    sr.z[tn] = *reinterpret_cast<const uint32_t *>(p.zeros + (size_t)nrow[tn] * p.G + (u & ~1));
-                }
-            } else {
-                sr.s[tn] = p.scales[(size_t)nrow[tn] * p.G + u];
-                sr.z[tn] = p.zeros[(size_t)nrow[tn] * p.G + u];
-            }
+        for (int tn = 0; tn < kTN; ++tn) {
+            r.s[tn] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(sbuf, goff[tn] + u * 2, 0, 0);   // (the load zero-extends)
+            r.z[tn] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(zbuf, goff[tn] + u * 2, 0, 0);
         }
     };
 
@@ -254,13 +301,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     // one super-step: eight K steps of 16 on the tile in lds[buf].  The activation fragments of K step
     // i + 1 are fetched from LDS before the matrix instructions of step i are issued.
-    auto compute = [&](const StepRegs &sr, int buf) __attribute__((always_inline)) {
-        const int half_shift = pairs ? 16 * buf : 0;     // buf is the parity of the super-step
-        const typename WeightRegs<BITS>::Affine aff[kTN] = {{(sr.s[0] >> half_shift) & 0xFFFFu, (sr.z[0] >> half_shift) & 0xFFFFu},
-                                                            {(sr.s[1] >> half_shift) & 0xFFFFu, (sr.z[1] >> half_shift) & 0xFFFFu}};
+    auto compute = [&](const StepRegs &sr, const SzRegs &q, int half_shift, int buf) __attribute__((always_inline)) {
+        const typename WeightRegs<BITS>::Affine aff[kTN] = {{(q.s[0] >> half_shift) & 0xFFFFu, (q.z[0] >> half_shift) & 0xFFFFu},
+                                                            {(q.s[1] >> half_shift) & 0xFFFFu, (q.z[1] >> half_shift) & 0xFFFFu}};
         auto a_frag = [&](int tm, int step) __attribute__((always_inline)) {
             const uint32_t off = a_lane ^ (uint32_t)((8 * (step / 4) + (step % 4)) << 4);
-            return *reinterpret_cast<const half8_t *>(&lds[buf][off + tm * (32 * kLdsRow)]);
+            return *reinterpret_cast<const half8_t *>(&lds_all[kg][buf][off + tm * (32 * kLdsRow)]);
         };
         half2_t wv3[kTN][16];                           // INT3 only
         auto b_frag = [&](int tn, int step) __attribute__((always_inline)) {
@@ -279,31 +325,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         // tile's weights of this step are de-quantized; during the second phase the first tile's
         // weights of the NEXT step are, and each activation fragment is re-read from LDS for the
         // next step right after its last use.  Vector, LDS and matrix instructions alternate, so
-        // the matrix pipe stays fed whatever the other wave of the SIMD is doing, and no operand
-        // needs a second register set.
+        // the matrix pipe stays fed whatever the other wave of the SIMD is doing.
         static_assert(kTN == 2, "the issue order below is written for two column tiles per wave");
-        constexpr int kValu = BITS == 4 ? (TM == 4 ? 4 : 7) : (TM == 4 ? 5 : 9);   // vector ops per matrix instruction
-        half8_t af[TM], b0, b1;
+        constexpr int kValu = BITS == 4 ? (TM == 4 ? 4 : TM == 3 ? 6 : 7) : (TM == 4 ? 5 : TM == 3 ? 7 : 9);   // vector ops per matrix instruction
+        // Activation fragments have two register sets: those of K step i + 1 are asked for during the FIRST phase
+        // of step i, a whole K step of matrix work before they are needed (asked for right after their last use,
+        // three matrix instructions ahead, every K step began with a wait for LDS).
+        half8_t af[2][TM], b0, b1;
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) af[tm] = a_frag(tm, 0);
+        for (int tm = 0; tm < TM; ++tm) af[0][tm] = a_frag(tm, 0);
         b0 = b_frag(0, 0);
 #pragma unroll
         for (int step = 0; step < 8; ++step) {
+            const int cur = step & 1, nxt = cur ^ 1;
             __builtin_amdgcn_sched_barrier(0);
             b1 = b_frag(1, step);
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) acc[tm][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[tm], b0, acc[tm][0], 0, 0, 0);
-#pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, kValu, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (step < 7) b0 = b_frag(0, step + 1);
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                acc[tm][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[tm], b1, acc[tm][1], 0, 0, 0);
-                if (step < 7) af[tm] = a_frag(tm, step + 1);
+                acc[tm][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][tm], b0, acc[tm][0], 0, 0, 0);
+                if (step < 7) af[nxt][tm] = a_frag(tm, step + 1);
             }
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm) {
@@ -311,26 +351,107 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x002, kValu, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            if (step < 7) b0 = b_frag(0, step + 1);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) acc[tm][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[cur][tm], b1, acc[tm][1], 0, 0, 0);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, kValu, 0);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    StepRegs cur, nxt;
-    step_load(cur, min(u0, U_all - 1), cur, false);
-    x_copy(min(u0, U_all - 1), u0 & 1);
-    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0): this wave's LDS copies have landed
-    __syncthreads();
-
-    for (int u = u0; u < U; ++u) {
-        const bool more = u + 1 < U;                    // block-uniform
-        if (more) {
-            step_load(nxt, u + 1, cur, true);
-            x_copy(u + 1, (u + 1) & 1);
+    // Three super-steps are under way at any time: the one being multiplied and the next two on their way from
+    // memory (weights into registers, activations into LDS).  One super-step of matrix work is shorter than a trip
+    // to memory, so with a single step of look-ahead every round ended in a wait of a microsecond or more.  The loop
+    // is unrolled six times so that register set (round % 3), scale/zero set and parity are compile-time: registers
+    // with a load in flight are never moved.
+    StepRegs wr[kStages];
+    SzRegs sz[kStages];
+    // The barrier alone: __syncthreads() comes with a fence that waits for every load in flight, which is exactly
+    // what the look-ahead must not do.  What has to be complete at a barrier is waited for explicitly in front of it
+    // (this wave's copies into LDS, by count); the LDS reads of the round just finished have been consumed by the
+    // matrix instructions.  The memory clobber keeps the compiler from moving LDS accesses across it.
+    auto block_barrier = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    };
+    // all loads of round `it` (super-step u0 + it); returns nothing, but every call issues exactly loads_of(it) loads
+    auto issue = [&](auto IT, int u) __attribute__((always_inline)) {
+        constexpr int it = decltype(IT)::value;
+        load_weights(wr[it % 3], u);
+        if constexpr (pairs) {
+            if constexpr ((it & 1) == 0) load_sz_pair(sz[(it / 2) % 3], u);
+        } else {
+            load_sz_single(sz[it % 3], u);
         }
-        compute(cur, u & 1);
-        if (more) cur = nxt;
-        __builtin_amdgcn_s_waitcnt(0x0F70);
+        x_copy(u, it % 3);
+    };
+    // wait until at most the loads of round `it` are in flight
+    auto wait_older_than = [&](auto IT) __attribute__((always_inline)) {
+        constexpr int it = decltype(IT)::value;
+        constexpr int n_pairs = kLoadsX + kLoadsW + ((it & 1) == 0 ? kLoadsSZ : 0), n_single = kLoadsX + kLoadsW + kLoadsSZ;
+        constexpr int n = pairs ? n_pairs : n_single;
+        __builtin_amdgcn_s_waitcnt((n & 15) | ((n >> 4) << 14) | 0x0F70);
+    };
+    // The loads of a round are issued whether or not the super-step exists (past the end: the last one again, never
+    // used): with a branch around them the compiler can no longer count the loads in flight and waits for all of them.
+    const int u_last = U_all - 1;
+    auto do_round = [&](auto IT, int i6) __attribute__((always_inline)) {
+        constexpr int it = decltype(IT)::value;           // round within the unrolled six
+        const int u = u0 + i6 + it;
+        issue(std::integral_constant<int, (it + 2) % 6>{}, min(u + 2, u_last));
+        if (u < U) compute(wr[it % 3], sz[pairs ? (it / 2) % 3 : it % 3], pairs ? 16 * (it & 1) : 0, it % 3);   // group-uniform
+        // the next round's operands must have landed (and, through the barrier, everybody's copies into LDS)
+        wait_older_than(std::integral_constant<int, (it + 2) % 6>{});
+        block_barrier();
+    };
+    issue(std::integral_constant<int, 0>{}, min(u0, u_last));
+    issue(std::integral_constant<int, 1>{}, min(u0 + 1, u_last));
+    wait_older_than(std::integral_constant<int, 1>{});
+    block_barrier();
+    // every group runs the same number of rounds so that the block's barriers match; a group whose share of K is
+    // shorter sits its last rounds out
+    for (int i6 = 0; i6 < U_part; i6 += 6) {
+        do_round(std::integral_constant<int, 0>{}, i6);
+        if (i6 + 1 >= U_part) break;
+        do_round(std::integral_constant<int, 1>{}, i6);
+        if (i6 + 2 >= U_part) break;
+        do_round(std::integral_constant<int, 2>{}, i6);
+        if (i6 + 3 >= U_part) break;
+        do_round(std::integral_constant<int, 3>{}, i6);
+        if (i6 + 4 >= U_part) break;
+        do_round(std::integral_constant<int, 4>{}, i6);
+        if (i6 + 5 >= U_part) break;
+        do_round(std::integral_constant<int, 5>{}, i6);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // the loads issued past the end have landed too: LDS is free
+    block_barrier();
+
+    // the K groups meet: group 1 leaves its accumulators in LDS (the activation buffers are free now: one wave's
+    // tiles take exactly one group's share of them), group 0 adds them to its own
+    if constexpr (KG > 1) {
+        static_assert(KG <= 2, "the hand-over below is written for two K groups");
+        static_assert(sizeof(float) * TM * kTN * 16 * 64 * kWavesN <= sizeof(lds_all), "accumulators must fit the activation buffers");
+        float *hand = reinterpret_cast<float *>(&lds_all[0][0][0]) + (size_t)wave * (TM * kTN * 16 * 64);
+        if (kg == 1) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < kTN; ++tn)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) hand[((tm * kTN + tn) * 16 + v) * 64 + lane] = acc[tm][tn][v];
+        }
         __syncthreads();
+        if (kg == 1) return;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < kTN; ++tn)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[tm][tn][v] += hand[((tm * kTN + tn) * 16 + v) * 64 + lane];
     }
 
     // up-projection: 2r extra K columns, t_hi and t_lo against the same B^T rows
@@ -371,7 +492,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
 }
 
-// y = sum of the K parts' fp32 partial results (only where K was split over blocks).
+// y = sum of the K parts' fp32 partial results (only for layers with so few tiles that K is split over blocks).
 __global__ __launch_bounds__(256) void fbq_sum_parts_kernel(const float *__restrict__ ypart, uint16_t *__restrict__ y, size_t total, int parts)
 {
     for (size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4; i < total; i += (size_t)gridDim.x * 256 * 4) {
@@ -390,37 +511,44 @@ __global__ __launch_bounds__(256) void fbq_sum_parts_kernel(const float *__restr
 // xp[m][128 u + 8 (l ^ (m % 16)) + e] = x[m][128 u + 32 (l / 4) + slot_source(8 (l % 4) + e)]
 // for chunk l = 0..15 of every 128-wide block u; one thread per 32 activations.
 template <int BITS>
+__device__ __forceinline__ void arrange_item(const uint16_t *__restrict__ x, uint16_t *__restrict__ xp, int K, int m, int b)
+{
+    const uint4 *src = reinterpret_cast<const uint4 *>(x + (size_t)m * K + b * 32);
+    half_t v[32];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint4 q = src[i];
+        const uint32_t wds[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const half2_t hh = h2_of(wds[j]);
+            v[i * 8 + j * 2] = hh.x;
+            v[i * 8 + j * 2 + 1] = hh.y;
+        }
+    }
+    uint16_t *dst = xp + (size_t)m * K + (b / 4) * 128;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        half2_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            o[j] = half2_t{v[slot_source<BITS>(i * 8 + 2 * j)], v[slot_source<BITS>(i * 8 + 2 * j + 1)]};
+        const int l = 4 * (b % 4) + i;
+        *reinterpret_cast<uint4 *>(dst + 8 * (l ^ (m & 15))) =
+            make_uint4(__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]),
+                       __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3]));
+    }
+}
+
+// The whole of x, for a layer without a sub-branch (with one, the down-projection's blocks arrange what they read).
+template <int BITS>
 __global__ __launch_bounds__(256) void fbq_arrange_x_kernel(const uint16_t *__restrict__ x, uint16_t *__restrict__ xp, int M, int K)
 {
     const int per_row = K / 32;
     const size_t total = (size_t)M * per_row;
     for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (size_t)gridDim.x * 256) {
         const int m = (int)(idx / per_row), b = (int)(idx - (size_t)m * per_row);
-        const uint4 *src = reinterpret_cast<const uint4 *>(x + (size_t)m * K + b * 32);
-        half_t v[32];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint4 q = src[i];
-            const uint32_t wds[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const half2_t hh = h2_of(wds[j]);
-                v[i * 8 + j * 2] = hh.x;
-                v[i * 8 + j * 2 + 1] = hh.y;
-            }
-        }
-        uint16_t *dst = xp + (size_t)m * K + (b / 4) * 128;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            half2_t o[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                o[j] = half2_t{v[slot_source<BITS>(i * 8 + 2 * j)], v[slot_source<BITS>(i * 8 + 2 * j + 1)]};
-            const int l = 4 * (b % 4) + i;
-            *reinterpret_cast<uint4 *>(dst + 8 * (l ^ (m & 15))) =
-                make_uint4(__builtin_bit_cast(uint32_t, o[0]), __builtin_bit_cast(uint32_t, o[1]),
-                           __builtin_bit_cast(uint32_t, o[2]), __builtin_bit_cast(uint32_t, o[3]));
-        }
+        arrange_item<BITS>(x, xp, K, m, b);
     }
 }
 
@@ -431,14 +559,22 @@ constexpr int kDownSlices = 8;       // K slices of the prefill down-projection 
 // Stage 1: partial[s][m][j] = sum over K slice s of x[m][k] * At[j][k], for one 32-row tile of tokens
 // and all r columns; the block's four waves take a quarter of the slice each and add their tiles up
 // through LDS in wave order.  RT = 32-column tiles (r <= 32 * RT).
-template <int RT>
+// The block also writes the arranged copy of the activations it reads (its 32 rows, its K slice): one pass over x
+// serves both, and the re-ordering needs no launch of its own.
+template <int BITS, int RT>
 __global__ __launch_bounds__(256) void fbq_down_proj_prefill_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ At,
-                                                                    float *__restrict__ partial, int M, int K, int r, int kslice)
+                                                                    float *__restrict__ partial, uint16_t *__restrict__ xp, int M, int K,
+                                                                    int r, int kslice)
 {
     extern __shared__ float sum[];                      // [32][32 * RT]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, h = lane >> 5;
     const int m0 = blockIdx.x * 32;
+    {
+        const int b0 = blockIdx.y * (kslice / 32), nb = min(K / 32, b0 + kslice / 32) - b0;   // 32-wide pieces of this slice
+        const int rows = min(32, M - m0);
+        for (int idx = tid; idx < rows * nb; idx += 256) arrange_item<BITS>(x, xp, K, m0 + idx / nb, b0 + idx % nb);
+    }
     const int kq = kslice / 4;                          // a multiple of 16
     const int kbeg = blockIdx.y * kslice + wave * kq;
     const int kend = min(K, kbeg + kq);
@@ -502,21 +638,22 @@ __global__ __launch_bounds__(256) void fbq_down_proj_finish_kernel(const float *
 // workspace: the arranged copy of x ([M rounded up to kRowPad][K] fp16; rows past M are never
 // written and only feed output rows that are never stored), then [M][2r] fp16 (t_hi | t_lo), then
 // kDownSlices x [M][r] fp32 partial sums
-static size_t xp_bytes(int M, int K) { return (size_t)ceil_div(M, kRowPad) * kRowPad * K * sizeof(uint16_t); }
+static size_t xp_bytes(int M, int K) { return ((size_t)ceil_div(M, kRowPad) + 1) * kRowPad * K * sizeof(uint16_t); }
 static size_t thl_bytes(int M, int r) { return ((size_t)M * 2 * r * sizeof(uint16_t) + 255) & ~(size_t)255; }
 
 static size_t down_partial_bytes(int M, int r) { return ((size_t)kDownSlices * M * r * sizeof(float) + 255) & ~(size_t)255; }
 
-// K is split over blocks where 64-row tiles would give at most as many blocks as there are CUs (256
-// assumed: the rule must not depend on the device, the workspace is sized without one), up to four
-// ways and never below eight super-steps per block.  M * N must be a multiple of 4 for the summing
-// launch (N is even... so it is whenever N % 4 == 0 or M % 2 == 0 and N % 2 == 0; otherwise no split).
+// K is split over blocks only where 64-row tiles give at most half as many tiles as there are CUs (256 assumed: the
+// rule must not depend on the device, the workspace is sized without one): up to four ways, never below eight
+// super-steps per group of waves.  Such a layer (256 tokens into a few thousand outputs over a long K) would leave
+// most of the GPU idle otherwise; everywhere else the two groups of a block are all the split there is and nothing
+// but y is written.  M * N must be a multiple of 4 for the summing launch.
 static int ksplit_of(int M, int N, int K)
 {
-    const long blocks = (long)ceil_div(N, kBN) * ceil_div(M, 64);
-    if (blocks > 256 || ((size_t)M * N) % 4 != 0 || N % 4 != 0) return 1;
-    int split = (int)std::min<long>(4, 512 / blocks);
-    while (split > 1 && (K / kBK) / split < 8) --split;
+    const long tiles = (long)ceil_div(N, kBN) * ceil_div(M, 64);
+    if (tiles > 128 || N % 4 != 0 || (K / kBK) % 2 != 0) return 1;
+    int split = (int)std::min<long>(4, 256 / tiles);
+    while (split > 1 && (K / kBK) / (2 * split) < 8) --split;
     return std::max(1, split);
 }
 
@@ -526,17 +663,19 @@ size_t prefill_workspace_bytes(int M, int N, int K, int r)
     return xp_bytes(M, K) + thl_bytes(M, r) + down_partial_bytes(M, r) + (split > 1 ? (size_t)split * M * N * sizeof(float) : 0);
 }
 
-hipError_t launch_arrange_x_prefill(const LinearArgs &a, hipStream_t stream)
+// Before the fused kernel: x re-ordered into the workspace and, with a sub-branch, t = x.A.  With a sub-branch two
+// launches (K slices of the down-projection, whose blocks also write the re-ordered x; then the slices' sums as
+// t_hi | t_lo); without one, the re-ordering alone.
+hipError_t launch_prepass_prefill(const LinearArgs &a, hipStream_t stream)
 {
-    const size_t items = (size_t)a.M * (a.K / 32);
-    const int blocks = (int)std::min<size_t>(4096, (items + 255) / 256);
-    if (a.bits == 4) hipLaunchKernelGGL(fbq_arrange_x_kernel<4>, dim3(blocks), dim3(256), 0, stream, a.x, (uint16_t *)a.workspace, a.M, a.K);
-    else hipLaunchKernelGGL(fbq_arrange_x_kernel<3>, dim3(blocks), dim3(256), 0, stream, a.x, (uint16_t *)a.workspace, a.M, a.K);
-    return hipGetLastError();
-}
-
-hipError_t launch_down_proj_prefill(const LinearArgs &a, hipStream_t stream)
-{
+    uint16_t *xp = (uint16_t *)a.workspace;
+    if (a.r == 0) {
+        const size_t items = (size_t)a.M * (a.K / 32);
+        const int blocks = (int)std::min<size_t>(4096, (items + 255) / 256);
+        if (a.bits == 4) hipLaunchKernelGGL(fbq_arrange_x_kernel<4>, dim3(blocks), dim3(256), 0, stream, a.x, xp, a.M, a.K);
+        else hipLaunchKernelGGL(fbq_arrange_x_kernel<3>, dim3(blocks), dim3(256), 0, stream, a.x, xp, a.M, a.K);
+        return hipGetLastError();
+    }
     // K slices: multiples of 64 so that each wave's quarter is a whole number of 16-wide K steps
     const int kslice = ceil_div(ceil_div(a.K, kDownSlices), 64) * 64;
     const int slices = ceil_div(a.K, kslice);
@@ -544,10 +683,13 @@ hipError_t launch_down_proj_prefill(const LinearArgs &a, hipStream_t stream)
     const int rt = ceil_div(a.r, 32);
     uint16_t *thl = (uint16_t *)((char *)a.workspace + xp_bytes(a.M, a.K));
     float *partial = (float *)((char *)thl + thl_bytes(a.M, a.r));
-    if (rt <= 1) hipLaunchKernelGGL(fbq_down_proj_prefill_kernel<1>, grid, dim3(256), 32 * 32 * sizeof(float), stream, a.x, a.At, partial, a.M, a.K, a.r, kslice);
-    else if (rt <= 2) hipLaunchKernelGGL(fbq_down_proj_prefill_kernel<2>, grid, dim3(256), 32 * 64 * sizeof(float), stream, a.x, a.At, partial, a.M, a.K, a.r, kslice);
-    else if (rt <= 4) hipLaunchKernelGGL(fbq_down_proj_prefill_kernel<4>, grid, dim3(256), 32 * 128 * sizeof(float), stream, a.x, a.At, partial, a.M, a.K, a.r, kslice);
-    else hipLaunchKernelGGL(fbq_down_proj_prefill_kernel<8>, grid, dim3(256), 32 * 256 * sizeof(float), stream, a.x, a.At, partial, a.M, a.K, a.r, kslice);
+#define FBQ_DOWN(B, R) hipLaunchKernelGGL((fbq_down_proj_prefill_kernel<B, R>), grid, dim3(256), 32 * 32 * R * sizeof(float), stream, a.x, a.At, partial, xp, a.M, a.K, a.r, kslice)
+    if (a.bits == 4) {
+        if (rt <= 1) FBQ_DOWN(4, 1); else if (rt <= 2) FBQ_DOWN(4, 2); else if (rt <= 4) FBQ_DOWN(4, 4); else FBQ_DOWN(4, 8);
+    } else {
+        if (rt <= 1) FBQ_DOWN(3, 1); else if (rt <= 2) FBQ_DOWN(3, 2); else if (rt <= 4) FBQ_DOWN(3, 4); else FBQ_DOWN(3, 8);
+    }
+#undef FBQ_DOWN
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int blocks = std::min(1024, ceil_div(a.M * a.r, 256));
@@ -575,20 +717,55 @@ hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream)
     p.M = a.M; p.N = a.N; p.K = a.K; p.r = a.r;
     p.row_words = (int)row_words(a.K, a.bits);
     p.G = a.K / kGroup;
-    // 128-row tiles amortise the de-quantization best; 64-row tiles when 128 would leave CUs without a block
+    // Tile height: 128 rows amortise the de-quantization best, but what counts is how evenly the tiles fill the
+    // compute units; with at most one tile per CU the block has eight waves, two groups that split K.
     const int nb = ceil_div(a.N, kBN);
-    const bool tall = (long)nb * ceil_div(a.M, 128) >= prefill_cu_count() || a.M <= 64;
-    p.row_blocks = ceil_div(a.M, tall ? 128 : 64);
-    p.ksplit = tall ? 1 : ksplit_of(a.M, a.N, a.K);
-    p.ypart = (float *)((char *)a.workspace + xp_bytes(a.M, a.K) + thl_bytes(a.M, a.r) + down_partial_bytes(a.M, a.r));
-    const dim3 grid(kXcds * ceil_div(nb, kXcds) * p.row_blocks * p.ksplit);
-    if (a.bits == 4) {
-        if (tall) hipLaunchKernelGGL((fbq_gemm_kernel<4, 4>), grid, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((fbq_gemm_kernel<4, 2>), grid, dim3(256), 0, stream, p);
-    } else {
-        if (tall) hipLaunchKernelGGL((fbq_gemm_kernel<3, 4>), grid, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((fbq_gemm_kernel<3, 2>), grid, dim3(256), 0, stream, p);
+    int tm = 4, kg = 1;
+    {
+        static const int env_tm = getenv("FBQ_TM") ? atoi(getenv("FBQ_TM")) : 0;
+        static const int env_kg = getenv("FBQ_KG") ? atoi(getenv("FBQ_KG")) : 0;
+        const int cus = prefill_cu_count();
+        double best = 1e30;
+        for (int t = 4; t >= 2; --t) {
+            const long blocks = (long)nb * ceil_div(a.M, 32 * t);
+            const double rounds = blocks <= cus ? 0.55 : (double)ceil_div((int)blocks, 2 * cus);   // a block alone on its CU runs faster
+            const double cost = rounds * (t + 0.65);
+            if (cost < best - 1e-9) { best = cost; tm = t; }
+        }
+        if (env_tm) tm = env_tm;
+        kg = (long)nb * ceil_div(a.M, 32 * tm) <= cus && a.K / kBK >= 16 ? 2 : 1;
+        if (env_kg) kg = env_kg;
+        if (tm == 4) kg = 1;                            // two groups' buffers of 128 rows would not fit the LDS
+        if (p.G & 1) { tm = 2; kg = 1; }
     }
+    p.ksplit = ksplit_of(a.M, a.N, a.K);
+    if (p.ksplit > 1) { tm = 2; kg = 2; }
+    p.ypart = (float *)((char *)a.workspace + xp_bytes(a.M, a.K) + thl_bytes(a.M, a.r) + down_partial_bytes(a.M, a.r));
+    p.row_blocks = ceil_div(a.M, 32 * tm);
+    p.full_cols = (nb / kXcds) * kXcds;
+    p.full_slots = (nb / kXcds) * p.row_blocks;
+    p.rem_tiles = (nb % kXcds) * p.row_blocks;
+    const dim3 grid(kXcds * (p.full_slots + ceil_div(p.rem_tiles, kXcds)) * p.ksplit);
+    const dim3 block(256 * kg);
+#define FBQ_GEMM(B, T, G, P) hipLaunchKernelGGL((fbq_gemm_kernel<B, T, G, P>), grid, block, 0, stream, p)
+    if (p.G & 1) {                                      // odd group count (no benchmark shape): one plain variant
+        if (a.bits == 4) FBQ_GEMM(4, 2, 1, false);
+        else FBQ_GEMM(3, 2, 1, false);
+        return hipGetLastError();
+    }
+    switch ((a.bits == 4 ? 100 : 0) + tm * 10 + kg) {
+    case 141: FBQ_GEMM(4, 4, 1, true); break;
+    case 131: FBQ_GEMM(4, 3, 1, true); break;
+    case 132: FBQ_GEMM(4, 3, 2, true); break;
+    case 121: FBQ_GEMM(4, 2, 1, true); break;
+    case 122: FBQ_GEMM(4, 2, 2, true); break;
+    case 41: FBQ_GEMM(3, 4, 1, true); break;
+    case 31: FBQ_GEMM(3, 3, 1, true); break;
+    case 32: FBQ_GEMM(3, 3, 2, true); break;
+    case 21: FBQ_GEMM(3, 2, 1, true); break;
+    default: FBQ_GEMM(3, 2, 2, true); break;
+    }
+#undef FBQ_GEMM
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && p.ksplit > 1) {
         const size_t total = (size_t)a.M * a.N;

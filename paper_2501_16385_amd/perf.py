@@ -192,6 +192,7 @@ def main():
     ap.add_argument("--iters", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--train-tokens", type=int, default=0, help="time the reconstruction step on this many calibration tokens instead")
+    ap.add_argument("--rotate-bytes", type=float, default=1.0e9, help="distinct copies of the layer rotate over at least this many bytes")
     ap.add_argument("--graph", action="store_true", help="replay the calls from one HIP graph over all copies")
     ap.add_argument("--twin", action="store_true", help="also time the branch-free twin (r = 0) on the same packed weights")
     ap.add_argument("--read-bytes", type=float, default=0, help="time the read-only yardstick kernel on launches of this many bytes instead")
@@ -202,7 +203,7 @@ def main():
     if a.read_bytes:
         print(json.dumps(time_read_stream(a.read_bytes, a.iters, a.warmup)), flush=True)
         return
-    print(json.dumps(time_layer(a.N, a.K, a.r, a.bits, a.M, a.iters, a.warmup, with_twin=a.twin, graph=a.graph)), flush=True)
+    print(json.dumps(time_layer(a.N, a.K, a.r, a.bits, a.M, a.iters, a.warmup, rotate_bytes=a.rotate_bytes, with_twin=a.twin, graph=a.graph)), flush=True)
 
 
 if __name__ == "__main__":
