@@ -2,9 +2,10 @@
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
 benchmark's cpu_baseline leg.  The product never imports this module and this
-module never imports the product.  Argument marshalling only; every number is
+module never imports the product.  Argument marshalling only: every number is
 computed by the C file, whose header states what is computed and how it is
-pinned.
+pinned - with one exception, `gram` (H = X^T X), which is the plain numpy
+product written out here.
 """
 from __future__ import annotations
 

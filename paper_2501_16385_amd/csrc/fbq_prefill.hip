@@ -34,7 +34,6 @@
 // The sub-branch enters as t = t_hi + t_lo (two fp16 halves, ~22 bits) against B^T rows.
 #include <hip/hip_fp16.h>
 
-#include <cstdlib>
 #include <type_traits>
 
 #include "fbq_internal.h"
@@ -722,8 +721,6 @@ hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream)
     const int nb = ceil_div(a.N, kBN);
     int tm = 4, kg = 1;
     {
-        static const int env_tm = getenv("FBQ_TM") ? atoi(getenv("FBQ_TM")) : 0;
-        static const int env_kg = getenv("FBQ_KG") ? atoi(getenv("FBQ_KG")) : 0;
         const int cus = prefill_cu_count();
         double best = 1e30;
         for (int t = 4; t >= 2; --t) {
@@ -732,9 +729,7 @@ hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream)
             const double cost = rounds * (t + 0.65);
             if (cost < best - 1e-9) { best = cost; tm = t; }
         }
-        if (env_tm) tm = env_tm;
         kg = (long)nb * ceil_div(a.M, 32 * tm) <= cus && a.K / kBK >= 16 ? 2 : 1;
-        if (env_kg) kg = env_kg;
         if (tm == 4) kg = 1;                            // two groups' buffers of 128 rows would not fit the LDS
         if (p.G & 1) { tm = 2; kg = 1; }
     }

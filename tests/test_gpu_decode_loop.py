@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import fbq_synth
-from helpers import make_oracle_layer, oracle_y, rel_l2, to_device_layer
+from helpers import assert_matches_oracle, make_oracle_layer, oracle_y, to_device_layer
 
 pytestmark = pytest.mark.gpu
 
@@ -45,8 +45,7 @@ def test_decoder_stack_linears_match_oracle_and_graph_replays_are_exact(bits, ba
         inputs = {"q": b["x_in"], "k": b["x_in"], "v": b["x_in"], "o": b["v"], "gate": b["h"], "up": b["h"], "down": b["act"]}
         for n in NAMES:
             want = oracle_y(oracle_layers[li][n], host(inputs[n]))
-            err = rel_l2(host(b[n]), want)
-            assert err <= Y_TOL, f"layer {li} {n}: rel L2 {err:.3e}"
+            assert_matches_oracle(host(b[n]), want, f"layer {li} {n}", tol=Y_TOL)
 
     # graph replays, with eager work and synchronisation between them, reproduce the eager pass bit for bit
     graph = stack.capture()

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import fbq_synth
-from helpers import gpu_y, make_oracle_layer, oracle_y, rel_l2, to_device_layer
+from helpers import assert_matches_oracle, gpu_y, make_oracle_layer, oracle_y, rel_l2, to_device_layer
 from oracle import fbq_oracle as orc
 
 pytestmark = pytest.mark.gpu
@@ -84,11 +84,8 @@ def test_decode_linear_matches_oracle(bits, N, K, r, M):
     dev = to_device_layer(L)
     got = gpu_y(dev, x)
     assert got.shape == (M, N) and np.all(np.isfinite(got))
-    err = rel_l2(got, want)
-    assert err <= Y_TOL, f"rel L2 {err:.3e}"
-    # per-token bound too, so that one bad row of a batch cannot hide
-    for m in range(M):
-        assert rel_l2(got[m], want[m]) <= Y_TOL
+    # layer norm, per-token norm (one bad row of a batch cannot hide) and every single output
+    assert_matches_oracle(got, want, f"{N}x{K} r={r} M={M}", tol=Y_TOL)
     # same launch twice: bit-identical (no races, no uninitialised scratch)
     assert np.array_equal(gpu_y(dev, x), got)
 
@@ -135,8 +132,7 @@ def test_benchmark_layers_full_size(config):
         seen.add((spec.N, spec.K))
         L = make_oracle_layer(spec, config=config, layer_index=li)
         x = fbq_synth.make_x(spec, Ms[0], config, li)
-        err = rel_l2(gpu_y(to_device_layer(L), x), oracle_y(L, x))
-        assert err <= Y_TOL, f"{spec.name}: rel L2 {err:.3e}"
+        assert_matches_oracle(gpu_y(to_device_layer(L), x), oracle_y(L, x), spec.name, tol=Y_TOL)
 
 
 def test_int3_llama_shapes_every_token_count_sampled_rows():
@@ -159,9 +155,7 @@ def test_int3_llama_shapes_every_token_count_sampled_rows():
         for M in Ms:
             got = gpu_y(dev, np.ascontiguousarray(x[:M]))
             assert got.shape == (M, spec.N) and np.all(np.isfinite(got))
-            for m in range(M):
-                err = rel_l2(got[m, rows], want[m])
-                assert err <= Y_TOL, f"{spec.name}, M={M}, token {m}: rel L2 {err:.3e}"
+            assert_matches_oracle(got[:, rows], want[:M], f"{spec.name}, M={M}", tol=Y_TOL)
 
 
 @pytest.mark.parametrize("bits", [4, 3])
@@ -182,10 +176,41 @@ def test_large_layer_sweep_sampled_rows(bits, N, K):
     for M in (1, 16, 256):
         got = gpu_y(dev, np.ascontiguousarray(x[:M]))
         assert got.shape == (M, N) and np.all(np.isfinite(got))
-        err = rel_l2(got[:, rows], want[:M])
-        assert err <= Y_TOL, f"M={M}: rel L2 {err:.3e}"
-        worst = max(rel_l2(got[m, rows], want[m]) for m in range(M))
-        assert worst <= 2 * Y_TOL, f"M={M}: worst token rel L2 {worst:.3e}"
+        assert_matches_oracle(got[:, rows], want[:M], f"M={M}", tol=Y_TOL)
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_large_layer_through_the_feedback_quantizer(bits):
+    """The 5120 -> 13824 layer of the large-layer sweep built the way the benchmark states it: W ~ N(0, 0.015) with 1 %
+    outliers x10, rank-128 branch, through the GPU feedback quantizer.  The oracle quantizes 64 sampled rows itself
+    (codes may differ from the GPU's only on near-ties, by exactly one step) and recomputes those rows of y from the
+    GPU's own codes at 1, 16 and 256 tokens."""
+    import torch
+    import paper_2501_16385_amd as fbq
+    N, K, r = 13824, 5120, 128
+    spec = spec_of(N, K, r, bits, w_std=0.015)
+    W = fbq_synth.make_weight(spec, 4, 10 + bits)
+    A, B = fbq_synth.make_branch(spec, 4, 10 + bits)
+    x = fbq_synth.make_x(spec, 256, 4, 10 + bits)
+    t16 = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+    dev = fbq.quantize_feedback(fbq.Desc(N, K, r, bits), t16(W), t16(A.T), t16(B.T))
+    torch.cuda.synchronize()
+    rng = np.random.Generator(np.random.Philox(37 + bits))
+    rows = np.sort(rng.choice(N, 64, replace=False))
+    rows_d = torch.from_numpy(rows).cuda()
+    codes = fbq.unpack_codes(dev)[rows_d].cpu().numpy()
+    s = dev.scales[rows_d].cpu().numpy().view(np.float16)
+    z = dev.zeros[rows_d].cpu().numpy().view(np.float16)
+    Brows = np.ascontiguousarray(B[:, rows])
+    want_codes, want_s, want_z = orc.quantize(np.ascontiguousarray(W[rows]), A, Brows, bits, spec.group)
+    assert np.array_equal(s, want_s) and np.array_equal(z, want_z)
+    diff = codes.astype(np.int16) - want_codes.astype(np.int16)
+    assert np.mean(diff != 0) <= 1e-4 and np.all(np.abs(diff) <= 1)
+    words = orc.pack(codes, bits)
+    want = orc.linear(x, words, s, z, A, Brows, bits, spec.group)
+    for M in (1, 16, 256):
+        got = gpu_y(dev, np.ascontiguousarray(x[:M]))
+        assert_matches_oracle(got[:, rows], want[:M], f"M={M}", tol=Y_TOL)
 
 
 # ------------------------------------------------------------------ reconstruct / quantize
@@ -222,8 +247,13 @@ def test_gpu_feedback_quantizer_matches_oracle(bits, N, K, r):
     assert np.array_equal(dev.scales.cpu().numpy().view(np.float16), L.scales)
     assert np.array_equal(dev.zeros.cpu().numpy().view(np.float16), L.zeros)
     diff = codes.astype(np.int16) - L.codes.astype(np.int16)
-    assert np.mean(diff != 0) <= 1e-4 and np.all(np.abs(diff) <= 1)
-    assert np.array_equal(dev.qweight.cpu().numpy().view(np.uint32), L.words) or np.mean(diff != 0) > 0
+    assert np.mean(diff != 0) <= 1e-4 and np.all(np.abs(diff) <= 1)     # only a near-tie of the rounding can differ, by one step
+    if not np.any(diff):
+        assert np.array_equal(dev.qweight.cpu().numpy().view(np.uint32), L.words)
+    # Sec. 4.1 on what the GPU itself produced: |W - W_F| <= s/2 with the GPU's codes, scales and zeros
+    WF = fbq.reconstruct(dev).cpu().numpy().astype(np.float64)
+    half = np.repeat(dev.scales.cpu().numpy().view(np.float16).astype(np.float64), 128, axis=1) / 2
+    assert np.all(np.abs(L.W.astype(np.float64) - WF) <= half * (1 + 1e-3))
 
 
 # ------------------------------------------------------------------ grouped launches, graph replay
@@ -249,7 +279,7 @@ def test_group_call_equals_single_calls(bits, M):
     for L, dev, x_np, y in zip(Ls, devs, xs_np, ys):
         single = gpu_y(dev, x_np)
         assert np.array_equal(y.cpu().numpy(), single)
-        assert rel_l2(y.cpu().numpy(), oracle_y(L, x_np)) <= Y_TOL
+        assert_matches_oracle(y.cpu().numpy(), oracle_y(L, x_np), "grouped call", tol=Y_TOL)
 
 
 @pytest.mark.parametrize("bits", [4, 3])
@@ -266,7 +296,7 @@ def test_group_of_wide_layers_four_tiles_per_block(bits):
     torch.cuda.synchronize()
     for L, dev, y in zip(Ls, devs, ys):
         assert np.array_equal(y.cpu().numpy(), gpu_y(dev, x_np))
-        assert rel_l2(y.cpu().numpy(), oracle_y(L, x_np)) <= Y_TOL
+        assert_matches_oracle(y.cpu().numpy(), oracle_y(L, x_np), "grouped call", tol=Y_TOL)
 
 
 def test_group_rejects_a_bad_layer_before_launching_any():
@@ -311,7 +341,7 @@ def test_replayed_graph_follows_new_activations(bits, M):
         graph.replay()
         torch.cuda.synchronize()
         got = y.cpu().numpy()
-        assert rel_l2(got, oracle_y(L, x_np)) <= Y_TOL, f"replay {rep}"
+        assert_matches_oracle(got, oracle_y(L, x_np), f"replay {rep}", tol=Y_TOL)
         assert np.array_equal(got, gpu_y(dev, x_np))                       # and equals an eager launch
 
 
@@ -333,7 +363,7 @@ def test_fallback_when_the_down_projection_never_arrives(bits, N, K, r, M):
         torch.cuda.synchronize()
     finally:
         assert fbq.load().fbq_test_set_spin_limit(before) == -1
-    assert rel_l2(got, oracle_y(L, x)) <= Y_TOL
+    assert_matches_oracle(got, oracle_y(L, x), "fall-back path", tol=Y_TOL)
 
 
 # ------------------------------------------------------------------ prefill (fp16 MFMA GEMM, M > 16)
@@ -360,10 +390,7 @@ def test_prefill_linear_matches_oracle(bits, N, K, r, M):
     dev = to_device_layer(L)
     got = gpu_y(dev, x)
     assert got.shape == (M, N) and np.all(np.isfinite(got))
-    err = rel_l2(got, want)
-    assert err <= Y_TOL, f"rel L2 {err:.3e}"
-    worst = max(rel_l2(got[m], want[m]) for m in range(M))
-    assert worst <= 2 * Y_TOL, f"worst token {worst:.3e}"      # a single token's norm is a noisier yardstick
+    assert_matches_oracle(got, want, f"{N}x{K} r={r} M={M}", tol=Y_TOL)
     assert np.array_equal(gpu_y(dev, x), got)
 
 
@@ -396,6 +423,5 @@ def test_prefill_benchmark_shapes_sampled_rows():
         rows = np.sort(rng.choice(spec.N, 192, replace=False))
         want = orc.linear(x, L.words[rows], L.scales[rows], L.zeros[rows], L.A, np.ascontiguousarray(L.B[:, rows]),
                           spec.bits, spec.group)
-        err = rel_l2(got[:, rows], want)
-        assert err <= Y_TOL, f"{spec.name}: rel L2 {err:.3e}"
+        assert_matches_oracle(got[:, rows], want, spec.name, tol=Y_TOL)
         assert np.all(np.isfinite(got))

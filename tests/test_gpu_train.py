@@ -86,7 +86,8 @@ def test_train_step_matches_oracle(bits, N, K, r, T, b_zero):
         assert np.array_equal(st.layer.At.cpu().numpy().view(np.float16), want["A16"].T)
         assert np.array_equal(st.layer.Bt.cpu().numpy().view(np.float16), want["B16"].T)
         codes = fbq.unpack_codes(st.layer).cpu().numpy()
-        assert np.mean(codes != want["codes"]) <= 1e-4
+        cdiff = codes.astype(np.int16) - want["codes"].astype(np.int16)
+        assert np.mean(cdiff != 0) <= 1e-4 and np.all(np.abs(cdiff) <= 1)     # a near-tie of the rounding, one step at most
         assert np.mean(st.layer.scales.cpu().numpy().view(np.float16) != want["scales"]) <= 1e-4
         assert np.mean(st.layer.zeros.cpu().numpy().view(np.float16) != want["zeros"]) <= 1e-4
 
