@@ -448,6 +448,14 @@ def main():
             t = perf.time_layer(11008, 4096, 64, 4, m, iters=200, warmup=20, graph="auto")
             fam[name] = {"shape": "4096->11008", "us": t["us"], "us_min": t["us_min"], "GBps": t["GBps"],
                          "frac_of_hbm_peak": round(t["GBps"] / HBM_PEAK_GBS, 4)}
+        # the shape of the paper's end-to-end run (Sec. 5.3): 32 decoder layers of Llama2-7B-shaped linears, rank 128, a
+        # prompt of 256 tokens, then 64 tokens generated one by one from a HIP graph; attention and normalisation are stubs
+        from paper_2501_16385_amd import decode_loop
+        for label, rank in (("prompt256_decode64_int4_r128", 128), ("prompt256_decode64_int4_branch_free", 0)):
+            stack_layers = decode_loop.random_stack(32, 4096, 11008, rank, 4)
+            fam[label] = decode_loop.prompt_then_decode(stack_layers, 4096, 11008, 256, 64)
+            del stack_layers
+            torch.cuda.empty_cache()
         # layer-wise reconstruction (Alg. 1) on the 4096 x 4096 shape of the set, 2048 calibration tokens
         fam["reconstruction_step"] = perf.time_train_step(4096, 4096, 64, 4, 2048, iters=20, warmup=3)
         out["other_kernel_families"] = fam

@@ -12,7 +12,7 @@ Y_TOL = 1e-3          # relative L2 per linear layer, as for the single-layer te
 HIDDEN, INTER, RANK = 256, 640, 16
 
 
-@pytest.mark.parametrize("batch", [1, 5])
+@pytest.mark.parametrize("batch", [1, 5, 72])      # one row (GEMV), a few (matrix-core decode), a prompt pass (prefill GEMM)
 @pytest.mark.parametrize("bits", [4, 3])
 def test_decoder_stack_linears_match_oracle_and_graph_replays_are_exact(bits, batch):
     import torch
