@@ -107,6 +107,36 @@ def time_layer(N, K, r, bits, M, iters=100, warmup=10, rotate_bytes=1.0e9, repea
     return out
 
 
+def time_group(shapes, r, bits, M, iters=100, warmup=10, rotate_bytes=1.0e9, repeats=3):
+    """Several layers (N, K) that read the same activations, served by one fbq_linear_group call (q/k/v, gate/up):
+    the call back to back on the stream, every call on another copy of the packed layers."""
+    lib = fbq.load()
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1)
+    descs = [fbq.Desc(N, K, r, bits) for (N, K) in shapes]
+    set_bytes = sum(fbq.packed_bytes(d) for d in descs)
+    copies = max(2, int(rotate_bytes // set_bytes))
+    sets = [[random_layer(d, gen) for d in descs] for _ in range(copies)]
+    xs = {}
+    for (N, K) in shapes:
+        if K not in xs:
+            xs[K] = torch.randn(M, K, device="cuda", generator=gen).half()
+    ys = [torch.empty(M, N, dtype=torch.float16, device="cuda") for (N, K) in shapes]
+    wss = [torch.zeros(max(16, fbq.workspace_bytes(d, M)), dtype=torch.uint8, device="cuda") for d in descs]
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    arrs = [fbq.make_group(ls, [xs[K] for (_, K) in shapes], ys, wss) for ls in sets]
+
+    def run(n):
+        for i in range(n):
+            rc = lib.fbq_linear_group(arrs[i % copies], len(shapes), M, stream)
+            if rc != 0:
+                raise RuntimeError(f"fbq_linear_group: {fbq.status_string(rc)}")
+    st = event_stats(run, iters, warmup, repeats)
+    nbytes = sum(fbq_synth.algorithmic_bytes(N, K, r, bits, M) for (N, K) in shapes)
+    return {"layers": [f"{K}->{N}" for (N, K) in shapes], "r": r, "bits": bits, "M": M, "us": st["us_median"], "us_min": st["us_min"],
+            "bytes": nbytes, "GBps": round(nbytes / st["us_median"] / 1e3, 1), "copies": copies, "iters": iters}
+
+
 def time_read_stream(nbytes, iters=200, warmup=20, pool_bytes=3 << 30, repeats=3):
     """The read-only yardstick kernel on launches of nbytes each, back to back, every launch on another part of
     a pool no cache holds.  Returns microseconds per launch (median of the batches) and GB/s."""
@@ -193,12 +223,17 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--train-tokens", type=int, default=0, help="time the reconstruction step on this many calibration tokens instead")
     ap.add_argument("--rotate-bytes", type=float, default=1.0e9, help="distinct copies of the layer rotate over at least this many bytes")
+    ap.add_argument("--group", type=str, default="", help="several layers in one fbq_linear_group call, as NxK,NxK,... (they share x where K is equal)")
     ap.add_argument("--graph", action="store_true", help="replay the calls from one HIP graph over all copies")
     ap.add_argument("--twin", action="store_true", help="also time the branch-free twin (r = 0) on the same packed weights")
     ap.add_argument("--read-bytes", type=float, default=0, help="time the read-only yardstick kernel on launches of this many bytes instead")
     a = ap.parse_args()
     if a.train_tokens:
         print(json.dumps(time_train_step(a.N, a.K, a.r, a.bits, a.train_tokens, a.iters, a.warmup)), flush=True)
+        return
+    if a.group:
+        shapes = [tuple(int(v) for v in item.split("x")) for item in a.group.split(",")]
+        print(json.dumps(time_group(shapes, a.r, a.bits, a.M, a.iters, a.warmup, a.rotate_bytes)), flush=True)
         return
     if a.read_bytes:
         print(json.dumps(time_read_stream(a.read_bytes, a.iters, a.warmup)), flush=True)
