@@ -553,7 +553,16 @@ __global__ __launch_bounds__(256) void fbq_arrange_x_kernel(const uint16_t *__re
 
 // ------------------------------------------------------------------ down-projection (prefill)
 
-constexpr int kDownSlices = 8;       // K slices of the prefill down-projection (one block each)
+// K slices of the prefill down-projection, one block per slice and 32-token tile: eight for a thousand tokens, more
+// for fewer tokens so that the pass has about one block per compute unit (256 assumed: the workspace is sized
+// without a device), never narrower than 256 activations.  Slices are multiples of 64 so that each wave's quarter
+// is a whole number of 16-wide K steps.
+static int down_slice_len(int M, int K)
+{
+    const int want = std::min(32, std::max(8, ceil_div(256, ceil_div(M, 32))));
+    return std::max(256, ceil_div(ceil_div(K, want), 64) * 64);
+}
+static int down_slices(int M, int K) { return ceil_div(K, down_slice_len(M, K)); }
 
 // Stage 1: partial[s][m][j] = sum over K slice s of x[m][k] * At[j][k], for one 32-row tile of tokens
 // and all r columns; the block's four waves take a quarter of the slice each and add their tiles up
@@ -636,11 +645,11 @@ __global__ __launch_bounds__(256) void fbq_down_proj_finish_kernel(const float *
 
 // workspace: the arranged copy of x ([M rounded up to kRowPad][K] fp16; rows past M are never
 // written and only feed output rows that are never stored), then [M][2r] fp16 (t_hi | t_lo), then
-// kDownSlices x [M][r] fp32 partial sums
+// down_slices x [M][r] fp32 partial sums
 static size_t xp_bytes(int M, int K) { return ((size_t)ceil_div(M, kRowPad) + 1) * kRowPad * K * sizeof(uint16_t); }
 static size_t thl_bytes(int M, int r) { return ((size_t)M * 2 * r * sizeof(uint16_t) + 255) & ~(size_t)255; }
 
-static size_t down_partial_bytes(int M, int r) { return ((size_t)kDownSlices * M * r * sizeof(float) + 255) & ~(size_t)255; }
+static size_t down_partial_bytes(int M, int K, int r) { return ((size_t)down_slices(M, K) * M * r * sizeof(float) + 255) & ~(size_t)255; }
 
 // K is split over blocks only where 64-row tiles give at most half as many tiles as there are CUs (256 assumed: the
 // rule must not depend on the device, the workspace is sized without one): up to four ways, never below eight
@@ -659,7 +668,7 @@ static int ksplit_of(int M, int N, int K)
 size_t prefill_workspace_bytes(int M, int N, int K, int r)
 {
     const int split = ksplit_of(M, N, K);
-    return xp_bytes(M, K) + thl_bytes(M, r) + down_partial_bytes(M, r) + (split > 1 ? (size_t)split * M * N * sizeof(float) : 0);
+    return xp_bytes(M, K) + thl_bytes(M, r) + down_partial_bytes(M, K, r) + (split > 1 ? (size_t)split * M * N * sizeof(float) : 0);
 }
 
 // Before the fused kernel: x re-ordered into the workspace and, with a sub-branch, t = x.A.  With a sub-branch two
@@ -675,9 +684,8 @@ hipError_t launch_prepass_prefill(const LinearArgs &a, hipStream_t stream)
         else hipLaunchKernelGGL(fbq_arrange_x_kernel<3>, dim3(blocks), dim3(256), 0, stream, a.x, xp, a.M, a.K);
         return hipGetLastError();
     }
-    // K slices: multiples of 64 so that each wave's quarter is a whole number of 16-wide K steps
-    const int kslice = ceil_div(ceil_div(a.K, kDownSlices), 64) * 64;
-    const int slices = ceil_div(a.K, kslice);
+    const int kslice = down_slice_len(a.M, a.K);
+    const int slices = down_slices(a.M, a.K);
     const dim3 grid(ceil_div(a.M, 32), slices);
     const int rt = ceil_div(a.r, 32);
     uint16_t *thl = (uint16_t *)((char *)a.workspace + xp_bytes(a.M, a.K));
@@ -735,7 +743,7 @@ hipError_t launch_gemm_prefill(const LinearArgs &a, hipStream_t stream)
     }
     p.ksplit = ksplit_of(a.M, a.N, a.K);
     if (p.ksplit > 1) { tm = 2; kg = 2; }
-    p.ypart = (float *)((char *)a.workspace + xp_bytes(a.M, a.K) + thl_bytes(a.M, a.r) + down_partial_bytes(a.M, a.r));
+    p.ypart = (float *)((char *)a.workspace + xp_bytes(a.M, a.K) + thl_bytes(a.M, a.r) + down_partial_bytes(a.M, a.K, a.r));
     p.row_blocks = ceil_div(a.M, 32 * tm);
     p.full_cols = (nb / kXcds) * kXcds;
     p.full_slots = (nb / kXcds) * p.row_blocks;
