@@ -290,15 +290,17 @@ __device__ __forceinline__ void job_only_block(const LayerParams &p, int m, int 
     if (jcol >= p.r) return;
     const __amdgpu_buffer_rsrc_t abuf = dev_buffer(p.At, p.r * p.K * 2);
     const __amdgpu_buffer_rsrc_t xbuf = dev_buffer(p.x + (size_t)m * p.K, p.K * 2);
+    __builtin_amdgcn_s_setprio(3);                      // every other block of the layer waits for these words
     uint4_t xr[CPW][4], ar[CPW][4];
 #pragma unroll
     for (int c = 0; c < CPW; ++c) {
-        const int k0 = ((ks * CPW + c) * 64 + lane) * kLaneCodes;
-        const int off = k0 < p.K ? k0 * 2 : kNowhere;    // past K: zeros from both buffers
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            xr[c][i] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, off + i * 16, 0, 0);
-            ar[c][i] = __builtin_amdgcn_raw_buffer_load_b128(abuf, off + i * 16, jcol * p.K * 2, 0);
+            // a wave-wide load covers 512 consecutive activations: fully coalesced, x and the column alike
+            const int k0 = ks * CPW * kChunk + ((c * 4 + i) * 64 + lane) * 8;
+            const int off = k0 < p.K ? k0 * 2 : kNowhere;    // past K: zeros from both buffers
+            xr[c][i] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, off, 0, 0);
+            ar[c][i] = __builtin_amdgcn_raw_buffer_load_b128(abuf, off, jcol * p.K * 2, 0);
         }
     }
     float tj = 0.0f;
