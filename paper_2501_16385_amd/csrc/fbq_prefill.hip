@@ -35,6 +35,7 @@
 #include <hip/hip_fp16.h>
 
 #include <type_traits>
+#include <cstdlib>
 
 #include "fbq_internal.h"
 
@@ -232,13 +233,6 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
     // activation tile: wave w copies rows [w kBM/4, (w+1) kBM/4) of the tile, four rows (1 KiB) per
     // instruction; lane l moves chunk l % 16 of row l / 16 and the hardware puts it at LDS base + 16 l.
     const uint16_t *xsrc = p.xp + (size_t)(m0 + wave * (kBM / 4) + (lane >> 4)) * p.K + (lane & 15) * 8;
-    auto x_copy = [&](int u, int buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < kCopies; ++j)
-            __builtin_amdgcn_global_load_lds(xsrc + (size_t)(4 * j) * p.K + u * kBK,
-                                             (__attribute__((address_space(3))) void *)&lds_all[kg][buf][(wave * (kBM / 4) + 4 * j) * kLdsRow],
-                                             16, 0, 0);
-    };
     // this lane's fragment address within a tile for K step 0 of row block 0; K step s = 4 c + i is
     // logical chunk 8 c + 4 h + i, stored at that index ^ (row % 16)
     const uint32_t a_lane = col * kLdsRow + (((4 * h) ^ (col & 15)) << 4);
@@ -274,33 +268,12 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
     // loads per super-step, each one instruction: the wait before a barrier names how many younger loads may stay in flight
     constexpr int kLoadsW = kTN * 2, kLoadsSZ = kTN * 2, kLoadsX = kBM / 16;
-    auto load_weights = [&](StepRegs &sr, int u) __attribute__((always_inline)) {
-#pragma unroll
-        for (int tn = 0; tn < kTN; ++tn)
-#pragma unroll
-            for (int c = 0; c < 2; ++c) sr.w[tn][c].load(qbuf, woff[tn] + (4 * u + 2 * c) * (WeightRegs<BITS>::kWords * 4));
-    };
-    auto load_sz_pair = [&](SzRegs &r, int u) __attribute__((always_inline)) {      // u even: the dword holds u and u + 1
-#pragma unroll
-        for (int tn = 0; tn < kTN; ++tn) {
-            r.s[tn] = __builtin_amdgcn_raw_buffer_load_b32(sbuf, goff[tn] + u * 2, 0, 0);
-            r.z[tn] = __builtin_amdgcn_raw_buffer_load_b32(zbuf, goff[tn] + u * 2, 0, 0);
-        }
-    };
-    auto load_sz_single = [&](SzRegs &r, int u) __attribute__((always_inline)) {
-#pragma unroll
-        for (int tn = 0; tn < kTN; ++tn) {
-            r.s[tn] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(sbuf, goff[tn] + u * 2, 0, 0);   // (the load zero-extends)
-            r.z[tn] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(zbuf, goff[tn] + u * 2, 0, 0);
-        }
-    };
-
     uint32_t k6400 = 0x64006400u;
     asm volatile("" : "+v"(k6400));                     // keep the constant in a VGPR for v_and_or_b32
 
     // one super-step: eight K steps of 16 on the tile in lds[buf].  The activation fragments of K step
     // i + 1 are fetched from LDS before the matrix instructions of step i are issued.
-    auto compute = [&](const StepRegs &sr, const SzRegs &q, int half_shift, int buf) __attribute__((always_inline)) {
+    auto compute = [&](const StepRegs &sr, const SzRegs &q, int half_shift, int buf, auto &&loads_of_step) __attribute__((always_inline)) {
         const typename WeightRegs<BITS>::Affine aff[kTN] = {{(q.s[0] >> half_shift) & 0xFFFFu, (q.z[0] >> half_shift) & 0xFFFFu},
                                                             {(q.s[1] >> half_shift) & 0xFFFFu, (q.z[1] >> half_shift) & 0xFFFFu}};
         auto a_frag = [&](int tm, int step) __attribute__((always_inline)) {
@@ -337,6 +310,11 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
         for (int step = 0; step < 8; ++step) {
             const int cur = step & 1, nxt = cur ^ 1;
+            __builtin_amdgcn_sched_barrier(0);
+            // this K step's share of the loads of the round after next: asked for here, between the matrix
+            // instructions, the load path works them off in the background; asked for all at once at the top of a
+            // round they kept every wave of the CU waiting in the queue of the address unit, with the matrix pipe idle
+            loads_of_step(step);
             __builtin_amdgcn_sched_barrier(0);
             b1 = b_frag(1, step);
 #pragma unroll
@@ -377,16 +355,42 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
     auto block_barrier = [&]() __attribute__((always_inline)) {
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     };
-    // all loads of round `it` (super-step u0 + it); returns nothing, but every call issues exactly loads_of(it) loads
+    // Load j of round `it` (super-step u): first the copies of the activation tile into LDS, then the packed words,
+    // then (with pairs: in even rounds only) scale and zero.  Every round issues exactly loads_in(it) loads, in this order.
+    auto loads_in = [](int it) constexpr { return kLoadsX + kLoadsW + (pairs && (it & 1) ? 0 : kLoadsSZ); };
+    auto issue_one = [&](auto IT, int u, int j) __attribute__((always_inline)) {
+        constexpr int it = decltype(IT)::value;
+        if (j < kLoadsX) {
+            __builtin_amdgcn_global_load_lds(xsrc + (size_t)(4 * j) * p.K + u * kBK,
+                                             (__attribute__((address_space(3))) void *)&lds_all[kg][it % 3][(wave * (kBM / 4) + 4 * j) * kLdsRow],
+                                             16, 0, 0);
+        } else if (j < kLoadsX + kLoadsW) {
+            const int tn = (j - kLoadsX) / 2, c = (j - kLoadsX) % 2;
+            wr[it % 3].w[tn][c].load(qbuf, woff[tn] + (4 * u + 2 * c) * (WeightRegs<BITS>::kWords * 4));
+        } else {
+            const int tn = (j - kLoadsX - kLoadsW) / 2, which = (j - kLoadsX - kLoadsW) % 2;
+            SzRegs &r = sz[pairs ? (it / 2) % 3 : it % 3];
+            if constexpr (pairs) {                      // u even: the dword holds u and u + 1
+                if (which == 0) r.s[tn] = __builtin_amdgcn_raw_buffer_load_b32(sbuf, goff[tn] + u * 2, 0, 0);
+                else r.z[tn] = __builtin_amdgcn_raw_buffer_load_b32(zbuf, goff[tn] + u * 2, 0, 0);
+            } else {                                    // (the load zero-extends)
+                if (which == 0) r.s[tn] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(sbuf, goff[tn] + u * 2, 0, 0);
+                else r.z[tn] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(zbuf, goff[tn] + u * 2, 0, 0);
+            }
+        }
+    };
+    // all loads of round `it` at once
     auto issue = [&](auto IT, int u) __attribute__((always_inline)) {
         constexpr int it = decltype(IT)::value;
-        load_weights(wr[it % 3], u);
-        if constexpr (pairs) {
-            if constexpr ((it & 1) == 0) load_sz_pair(sz[(it / 2) % 3], u);
-        } else {
-            load_sz_single(sz[it % 3], u);
-        }
-        x_copy(u, it % 3);
+#pragma unroll
+        for (int j = 0; j < loads_in(it); ++j) issue_one(IT, u, j);
+    };
+    // the share of K step `step` (0..7) of them: load j goes with step 8 j / loads_in(it)
+    auto issue_share = [&](auto IT, int u, int step) __attribute__((always_inline)) {
+        constexpr int it = decltype(IT)::value;
+#pragma unroll
+        for (int j = 0; j < loads_in(it); ++j)
+            if (8 * j / loads_in(it) == step) issue_one(IT, u, j);
     };
     // wait until at most the loads of round `it` are in flight
     auto wait_older_than = [&](auto IT) __attribute__((always_inline)) {
@@ -401,8 +405,13 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
     auto do_round = [&](auto IT, int i6) __attribute__((always_inline)) {
         constexpr int it = decltype(IT)::value;           // round within the unrolled six
         const int u = u0 + i6 + it;
-        issue(std::integral_constant<int, (it + 2) % 6>{}, min(u + 2, u_last));
-        if (u < U) compute(wr[it % 3], sz[pairs ? (it / 2) % 3 : it % 3], pairs ? 16 * (it & 1) : 0, it % 3);   // group-uniform
+        const int un = min(u + 2, u_last);
+        if (u < U) {                                    // group-uniform; both sides issue the same loads
+            compute(wr[it % 3], sz[pairs ? (it / 2) % 3 : it % 3], pairs ? 16 * (it & 1) : 0, it % 3,
+                    [&](int step) __attribute__((always_inline)) { issue_share(std::integral_constant<int, (it + 2) % 6>{}, un, step); });
+        } else {
+            issue(std::integral_constant<int, (it + 2) % 6>{}, un);
+        }
         // the next round's operands must have landed (and, through the barrier, everybody's copies into LDS)
         wait_older_than(std::integral_constant<int, (it + 2) % 6>{});
         block_barrier();
@@ -455,20 +464,34 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
 
     // up-projection: 2r extra K columns, t_hi and t_lo against the same B^T rows
     if (p.r > 0 && part == 0) {
+        // (the operands of four steps are requested before the first of them is multiplied: step by step, every step
+        // would be a round trip to memory)
         const int steps = (2 * p.r) / 16;
-        for (int st = 0; st < steps; ++st) {
-            const int jj = st * 16 + h * 8;             // column of [t_hi | t_lo]
-            const int jb = jj >= p.r ? jj - p.r : jj;   // tap of B
-            half8_t bf[kTN];
+        constexpr int kUp = 4;
+        for (int st0 = 0; st0 < steps; st0 += kUp) {
+            half8_t bf[kUp][kTN], af[kUp][TM];
 #pragma unroll
-            for (int tn = 0; tn < kTN; ++tn) bf[tn] = *reinterpret_cast<const half8_t *>(p.Bt + (size_t)nrow[tn] * p.r + jb);
+            for (int i = 0; i < kUp; ++i) {
+                const int st = min(st0 + i, steps - 1);
+                const int jj = st * 16 + h * 8;         // column of [t_hi | t_lo]
+                const int jb = jj >= p.r ? jj - p.r : jj;   // tap of B
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                const int m = min(m0 + tm * 32 + col, p.M - 1);
-                const half8_t af = *reinterpret_cast<const half8_t *>(p.thl + (size_t)m * (2 * p.r) + jj);
+                for (int tn = 0; tn < kTN; ++tn) bf[i][tn] = *reinterpret_cast<const half8_t *>(p.Bt + (size_t)nrow[tn] * p.r + jb);
 #pragma unroll
-                for (int tn = 0; tn < kTN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf[tn], acc[tm][tn], 0, 0, 0);
+                for (int tm = 0; tm < TM; ++tm) {
+                    const int m = min(m0 + tm * 32 + col, p.M - 1);
+                    af[i][tm] = *reinterpret_cast<const half8_t *>(p.thl + (size_t)m * (2 * p.r) + jj);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kUp; ++i) {
+                if (st0 + i < steps) {                  // uniform
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                        for (int tn = 0; tn < kTN; ++tn)
+                            acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i][tm], bf[i][tn], acc[tm][tn], 0, 0, 0);
+                }
             }
         }
     }
@@ -578,11 +601,6 @@ __global__ __launch_bounds__(256) void fbq_down_proj_prefill_kernel(const uint16
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, h = lane >> 5;
     const int m0 = blockIdx.x * 32;
-    {
-        const int b0 = blockIdx.y * (kslice / 32), nb = min(K / 32, b0 + kslice / 32) - b0;   // 32-wide pieces of this slice
-        const int rows = min(32, M - m0);
-        for (int idx = tid; idx < rows * nb; idx += 256) arrange_item<BITS>(x, xp, K, m0 + idx / nb, b0 + idx % nb);
-    }
     const int kq = kslice / 4;                          // a multiple of 16
     const int kbeg = blockIdx.y * kslice + wave * kq;
     const int kend = min(K, kbeg + kq);
@@ -597,13 +615,37 @@ __global__ __launch_bounds__(256) void fbq_down_proj_prefill_kernel(const uint16
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[rt][v] = 0.0f;
 
-    for (int kk = kbeg; kk < kend; kk += 16) {
-        const half8_t af = *reinterpret_cast<const half8_t *>(xrow + kk);
+    // A wave's stretch is short (a few steps of 16), and step by step it would be one round trip to memory per
+    // step: all operands of kBatch steps are requested before the first product (steps past the end re-read the
+    // first and are not multiplied).  The re-ordering of the block's share of x runs while the first batch is
+    // on its way.
+    constexpr int kBatch = RT <= 2 ? 8 : (RT <= 4 ? 4 : 2);
+    for (int k0 = kbeg; k0 < kend; k0 += 16 * kBatch) {
+        half8_t af[kBatch], bf[kBatch][RT];
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            const half8_t bf = *reinterpret_cast<const half8_t *>(arow[rt] + kk);
-            acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf, acc[rt], 0, 0, 0);
+        for (int i = 0; i < kBatch; ++i) {
+            const int kk = k0 + 16 * i < kend ? k0 + 16 * i : kbeg;
+            af[i] = *reinterpret_cast<const half8_t *>(xrow + kk);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) bf[i][rt] = *reinterpret_cast<const half8_t *>(arow[rt] + kk);
         }
+        if (k0 == kbeg) {
+            const int b0 = blockIdx.y * (kslice / 32), nb = min(K / 32, b0 + kslice / 32) - b0;   // 32-wide pieces of this slice
+            const int rows = min(32, M - m0);
+            for (int idx = tid; idx < rows * nb; idx += 256) arrange_item<BITS>(x, xp, K, m0 + idx / nb, b0 + idx % nb);
+        }
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            if (k0 + 16 * i < kend) {                   // wave-uniform
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[i][rt], acc[rt], 0, 0, 0);
+            }
+        }
+    }
+    if (kbeg >= kend) {                                 // a wave without a stretch of its own still re-orders its share
+        const int b0 = blockIdx.y * (kslice / 32), nb = min(K / 32, b0 + kslice / 32) - b0;
+        const int rows = min(32, M - m0);
+        for (int idx = tid; idx < rows * nb; idx += 256) arrange_item<BITS>(x, xp, K, m0 + idx / nb, b0 + idx % nb);
     }
 
     const int ld = 32 * RT;
@@ -633,8 +675,15 @@ __global__ __launch_bounds__(256) void fbq_down_proj_finish_kernel(const float *
 {
     const size_t total = (size_t)M * r;
     for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (size_t)gridDim.x * 256) {
+        // eight slices per round trip to memory, added in slice order
         float t = 0.0f;
-        for (int s = 0; s < slices; ++s) t += partial[(size_t)s * total + idx];
+        for (int s0 = 0; s0 < slices; s0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = partial[(size_t)min(s0 + k, slices - 1) * total + idx];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) t += s0 + k < slices ? v[k] : 0.0f;
+        }
         const size_t m = idx / r, j = idx - m * r;
         const half_t hi = (half_t)t;
         const half_t lo = (half_t)(t - (float)hi);
