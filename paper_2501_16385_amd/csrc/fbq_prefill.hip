@@ -186,7 +186,7 @@ __device__ __forceinline__ half8_t pack8(half2_t a, half2_t b, half2_t c, half2_
 // to give every CU two blocks of four waves runs one block of eight waves per CU instead: the groups take
 // alternate halves of K and group 1 hands its accumulators to group 0 through LDS at the end, so nothing but y
 // is ever written.
-// PAIRS: the number of groups per row is even, so scale and zero of two consecutive super-steps are one aligned dword.
+// PAIRS: the number of groups per row is even, so scale and zero of six consecutive super-steps are three aligned dwords.
 template <int BITS, int TM, int KG, bool PAIRS>
 __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))) void fbq_gemm_kernel(const PrefillParams p)
 {
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int U_all = p.K / kBK;
     const int shares = KG * p.ksplit;                   // K is shared out over the groups of a block and, for a layer with very few tiles, over blocks
     int U_part = (U_all + shares - 1) / shares;
-    if (PAIRS) U_part = (U_part + 1) & ~1;              // an even first super-step: scale and zero come in pairs
+    if (PAIRS) U_part = (U_part + 1) & ~1;              // an even first super-step: scale and zero come as aligned dwords
     const int u0 = (part * KG + kg) * U_part, U = min(U_all, u0 + U_part);   // this group's super-steps: u0 .. U - 1 (at most U_part)
 
     // this lane's weight rows (clamped: columns past N are computed on a valid row and never stored)
@@ -245,15 +245,17 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.0f;
 
-    // The packed words of one super-step (two code blocks, the k halves, per N tile), and scale and zero: fp16 bits,
-    // one per register.  Scale and zero are 2-byte loads of 32 different rows, as expensive for the load path as the
-    // 16-byte weight loads; with an even number of groups per row the pair of an even and the following odd
-    // super-step is one aligned dword, fetched with the even step.
+    // The packed words of one super-step (two code blocks, the k halves, per N tile), and scale and zero as fp16 bits.
+    // Scale and zero are loads of 32 different rows, as expensive for the load path as the 16-byte weight loads
+    // however few bytes they fetch (measured: a quarter of the kernel's time went into them when every second
+    // super-step fetched a dword of each).  With an even number of groups per row, six consecutive groups of a row
+    // from an even one on are three aligned dwords: one 12-byte load per row, array and six super-steps - the six
+    // rounds of the unrolled loop.  With an odd number of groups, one 2-byte load per super-step.
     struct StepRegs {
         WeightRegs<BITS> w[kTN][2];
     };
     struct SzRegs {
-        uint32_t s[kTN], z[kTN];
+        uint32_t s[kTN][3], z[kTN][3];                  // (single loads: element 0 only)
     };
     constexpr bool pairs = PAIRS;
     const __amdgpu_buffer_rsrc_t qbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(p.qw), 0, (int)((size_t)p.N * p.row_words * 4), 0x00020000);
@@ -273,9 +275,11 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
 
     // one super-step: eight K steps of 16 on the tile in lds[buf].  The activation fragments of K step
     // i + 1 are fetched from LDS before the matrix instructions of step i are issued.
-    auto compute = [&](const StepRegs &sr, const SzRegs &q, int half_shift, int buf, auto &&loads_of_step) __attribute__((always_inline)) {
-        const typename WeightRegs<BITS>::Affine aff[kTN] = {{(q.s[0] >> half_shift) & 0xFFFFu, (q.z[0] >> half_shift) & 0xFFFFu},
-                                                            {(q.s[1] >> half_shift) & 0xFFFFu, (q.z[1] >> half_shift) & 0xFFFFu}};
+    // (q, gi: the registers that hold scale and zero, and which of their six fp16 it is)
+    auto compute = [&](const StepRegs &sr, const SzRegs &q, int gi, int buf, auto &&loads_of_step) __attribute__((always_inline)) {
+        const int half_shift = 16 * (gi & 1);
+        const typename WeightRegs<BITS>::Affine aff[kTN] = {{(q.s[0][gi / 2] >> half_shift) & 0xFFFFu, (q.z[0][gi / 2] >> half_shift) & 0xFFFFu},
+                                                            {(q.s[1][gi / 2] >> half_shift) & 0xFFFFu, (q.z[1][gi / 2] >> half_shift) & 0xFFFFu}};
         auto a_frag = [&](int tm, int step) __attribute__((always_inline)) {
             const uint32_t off = a_lane ^ (uint32_t)((8 * (step / 4) + (step % 4)) << 4);
             return *reinterpret_cast<const half8_t *>(&lds_all[kg][buf][off + tm * (32 * kLdsRow)]);
@@ -356,9 +360,10 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     };
     // Load j of round `it` (super-step u): first the copies of the activation tile into LDS, then the packed words,
-    // then (with pairs: in even rounds only) scale and zero.  Every round issues exactly loads_in(it) loads, in this order.
-    auto loads_in = [](int it) constexpr { return kLoadsX + kLoadsW + (pairs && (it & 1) ? 0 : kLoadsSZ); };
-    auto issue_one = [&](auto IT, int u, int j) __attribute__((always_inline)) {
+    // then scale and zero (the six-group loads: in the first of the six rounds only; they go to set 0 before the
+    // loop and to set 1, the one in waiting, inside it).  Every round issues exactly loads_in(it) loads, in this order.
+    auto loads_in = [](int it) constexpr { return kLoadsX + kLoadsW + (pairs && it % 6 != 0 ? 0 : kLoadsSZ); };
+    auto issue_one = [&](auto IT, auto FIRST, int u, int j) __attribute__((always_inline)) {
         constexpr int it = decltype(IT)::value;
         if (j < kLoadsX) {
             __builtin_amdgcn_global_load_lds(xsrc + (size_t)(4 * j) * p.K + u * kBK,
@@ -369,34 +374,34 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
             wr[it % 3].w[tn][c].load(qbuf, woff[tn] + (4 * u + 2 * c) * (WeightRegs<BITS>::kWords * 4));
         } else {
             const int tn = (j - kLoadsX - kLoadsW) / 2, which = (j - kLoadsX - kLoadsW) % 2;
-            SzRegs &r = sz[pairs ? (it / 2) % 3 : it % 3];
-            if constexpr (pairs) {                      // u even: the dword holds u and u + 1
-                if (which == 0) r.s[tn] = __builtin_amdgcn_raw_buffer_load_b32(sbuf, goff[tn] + u * 2, 0, 0);
-                else r.z[tn] = __builtin_amdgcn_raw_buffer_load_b32(zbuf, goff[tn] + u * 2, 0, 0);
+            if constexpr (pairs) {                      // u even (past the end: whatever, rounded down to a dword; never used)
+                SzRegs &r = sz[decltype(FIRST)::value ? 0 : 1];
+                const uint3v_t v = __builtin_amdgcn_raw_buffer_load_b96(which == 0 ? sbuf : zbuf, (goff[tn] + u * 2) & ~3, 0, 0);
+                if (which == 0) { r.s[tn][0] = v.x; r.s[tn][1] = v.y; r.s[tn][2] = v.z; }
+                else { r.z[tn][0] = v.x; r.z[tn][1] = v.y; r.z[tn][2] = v.z; }
             } else {                                    // (the load zero-extends)
-                if (which == 0) r.s[tn] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(sbuf, goff[tn] + u * 2, 0, 0);
-                else r.z[tn] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(zbuf, goff[tn] + u * 2, 0, 0);
+                SzRegs &r = sz[it % 3];
+                if (which == 0) r.s[tn][0] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(sbuf, goff[tn] + u * 2, 0, 0);
+                else r.z[tn][0] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(zbuf, goff[tn] + u * 2, 0, 0);
             }
         }
     };
     // all loads of round `it` at once
-    auto issue = [&](auto IT, int u) __attribute__((always_inline)) {
+    auto issue = [&](auto IT, auto FIRST, int u) __attribute__((always_inline)) {
         constexpr int it = decltype(IT)::value;
 #pragma unroll
-        for (int j = 0; j < loads_in(it); ++j) issue_one(IT, u, j);
+        for (int j = 0; j < loads_in(it); ++j) issue_one(IT, FIRST, u, j);
     };
     // the share of K step `step` (0..7) of them: load j goes with step 8 j / loads_in(it)
     auto issue_share = [&](auto IT, int u, int step) __attribute__((always_inline)) {
         constexpr int it = decltype(IT)::value;
 #pragma unroll
         for (int j = 0; j < loads_in(it); ++j)
-            if (8 * j / loads_in(it) == step) issue_one(IT, u, j);
+            if (8 * j / loads_in(it) == step) issue_one(IT, std::false_type{}, u, j);
     };
     // wait until at most the loads of round `it` are in flight
     auto wait_older_than = [&](auto IT) __attribute__((always_inline)) {
-        constexpr int it = decltype(IT)::value;
-        constexpr int n_pairs = kLoadsX + kLoadsW + ((it & 1) == 0 ? kLoadsSZ : 0), n_single = kLoadsX + kLoadsW + kLoadsSZ;
-        constexpr int n = pairs ? n_pairs : n_single;
+        constexpr int n = loads_in(decltype(IT)::value);
         __builtin_amdgcn_s_waitcnt((n & 15) | ((n >> 4) << 14) | 0x0F70);
     };
     // The loads of a round are issued whether or not the super-step exists (past the end: the last one again, never
@@ -407,22 +412,23 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int u = u0 + i6 + it;
         const int un = min(u + 2, u_last);
         if (u < U) {                                    // group-uniform; both sides issue the same loads
-            compute(wr[it % 3], sz[pairs ? (it / 2) % 3 : it % 3], pairs ? 16 * (it & 1) : 0, it % 3,
+            compute(wr[it % 3], sz[pairs ? 0 : it % 3], pairs ? it : 0, it % 3,
                     [&](int step) __attribute__((always_inline)) { issue_share(std::integral_constant<int, (it + 2) % 6>{}, un, step); });
         } else {
-            issue(std::integral_constant<int, (it + 2) % 6>{}, un);
+            issue(std::integral_constant<int, (it + 2) % 6>{}, std::false_type{}, un);
         }
         // the next round's operands must have landed (and, through the barrier, everybody's copies into LDS)
         wait_older_than(std::integral_constant<int, (it + 2) % 6>{});
         block_barrier();
     };
-    issue(std::integral_constant<int, 0>{}, min(u0, u_last));
-    issue(std::integral_constant<int, 1>{}, min(u0 + 1, u_last));
+    issue(std::integral_constant<int, 0>{}, std::true_type{}, min(u0, u_last));
+    issue(std::integral_constant<int, 1>{}, std::true_type{}, min(u0 + 1, u_last));
     wait_older_than(std::integral_constant<int, 1>{});
     block_barrier();
     // every group runs the same number of rounds so that the block's barriers match; a group whose share of K is
     // shorter sits its last rounds out
     for (int i6 = 0; i6 < U_part; i6 += 6) {
+        if (pairs && i6 > 0) sz[0] = sz[1];             // the set that was in waiting (requested two rounds ago: landed before the last barrier)
         do_round(std::integral_constant<int, 0>{}, i6);
         if (i6 + 1 >= U_part) break;
         do_round(std::integral_constant<int, 1>{}, i6);
@@ -463,7 +469,54 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
 
     // up-projection: 2r extra K columns, t_hi and t_lo against the same B^T rows
-    if (p.r > 0 && part == 0) {
+    if (p.r > 0 && part == 0 && p.r % 64 == 0) {
+        // 64 taps at a time through LDS (the activation buffers are free now).  Every lane fetching its own 16 bytes of
+        // its own row - 32 rows per load, some forty loads per wave, all at once - kept the address unit busy for
+        // microseconds at the end of every block; copied into LDS, a load moves 1 KiB of whole rows (eight lanes per
+        // 128-byte row of B^T, sixteen per 256-byte row of t_hi | t_lo), and the operands come out of LDS.  Rows are
+        // stored with the position of each 16-byte piece XOR-ed with the row number, as the activation tiles are.
+        static_assert(sizeof(lds_all) >= kBN * 128 + kBM * 256, "the activation buffers must hold 64 taps of the block's rows of B^T and of t");
+        unsigned char *const lds_b = &lds_all[0][0][0];     // [256 rows][8 pieces]
+        unsigned char *const lds_t = lds_b + kBN * 128;     // [kBM rows][16 pieces: 8 of t_hi, 8 of t_lo]
+        for (int c0 = 0; c0 < p.r; c0 += 64) {
+            block_barrier();                            // everybody is done with what LDS held before
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int row = (wave * 8 + i) * 8 + (lane >> 3), piece = (lane & 7) ^ (row & 7);
+                const int n = min(bn * kBN + row, p.N - 1);
+                __builtin_amdgcn_global_load_lds(p.Bt + (size_t)n * p.r + c0 + piece * 8,
+                                                 (__attribute__((address_space(3))) void *)(lds_b + (wave * 8 + i) * 1024), 16, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < kCopies; ++j) {
+                const int row = wave * (kBM / 4) + 4 * j + (lane >> 4), piece = (lane & 15) ^ (row & 15);
+                const int m = min(m0 + row, p.M - 1);
+                const uint16_t *src = p.thl + (size_t)m * (2 * p.r) + (piece < 8 ? c0 + piece * 8 : p.r + c0 + (piece - 8) * 8);
+                __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void *)(lds_t + (wave * (kBM / 4) + 4 * j) * 256), 16, 0, 0);
+            }
+            __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0): this wave's copies have landed
+            block_barrier();
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                half8_t bf[kTN];
+#pragma unroll
+                for (int tn = 0; tn < kTN; ++tn) {
+                    const int row = wave * (kTN * 32) + tn * 32 + col;
+                    bf[tn] = *reinterpret_cast<const half8_t *>(lds_b + row * 128 + (((2 * st + h) ^ (row & 7)) << 4));
+                }
+#pragma unroll
+                for (int half = 0; half < 2; ++half)
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) {
+                        const int row = tm * 32 + col;
+                        const half8_t af = *reinterpret_cast<const half8_t *>(lds_t + row * 256 + (((8 * half + 2 * st + h) ^ (row & 15)) << 4));
+#pragma unroll
+                        for (int tn = 0; tn < kTN; ++tn)
+                            acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf[tn], acc[tm][tn], 0, 0, 0);
+                    }
+            }
+        }
+    } else if (p.r > 0 && part == 0) {
         // (the operands of four steps are requested before the first of them is multiplied: step by step, every step
         // would be a round trip to memory)
         const int steps = (2 * p.r) / 16;
