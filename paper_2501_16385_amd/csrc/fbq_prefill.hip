@@ -587,16 +587,14 @@ __global__ __launch_bounds__(256) void fbq_sum_parts_kernel(const float *__restr
 // ------------------------------------------------------------------ activation pre-pass
 
 // xp[m][128 u + 8 (l ^ (m % 16)) + e] = x[m][128 u + 32 (l / 4) + slot_source(8 (l % 4) + e)]
-// for chunk l = 0..15 of every 128-wide block u; one thread per 32 activations.
+// for chunk l = 0..15 of every 128-wide block u; one thread per 32 activations (q4: the 64 bytes of piece b of row m).
 template <int BITS>
-__device__ __forceinline__ void arrange_item(const uint16_t *__restrict__ x, uint16_t *__restrict__ xp, int K, int m, int b)
+__device__ __forceinline__ void arrange_store(const uint4 (&q4)[4], uint16_t *__restrict__ xp, int K, int m, int b)
 {
-    const uint4 *src = reinterpret_cast<const uint4 *>(x + (size_t)m * K + b * 32);
     half_t v[32];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const uint4 q = src[i];
-        const uint32_t wds[4] = {q.x, q.y, q.z, q.w};
+        const uint32_t wds[4] = {q4[i].x, q4[i].y, q4[i].z, q4[i].w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const half2_t hh = h2_of(wds[j]);
@@ -618,52 +616,87 @@ __device__ __forceinline__ void arrange_item(const uint16_t *__restrict__ x, uin
     }
 }
 
+// Items [first, first + count) of a row-major list of (row, 32-wide piece) pairs, `nb` pieces per row starting at piece
+// b0 of row m0: `stride` threads share them, thread `t` takes t, t + stride, ...  The loads of kArrangeBatch items are
+// requested before the first of them is stored (item by item, every item was a round trip to memory).
+constexpr int kArrangeBatch = 3;
+template <int BITS>
+__device__ __forceinline__ void arrange_items(const uint16_t *__restrict__ x, uint16_t *__restrict__ xp, int K, int m0, int b0, int nb,
+                                              long count, long t, long stride)
+{
+    for (long i0 = t; i0 < count; i0 += stride * kArrangeBatch) {
+        uint4 q4[kArrangeBatch][4];
+#pragma unroll
+        for (int k = 0; k < kArrangeBatch; ++k) {
+            const long idx = min(i0 + k * stride, count - 1);          // (past the end: the last item again, not stored)
+            const uint4 *src = reinterpret_cast<const uint4 *>(x + (size_t)(m0 + idx / nb) * K + (b0 + idx % nb) * 32);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) q4[k][i] = src[i];
+        }
+#pragma unroll
+        for (int k = 0; k < kArrangeBatch; ++k) {
+            const long idx = i0 + k * stride;
+            if (idx < count) arrange_store<BITS>(q4[k], xp, K, m0 + (int)(idx / nb), b0 + (int)(idx % nb));
+        }
+    }
+}
+
 // The whole of x, for a layer without a sub-branch (with one, the down-projection's blocks arrange what they read).
 template <int BITS>
 __global__ __launch_bounds__(256) void fbq_arrange_x_kernel(const uint16_t *__restrict__ x, uint16_t *__restrict__ xp, int M, int K)
 {
-    const int per_row = K / 32;
-    const size_t total = (size_t)M * per_row;
-    for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (size_t)gridDim.x * 256) {
-        const int m = (int)(idx / per_row), b = (int)(idx - (size_t)m * per_row);
-        arrange_item<BITS>(x, xp, K, m, b);
-    }
+    arrange_items<BITS>(x, xp, K, 0, 0, K / 32, (long)M * (K / 32), (long)blockIdx.x * 256 + threadIdx.x, (long)gridDim.x * 256);
 }
 
 // ------------------------------------------------------------------ down-projection (prefill)
 
 // K slices of the prefill down-projection, one block per slice and 32-token tile: eight for a thousand tokens, more
 // for fewer tokens so that the pass has about one block per compute unit (256 assumed: the workspace is sized
-// without a device), never narrower than 256 activations.  Slices are multiples of 64 so that each wave's quarter
-// is a whole number of 16-wide K steps.
+// without a device), never narrower than 256 activations.  Slices are whole quantization groups: the kernel walks
+// them in chunks of 128.
 static int down_slice_len(int M, int K)
 {
     const int want = std::min(32, std::max(8, ceil_div(256, ceil_div(M, 32))));
-    return std::max(256, ceil_div(ceil_div(K, want), 64) * 64);
+    return std::max(256, ceil_div(ceil_div(K, want), kBK) * kBK);
 }
 static int down_slices(int M, int K) { return ceil_div(K, down_slice_len(M, K)); }
 
-// Stage 1: partial[s][m][j] = sum over K slice s of x[m][k] * At[j][k], for one 32-row tile of tokens
-// and all r columns; the block's four waves take a quarter of the slice each and add their tiles up
-// through LDS in wave order.  RT = 32-column tiles (r <= 32 * RT).
-// The block also writes the arranged copy of the activations it reads (its 32 rows, its K slice): one pass over x
-// serves both, and the re-ordering needs no launch of its own.
+// Stage 1: partial[s][m][j] = sum over K slice s of x[m][k] * At[j][k], for one 32-row tile of tokens and all r
+// columns.  RT = 32-column tiles (r <= 32 * RT).  The block also writes the arranged copy of the activations it
+// reads (its 32 rows, its K slice): one pass over x serves both, and the re-ordering needs no launch of its own.
+//
+// The slice is walked in chunks of 128: the chunk's 32 rows of x and 32 RT rows of A^T (256 bytes each) are copied
+// into LDS by global_load_lds_dwordx4 - four whole rows per instruction - while the chunk before is being worked on
+// (two buffers).  (Fetched by the lanes themselves, 16 bytes of one row per lane and instruction, the operands of a
+// long slice kept the CU's address unit busy longer than everything else in this kernel took.)  Rows are stored
+// with the position of each 16-byte piece XOR-ed with the row number, as the fused kernel's tiles are.  Of a
+// chunk's eight K steps of 16, wave w multiplies steps 2w and 2w + 1; the four waves' tiles meet in LDS at the end.
 template <int BITS, int RT>
 __global__ __launch_bounds__(256) void fbq_down_proj_prefill_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ At,
                                                                     float *__restrict__ partial, uint16_t *__restrict__ xp, int M, int K,
                                                                     int r, int kslice)
 {
-    extern __shared__ float sum[];                      // [32][32 * RT]
+    constexpr int kRows = 32 + 32 * RT;                 // rows of a chunk in LDS: the tokens, then the columns of A
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_down[2 * kRows * 256];   // [2][kRows][256 B]; afterwards float [32][32 RT]
+    static_assert(sizeof(lds_down) <= 160 * 1024 && sizeof(lds_down) >= 32 * 32 * RT * sizeof(float), "two chunks must fit the CU's LDS and hold the summed tile");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, h = lane >> 5;
     const int m0 = blockIdx.x * 32;
-    const int kq = kslice / 4;                          // a multiple of 16
-    const int kbeg = blockIdx.y * kslice + wave * kq;
-    const int kend = min(K, kbeg + kq);
-    const uint16_t *xrow = x + (size_t)min(m0 + col, M - 1) * K + h * 8;
-    const uint16_t *arow[RT];
+    const int k_lo = blockIdx.y * kslice, k_hi = min(K, k_lo + kslice);
+    const int chunks = (k_hi - k_lo) / kBK;             // K and the slices are whole groups of 128
+
+    // copies of chunk c: instruction i of the block moves rows 4 i .. 4 i + 3 (lane l: piece l % 16 of row 4 i + l / 16,
+    // put at LDS position l of the instruction's 1 KiB, i.e. the piece the position stands for is position ^ row)
+    auto copy_chunk = [&](int c, int buf) __attribute__((always_inline)) {
+        unsigned char *base = lds_down + (size_t)buf * kRows * 256;
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) arow[rt] = At + (size_t)min(rt * 32 + col, r - 1) * K + h * 8;
+        for (int j = 0; j < kRows / 16; ++j) {
+            const int i = wave * (kRows / 16) + j;      // this wave's share of the kRows / 4 instructions
+            const int row = 4 * i + (lane >> 4), piece = (lane & 15) ^ (row & 15);
+            const uint16_t *src = row < 32 ? x + (size_t)min(m0 + row, M - 1) * K : At + (size_t)min(row - 32, r - 1) * K;
+            __builtin_amdgcn_global_load_lds(src + k_lo + c * kBK + piece * 8, (__attribute__((address_space(3))) void *)(base + i * 1024), 16, 0, 0);
+        }
+    };
 
     float16_t acc[RT];
 #pragma unroll
@@ -671,39 +704,39 @@ __global__ __launch_bounds__(256) void fbq_down_proj_prefill_kernel(const uint16
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[rt][v] = 0.0f;
 
-    // A wave's stretch is short (a few steps of 16), and step by step it would be one round trip to memory per
-    // step: all operands of kBatch steps are requested before the first product (steps past the end re-read the
-    // first and are not multiplied).  The re-ordering of the block's share of x runs while the first batch is
-    // on its way.
-    constexpr int kBatch = RT <= 2 ? 8 : (RT <= 4 ? 4 : 2);
-    for (int k0 = kbeg; k0 < kend; k0 += 16 * kBatch) {
-        half8_t af[kBatch], bf[kBatch][RT];
+    if (chunks > 0) copy_chunk(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0)
+    __syncthreads();
+    for (int c = 0; c < chunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < chunks) copy_chunk(c + 1, buf ^ 1);
+        const unsigned char *base = lds_down + (size_t)buf * kRows * 256;
+        // the re-ordered copy: 32 rows x 4 pieces of 32 activations, one per thread of the first two waves
+        if (tid < 128) {
+            const int i = tid >> 2, b = tid & 3;
+            if (m0 + i < M) {
+                uint4 q4[4];
 #pragma unroll
-        for (int i = 0; i < kBatch; ++i) {
-            const int kk = k0 + 16 * i < kend ? k0 + 16 * i : kbeg;
-            af[i] = *reinterpret_cast<const half8_t *>(xrow + kk);
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) bf[i][rt] = *reinterpret_cast<const half8_t *>(arow[rt] + kk);
-        }
-        if (k0 == kbeg) {
-            const int b0 = blockIdx.y * (kslice / 32), nb = min(K / 32, b0 + kslice / 32) - b0;   // 32-wide pieces of this slice
-            const int rows = min(32, M - m0);
-            for (int idx = tid; idx < rows * nb; idx += 256) arrange_item<BITS>(x, xp, K, m0 + idx / nb, b0 + idx % nb);
-        }
-#pragma unroll
-        for (int i = 0; i < kBatch; ++i) {
-            if (k0 + 16 * i < kend) {                   // wave-uniform
-#pragma unroll
-                for (int rt = 0; rt < RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[i][rt], acc[rt], 0, 0, 0);
+                for (int k = 0; k < 4; ++k) q4[k] = *reinterpret_cast<const uint4 *>(base + i * 256 + (((4 * b + k) ^ (i & 15)) << 4));
+                arrange_store<BITS>(q4, xp, K, m0 + i, (k_lo + c * kBK) / 32 + b);
             }
         }
-    }
-    if (kbeg >= kend) {                                 // a wave without a stretch of its own still re-orders its share
-        const int b0 = blockIdx.y * (kslice / 32), nb = min(K / 32, b0 + kslice / 32) - b0;
-        const int rows = min(32, M - m0);
-        for (int idx = tid; idx < rows * nb; idx += 256) arrange_item<BITS>(x, xp, K, m0 + idx / nb, b0 + idx % nb);
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            const int pc = 2 * (2 * wave + st) + h;     // the 16-byte piece with this lane's k of the step
+            const half8_t af = *reinterpret_cast<const half8_t *>(base + col * 256 + ((pc ^ (col & 15)) << 4));
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                const int row = 32 + rt * 32 + col;
+                const half8_t bf = *reinterpret_cast<const half8_t *>(base + row * 256 + ((pc ^ (row & 15)) << 4));
+                acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf, acc[rt], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);             // the next chunk has landed (and this chunk's stores are out)
+        __syncthreads();                                // ... everybody's part of it; and everybody is done reading this one
     }
 
+    float *sum = reinterpret_cast<float *>(lds_down);
     const int ld = 32 * RT;
     for (int w = 0; w < 4; ++w) {
         if (wave == w) {
@@ -795,7 +828,7 @@ hipError_t launch_prepass_prefill(const LinearArgs &a, hipStream_t stream)
     const int rt = ceil_div(a.r, 32);
     uint16_t *thl = (uint16_t *)((char *)a.workspace + xp_bytes(a.M, a.K));
     float *partial = (float *)((char *)thl + thl_bytes(a.M, a.r));
-#define FBQ_DOWN(B, R) hipLaunchKernelGGL((fbq_down_proj_prefill_kernel<B, R>), grid, dim3(256), 32 * 32 * R * sizeof(float), stream, a.x, a.At, partial, xp, a.M, a.K, a.r, kslice)
+#define FBQ_DOWN(B, R) hipLaunchKernelGGL((fbq_down_proj_prefill_kernel<B, R>), grid, dim3(256), 0, stream, a.x, a.At, partial, xp, a.M, a.K, a.r, kslice)
     if (a.bits == 4) {
         if (rt <= 1) FBQ_DOWN(4, 1); else if (rt <= 2) FBQ_DOWN(4, 2); else if (rt <= 4) FBQ_DOWN(4, 4); else FBQ_DOWN(4, 8);
     } else {
