@@ -102,6 +102,30 @@ class GroupCall:
         if rc:
             raise RuntimeError(f"fbq_linear_group failed with status {rc}")
 
+    def enqueue(self, stream_ptr):
+        return self.fn(self.arr, self.args[1], self.args[2], stream_ptr)
+
+
+class UnfusedCall:
+    """Pre-marshalled fbq_linear_unfused call: one layer as the conventional three launches (Sec. 3.2)."""
+
+    def __init__(self, fbq, layer, x, y, ws, M, stream_ptr):
+        self.fn = fbq.load().fbq_linear_unfused
+        self.desc = layer.desc.c()
+        p = lambda t: ctypes.c_void_p(0 if t is None else t.data_ptr())
+        self.keep = (layer, x, y, ws)
+        self.head = (ctypes.byref(self.desc), M, p(x), p(layer.qweight), p(layer.scales), p(layer.zeros), p(layer.At), p(layer.Bt), p(y), p(ws),
+                     ctypes.c_size_t(ws.numel()))
+        self.sp = stream_ptr
+
+    def __call__(self):
+        rc = self.enqueue(self.sp)
+        if rc:
+            raise RuntimeError(f"fbq_linear_unfused failed with status {rc}")
+
+    def enqueue(self, stream_ptr):
+        return self.fn(*self.head, stream_ptr)
+
 
 class LayerSetBench:
     """The rotating copies of one layer set and the schedules timed over them."""
@@ -149,6 +173,14 @@ class LayerSetBench:
             out.append(calls)
         return out
 
+    def schedule_unfused(self, M):
+        """Every layer as fbq_linear_unfused (three launches each), one list of calls per copy of the layer set."""
+        torch, fbq = self.torch, self.fbq
+        xs = [x[:M].contiguous() for x in self.xs_full]
+        ys = [torch.empty((M, s.N), dtype=torch.float16, device="cuda") for s in self.specs]
+        wss = [torch.zeros(max(16, fbq.workspace_bytes(l.desc, M)), dtype=torch.uint8, device="cuda") for l in self.base]
+        return [[UnfusedCall(fbq, ls[i], xs[i], ys[i], wss[i], M, self.sp) for i in range(len(self.specs))] for ls in self.sets]
+
     def timed(self, sched, steps, warmup, batches, graph=False):
         """`batches` times exactly `steps` steps between two events on the launch stream.  Returns ms per step
         (median, min and mean over the batches) and the host wall clock per step of the median batch.
@@ -165,9 +197,9 @@ class LayerSetBench:
             with torch.cuda.graph(g, stream=side):
                 for calls in sched:
                     for call in calls:
-                        rc = call.fn(call.arr, call.args[1], call.args[2], gsp)
+                        rc = call.enqueue(gsp)
                         if rc:
-                            raise RuntimeError(f"fbq_linear_group failed with status {rc} during capture")
+                            raise RuntimeError(f"a launch failed with status {rc} during capture")
             replays = max(1, -(-steps // len(sched)))
             for _ in range(max(1, warmup // len(sched))):
                 g.replay()
@@ -326,6 +358,13 @@ def main():
     t_merged = lsb.timed(lsb.schedule(merged, M), K, W, R)
     t_merged_plain = lsb.timed(lsb.schedule(merged, M, plain=True), K, W, R)
 
+    # The conventional arrangement (Sec. 3.2: main path, down-projection and a read-modify-write up-projection as
+    # launches of their own) against the fused layer and the branch-free layer, layer by layer, all three replayed
+    # from HIP graphs (21, 7 and 7 launches per step: the host could not enqueue them fast enough otherwise).
+    tg_unfused = lsb.timed(lsb.schedule_unfused(M), K, W, R, graph=True)
+    tg_layer = lsb.timed(lsb.schedule(per_layer, M), K, W, R, graph=True)
+    tg_layer_plain = lsb.timed(lsb.schedule(per_layer, M, plain=True), K, W, R, graph=True)
+
     # every stage's launch alone, back to back on the stream (this includes the ~1.5 us the command processor needs
     # between two dependent launches; launches under 9 us are also replayed from a HIP graph over all copies, because
     # the host cannot enqueue a launch every 4 us, and the faster counts); the one that moves most bytes is the dominant kernel of `roofline`
@@ -378,6 +417,16 @@ def main():
                       "per_layer": mode(t_layer, t_layer_plain, len(per_layer)),
                       "merged": mode(t_merged, t_merged_plain, 2)},
         "launches_of_the_staged_schedule": stage_rows,
+        "unfused_comparator": {
+            "what": "the same 7 layers, layer by layer, replayed from HIP graphs: fbq_linear_unfused (quantized main path, "
+                    "then t = x.A, then y += t.B as launches of their own: 21 launches per step), fbq_linear (7) and the "
+                    "branch-free twins (7)",
+            "us_per_step_unfused": round(tg_unfused["median"] * 1e3, 3),
+            "us_per_step_fused": round(tg_layer["median"] * 1e3, 3),
+            "us_per_step_branch_free": round(tg_layer_plain["median"] * 1e3, 3),
+            "extra_time_removed_by_fusion_pct": round(100 * (tg_unfused["median"] - tg_layer["median"]) /
+                                                      max(1e-9, tg_unfused["median"] - tg_layer_plain["median"]), 1),
+            "paper": "60 % of the extra inference time (Sec. 4.3; RTX 3090, its own kernels, whole model): context, not a comparison"},
         "roofline": {"bound": "hbm", "kernel": "fbq_gemv_kernel, the launch serving " + dom["launch"],
                      "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["frac_of_hbm_peak"],
                      "traffic": traffic, "traffic_source": f"quoted from the committed rocprofv3 summary {TRAFFIC_PROFILE} "

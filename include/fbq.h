@@ -209,6 +209,22 @@ fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, const void *A
                                  void *qweight_out, void *scales_out, void *zeros_out, fbq_stream stream);
 
 /*
+ * fbq_linear_unfused - comparator, not the product path: the conventional arrangement of a quantized
+ * layer with a low-rank sub-branch that Sec. 3.2 describes and Sec. 4.3 replaces (Fig. 4, left).  Same
+ * arguments and result as fbq_linear for M <= 16, computed as three launches: the quantized main path
+ * y = x . Wq^T (this library's kernel without the sub-branch), t = x . A rounded to fp16 as a
+ * stand-alone kernel's output is, and y += t . B, which reads y back and writes it again.  The time it
+ * takes beyond the branch-free layer, against what fbq_linear takes beyond it, is the share of the
+ * sub-branch's cost that the fusion removes (the paper reports 60 % for its kernels, Sec. 4.3).
+ *   workspace: fbq_workspace_bytes(d, M) bytes as for fbq_linear (its first M r fp16 hold t).
+ * Errors: as fbq_linear; FBQ_ERR_UNSUPPORTED for M > 16.  Differs from fbq_linear by the fp16
+ * rounding of t (about 2^-11 relative on the sub-branch's share of y).
+ */
+fbq_status fbq_linear_unfused(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
+                              const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
+                              size_t workspace_bytes, fbq_stream stream);
+
+/*
  * fbq_measure_read_stream - measurement aid, not part of the method.  One launch that reads every
  * 16-byte piece of buf[0, bytes) once and writes nothing.  Timed like the decode kernels (back to back
  * on a stream, over buffers no cache holds) it gives what the memory system delivers to a launch of

@@ -187,6 +187,23 @@ hipError_t launch_one(const LinearArgs &a, hipStream_t s)
 
 }  // namespace fbq
 
+extern "C" fbq_status fbq_linear_unfused(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
+                                         const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
+                                         size_t workspace_bytes, fbq_stream stream)
+{
+    LinearArgs a;
+    const fbq_status st = check_layer(d, M, x, qweight, scales, zeros, At, Bt, y, workspace, workspace_bytes, &a);
+    if (st != FBQ_OK) return st;
+    if (M > kDecodeMaxM) return FBQ_ERR_UNSUPPORTED;
+    if (d->r > 0 && workspace_bytes < (size_t)M * d->r * sizeof(uint16_t)) return FBQ_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    LinearArgs main_path = a;                           // the quantized layer without its sub-branch ...
+    main_path.r = 0; main_path.At = nullptr; main_path.Bt = nullptr;
+    hipError_t e = launch_one(main_path, s);
+    if (e == hipSuccess && d->r > 0) e = launch_unfused_branch(a, (uint16_t *)workspace, s);   // ... and the sub-branch on top
+    return hip_status(e);
+}
+
 extern "C" fbq_status fbq_linear(const fbq_desc *d, int M, const void *x, const void *qweight, const void *scales,
                                  const void *zeros, const void *At, const void *Bt, void *y, void *workspace,
                                  size_t workspace_bytes, fbq_stream stream)

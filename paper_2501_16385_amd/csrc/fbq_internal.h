@@ -63,6 +63,8 @@ hipError_t launch_quantize(const fbq_desc &d, const uint16_t *W, const uint16_t 
                            uint16_t *Dt16 = nullptr, int ldt = 0, float gain = 0.0f);
 
 hipError_t launch_read_stream(const void *buf, size_t bytes, hipStream_t stream);
+// the sub-branch as two launches of its own on top of a y the main path has written (t: [M][r] fp16 scratch)
+hipError_t launch_unfused_branch(const LinearArgs &a, uint16_t *t, hipStream_t stream);
 
 // Arguments of one reconstruction iteration (validated): see fbq_train_step.
 struct TrainArgs {

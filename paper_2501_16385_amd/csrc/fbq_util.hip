@@ -286,4 +286,62 @@ hipError_t launch_read_stream(const void *buf, size_t bytes, hipStream_t stream)
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ conventional sub-branch (comparator)
+
+// The arrangement the fused kernel replaces (Sec. 3.2, Fig. 4 left): after the quantized main path has written
+// y, the sub-branch runs as launches of its own - t = x.A, rounded to fp16 as a stand-alone kernel's output is,
+// then y += t.B, which reads y back and writes it again.  Plain kernels: this path exists to be measured against.
+
+// t[m][j] = sum_k x[m][k] At[j][k]: one block per (column j, token m), 256 threads along K.
+__global__ __launch_bounds__(256) void fbq_unfused_down_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ At,
+                                                               uint16_t *__restrict__ t, int K, int r)
+{
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    __shared__ float part[4];
+    const int j = blockIdx.x, m = blockIdx.y, tid = threadIdx.x;
+    const uint4 *xr = reinterpret_cast<const uint4 *>(x + (size_t)m * K), *ar = reinterpret_cast<const uint4 *>(At + (size_t)j * K);
+    float acc = 0.0f;
+    for (int i = tid; i < K / 8; i += 256) {
+        const uint4 a = xr[i], b = ar[i];
+        const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, aw[q]), __builtin_bit_cast(h2, bw[q]), acc, false);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+    if ((tid & 63) == 0) part[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) t[(size_t)m * r + j] = __builtin_bit_cast(uint16_t, (_Float16)(part[0] + part[1] + part[2] + part[3]));
+}
+
+// y[m][n] += sum_j t[m][j] Bt[n][j]: one thread per output, t of the token in LDS.
+__global__ __launch_bounds__(256) void fbq_unfused_up_kernel(const uint16_t *__restrict__ t, const uint16_t *__restrict__ Bt,
+                                                             uint16_t *__restrict__ y, int N, int r)
+{
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    __shared__ uint32_t tl[kMaxRank / 2];
+    const int m = blockIdx.y, n = blockIdx.x * 256 + threadIdx.x;
+    for (int i = threadIdx.x; i < r / 2; i += 256) tl[i] = reinterpret_cast<const uint32_t *>(t + (size_t)m * r)[i];
+    __syncthreads();
+    if (n >= N) return;
+    const uint4 *br = reinterpret_cast<const uint4 *>(Bt + (size_t)n * r);
+    float acc = (float)__builtin_bit_cast(_Float16, y[(size_t)m * N + n]);
+    for (int i = 0; i < r / 8; ++i) {
+        const uint4 b = br[i];
+        const uint32_t bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, tl[4 * i + q]), __builtin_bit_cast(h2, bw[q]), acc, false);
+    }
+    y[(size_t)m * N + n] = __builtin_bit_cast(uint16_t, (_Float16)acc);
+}
+
+hipError_t launch_unfused_branch(const LinearArgs &a, uint16_t *t, hipStream_t stream)
+{
+    hipLaunchKernelGGL(fbq_unfused_down_kernel, dim3(a.r, a.M), dim3(256), 0, stream, a.x, a.At, t, a.K, a.r);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(fbq_unfused_up_kernel, dim3(ceil_div(a.N, 256), a.M), dim3(256), 0, stream, t, a.Bt, a.y, a.N, a.r);
+    return hipGetLastError();
+}
+
 }  // namespace fbq

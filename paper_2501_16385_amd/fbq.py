@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libfbq.so")
 _lib: Optional[ctypes.CDLL] = None
 
 EXPORTED_SYMBOLS = ["fbq_status_string", "fbq_check_desc", "fbq_packed_bytes", "fbq_workspace_bytes", "fbq_pack",
-                    "fbq_linear", "fbq_linear_static", "fbq_linear_group", "fbq_reconstruct", "fbq_unpack_codes", "fbq_quantize_feedback",
+                    "fbq_linear", "fbq_linear_static", "fbq_linear_unfused", "fbq_linear_group", "fbq_reconstruct", "fbq_unpack_codes", "fbq_quantize_feedback",
                     "fbq_train_workspace_bytes", "fbq_gram", "fbq_train_step", "fbq_test_set_spin_limit",
                     "fbq_measure_read_stream"]
 
@@ -79,6 +79,8 @@ def load() -> ctypes.CDLL:
         lib.fbq_linear.argtypes = [dp, i32] + [vp] * 8 + [sz, vp]
         lib.fbq_linear_static.restype = i32
         lib.fbq_linear_static.argtypes = [dp, i32] + [vp] * 8
+        lib.fbq_linear_unfused.restype = i32
+        lib.fbq_linear_unfused.argtypes = [dp, i32] + [vp] * 8 + [sz, vp]
         lib.fbq_measure_read_stream.restype = i32
         lib.fbq_measure_read_stream.argtypes = [vp, sz, vp]
         lib.fbq_test_set_spin_limit.restype = i32
@@ -210,6 +212,25 @@ def linear(layer: DeviceLayer, x, y=None, workspace=None, stream=None):
                            _dev_ptr(layer.zeros), _dev_ptr(layer.At), _dev_ptr(layer.Bt), _dev_ptr(y), _dev_ptr(workspace),
                            wbytes, _stream(stream))
     _check(rc, "fbq_linear")
+    return y
+
+
+def linear_unfused(layer: DeviceLayer, x, y=None, workspace=None, stream=None):
+    """fbq_linear_unfused: the comparator of Sec. 3.2 - main path, down-projection and read-modify-write
+    up-projection as three launches (up to 16 tokens)."""
+    import torch
+    d = layer.desc
+    M = int(x.shape[0])
+    if y is None:
+        y = torch.empty((M, d.N), dtype=torch.float16, device=x.device)
+    need = workspace_bytes(d, M)
+    if workspace is None and need:
+        workspace = torch.zeros(need, dtype=torch.uint8, device=x.device)
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load().fbq_linear_unfused(ctypes.byref(d.c()), M, _dev_ptr(x), _dev_ptr(layer.qweight), _dev_ptr(layer.scales),
+                                   _dev_ptr(layer.zeros), _dev_ptr(layer.At), _dev_ptr(layer.Bt), _dev_ptr(y), _dev_ptr(workspace),
+                                   wbytes, _stream(stream))
+    _check(rc, "fbq_linear_unfused")
     return y
 
 
