@@ -16,6 +16,7 @@ hipError_t launch_reconstruct(const fbq_desc &, const uint32_t *, const uint16_t
 hipError_t launch_quantize(const fbq_desc &, const uint16_t *, const uint16_t *, const uint16_t *, uint32_t *, uint16_t *, uint16_t *,
                            hipStream_t, uint16_t *, uint16_t *, int, float) { return hipErrorNotSupported; }
 hipError_t launch_read_stream(const void *, size_t, hipStream_t) { return hipErrorNotSupported; }
+hipError_t launch_unfused_branch(const LinearArgs &, uint16_t *, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_gram(int, int, const uint16_t *, float, uint16_t *, void *, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_train_step(const TrainArgs &, hipStream_t) { return hipErrorNotSupported; }
 size_t train_workspace_bytes(int, int, int, int) { return 256; }
