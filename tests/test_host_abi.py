@@ -65,6 +65,10 @@ def test_linear_argument_errors_without_launch():
     static = lambda M, x: lib.fbq_linear_static(ctypes.byref(d.c()), M, x, ok, ok, ok, ok, ok, ok, None)
     assert static(0, ok) == 2 and static(17, ok) == 3 and static(1, None) == 1 and static(1, odd) == 4
     assert lib.fbq_linear_static(None, 1, ok, ok, ok, ok, ok, ok, ok, None) == 1
+    # the comparator (conventional three-launch sub-branch) validates like fbq_linear and stops at 16 tokens
+    unfused = lambda M, x, ws, wb: lib.fbq_linear_unfused(ctypes.byref(d.c()), M, x, ok, ok, ok, ok, ok, ok, ws, wb, None)
+    assert unfused(0, ok, ok, 1 << 20) == 2 and unfused(1, None, ok, 1 << 20) == 1 and unfused(1, odd, ok, 1 << 20) == 4
+    assert unfused(1, ok, ok, 8) == 5 and unfused(17, ok, ok, 1 << 20) == 3
     assert lib.fbq_unpack_codes(ctypes.byref(d.c()), None, ok, None) == 1
     assert lib.fbq_reconstruct(ctypes.byref(d.c()), ok, ok, ok, None, ok, ok, None) == 1
     assert lib.fbq_quantize_feedback(ctypes.byref(d.c()), ok, ok, ok, odd, ok, ok, None) == 4
