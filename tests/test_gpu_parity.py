@@ -377,6 +377,9 @@ PREFILL_CASES = [
     (300, 1408, 24, 34),              # 16 + 16 + 2: the last two tokens through the GEMV
     (768, 5120, 128, 300),
     (320, 2304, 256, 129),
+    (300, 1408, 24, 100),             # a rank that is not a multiple of 64: the up-projection's operands straight from memory
+    (257, 256, 8, 70),
+    (520, 1280, 96, 200),
 ]
 
 
