@@ -637,19 +637,23 @@ static_assert(kMaxSlices == kSumSlices, "the summing blocks ask for every slice 
 static_assert((size_t)(kMaxSlices + 1) * kTokens * kMaxRank * 8 <= kStaticScratchBytes, "the static scratch must hold the largest few-token hand-over");
 size_t small_m_workspace_bytes(int K, int r) { (void)K; return (size_t)(kMaxSlices + 1) * kTokens * r * 8; }
 
-static int tiles_per_block_of(int total_tiles, int preparing_blocks, int bits)
+static int tiles_per_block_of(int total_tiles, int preparing_blocks, int passes)
 {
-    // Blocks run one per compute unit, in rounds; a block's time grows with its tiles plus about one
-    // tile's worth of fixed work (arranging the activations, the up-projection, the reduction).  So: the
-    // tile count that makes rounds x (tiles + 1) smallest, the blocks that do the down-projection
-    // counted in (they hold a compute unit each while they run).  4096 rows: two tiles in one round
-    // instead of one tile in a round and a bit; q/k/v together: four tiles in one round instead of
-    // three in two; gate/up together: three tiles in two full rounds rather than four in one and a half.
-    (void)bits;
-    const int max_tiles = kMaxTiles;
+    // Blocks run one per compute unit, in rounds; a block's time grows with passes x (tiles + about one tile's
+    // worth of fixed work: arranging the activations, the reduction).  The blocks that do the down-projection come
+    // first in the grid and are gone after about two such units - which only matters where they and the
+    // consumers together do not fit the GPU at once: then some consumers start that much later.  (Counting them
+    // as full blocks of a round, as an earlier version did, chose one tile per block for long K with few rows:
+    // 28672 -> 8192 at 16 tokens 58 us, with two tiles 46; 13824 -> 5120 28.6 and 24.7.)  So: the tile count that
+    // makes rounds x passes x (tiles + 1), plus that delay where it applies, smallest.  4096 rows: two tiles in
+    // one round beside the preparing blocks instead of one tile and a late start; q/k/v together: four tiles
+    // instead of three for the same reason; gate/up together: three tiles in two full rounds rather than four in
+    // one and a half; 11008 -> 4096: one tile per block (16.3 us against 17.9 with two).
+    constexpr int kPrepUnits = 2;
     int best = 1, best_cost = 1 << 30;
-    for (int t = 1; t <= max_tiles; ++t) {
-        const int cost = ceil_div(ceil_div(total_tiles, t) + preparing_blocks, cu_count()) * (t + 1);
+    for (int t = 1; t <= kMaxTiles; ++t) {
+        const int consumers = ceil_div(total_tiles, t);
+        const int cost = ceil_div(consumers, cu_count()) * passes * (t + 1) + (consumers + preparing_blocks > cu_count() ? kPrepUnits : 0);
         if (cost < best_cost) { best = t; best_cost = cost; }
     }
     return best;
@@ -681,7 +685,7 @@ hipError_t launch_gemv_small_m(const LinearArgs *layers, int n_layers, hipStream
     int preparing = 0;
     for (int i = 0; i < n_layers; ++i)
         if (layers[i].r > 0) preparing += ceil_div(layers[i].r, 16) * (ceil_div(layers[i].K, slice_length(layers[i].K)) + 1);
-    const int tpb = tiles_per_block_of(total_tiles, preparing, first.bits);
+    const int tpb = tiles_per_block_of(total_tiles, preparing, ceil_div(first.K / kGroup, kPassGroups));
     SmallGroup g;
     g.n_layers = n_layers;
     int row_blocks = 0;                                  // widest row of the grid
