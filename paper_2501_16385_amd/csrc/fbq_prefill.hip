@@ -552,7 +552,36 @@ __global__ __launch_bounds__(256 * KG) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
     }
 
-    // single store of y: accumulator register v of a lane holds row 8*(v/4) + 4*h + v%4, column `col`
+    // store of y: accumulator register v of a lane holds row 8*(v/4) + 4*h + v%4, column `col`
+    if (p.ksplit == 1 && p.N % 8 == 0) {
+        // Stored straight from the accumulators, an instruction writes two 64-byte pieces of two rows, ninety-six such
+        // instructions per wave, and the address unit is the busy one again.  Each wave turns its tile round in LDS
+        // instead (its own 32*TM rows of 64 fp16, 144 bytes apart so that the two halves of the wave fall on different
+        // banks) and writes whole 128-byte row pieces, 16 bytes per lane, eight rows per instruction.
+        constexpr int kOutRow = 64 * 2 + 16;
+        static_assert(kWavesN * kBM * kOutRow <= (int)sizeof(lds_all), "the waves' output tiles must fit the activation buffers");
+        static_assert(kTN == 2, "a wave's output rows are 64 columns wide");
+        unsigned char *const out = &lds_all[0][0][0] + wave * (kBM * kOutRow);
+        block_barrier();                                // everybody is done with what LDS held before
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < kTN; ++tn)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = tm * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+                    *reinterpret_cast<half_t *>(out + row * kOutRow + (tn * 32 + col) * 2) = (half_t)acc[tm][tn][v];
+                }
+        // (the wave reads what itself wrote: LDS keeps a wave's accesses in order)
+#pragma unroll
+        for (int i = 0; i < kBM / 8; ++i) {
+            const int row = i * 8 + (lane >> 3), piece = lane & 7;
+            const uint4 v = *reinterpret_cast<const uint4 *>(out + row * kOutRow + piece * 16);
+            const int m = m0 + row, n = nw + piece * 8;
+            if (m < p.M && n < p.N) *reinterpret_cast<uint4 *>(p.y + (size_t)m * p.N + n) = v;
+        }
+        return;
+    }
 #pragma unroll
     for (int tn = 0; tn < kTN; ++tn) {
         const int n = nw + tn * 32 + col;
