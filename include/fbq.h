@@ -78,7 +78,8 @@ size_t fbq_packed_bytes(const fbq_desc *d);
 /* Bytes of device scratch fbq_linear needs for M tokens.  M <= 2: the down-projection t = x.A on its
  * way from the blocks that compute it to the blocks that use it, as tagged 8-byte words, one per token,
  * column of A and K slice (0 when r == 0).  3 <= M <= 64: the same hand-over for 16 token rows, per
- * K slice and summed (0 when r == 0); the tokens are served 16 at a time.  M > 64: the activations
+ * K slice and summed, once for every 16 tokens or part of them (0 when r == 0) - unless the layer is so large that
+ * 17..64 tokens take the path of M > 64.  M > 64: the activations
  * re-ordered for the matrix cores (M rounded up to 128 rows of K fp16), t as two fp16 halves and its
  * partial sums, and, where the launch splits K over blocks, fp32 partial outputs (up to 4 x M x N);
  * not 0 even when r == 0.  0 for an invalid descriptor or M < 1. */
@@ -107,9 +108,10 @@ fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *sca
  * count (packed words streamed once per token, unpacked in registers; the down-projection runs in
  * the same launch, one column of A per block as a small job in front of the block's first tile).  3 <= M <= 16 streams the packed words once for all
  * tokens against a 16-token matrix-core tile, also in ONE launch whose first blocks do the
- * down-projection; 17 <= M <= 64 takes that launch 16 tokens at a time (the packed words are read
- * once per 16 tokens, which at these counts is still cheaper than unpacking them into fp16 tiles; one or two
- * tokens left over go through the GEMV).  M > 64 runs the fp16 MFMA GEMM after a pass that
+ * down-projection; 17 <= M <= 64 is the same launch with the sets of 16 tokens side by side (the packed words are read
+ * once per 16 tokens, which for most layers is still cheaper there than unpacking them into fp16 tiles; one or two
+ * tokens left over go through the GEMV; a layer so large that reading it two to four times costs more takes the path
+ * of M > 64 instead).  M > 64 runs the fp16 MFMA GEMM after a pass that
  * re-orders x and a separate down-projection; a layer with too few output tiles to fill the GPU has
  * its K range split over up to 4 blocks per tile, summed in fp32 by a last small launch.
  *   x         device [M, K] fp16             qweight, scales, zeros, At, Bt: device, layout above

@@ -42,13 +42,32 @@ extern "C" size_t fbq_packed_bytes(const fbq_desc *d)
     return (size_t)d->N * row_words(d->K, d->bits) * sizeof(uint32_t);
 }
 
+// 17..64 tokens: whether the few-token kernel, the sets of 16 tokens side by side in one launch, is expected to beat
+// the prefill GEMM.  It streams the packed words once per set, in passes of 4096 along K; the GEMM reads them once
+// but has a long start (three launches, few tiles) and a K loop per tile that few tiles cannot hide.  Fitted to
+// measurements of both at 32, 48 and 64 tokens on ten shapes (us; MC = millions of codes, K counted in whole passes
+// for the sets): the sets take about 2 + sets x (2.2 + 0.165 MC), the GEMM 30 + 0.135 MC + 1.5 K / 1024 (with INT3
+// and INT4 alike).  Examples, sets / GEMM: 8192 -> 28672 at 32 tokens 84 / 71, at 64 160 / 83; 28672 -> 8192 at 32
+// tokens 80 / 101, at 48 122 / 101; 4096 -> 11008 at 64 tokens 35 / 41; 13824 -> 5120 at 48 tokens 50 / 62.
+static bool sets_beat_gemm(int M, int N, int K)
+{
+    const int sets = (M + kDecodeMaxM - 1) / kDecodeMaxM;
+    const double k_passes = 4096.0 * ((K + 4095) / 4096);
+    const double cost_sets = 2.0 + sets * (2.2 + 0.165e-6 * N * k_passes);
+    const double cost_gemm = 30.0 + 0.135e-6 * N * (double)K + 1.5 * K / 1024.0;
+    return cost_sets <= cost_gemm;
+}
+
 extern "C" size_t fbq_workspace_bytes(const fbq_desc *d, int M)
 {
     if (fbq_check_desc(d) != FBQ_OK || M < 1) return 0;
     if (M <= kPerTokenMaxM) return d->r == 0 ? 0 : decode_workspace_bytes(M, d->K, d->r);
-    // up to 64 tokens go through the few-token kernel 16 at a time (one or two left over through the GEMV, whose
-    // hand-over words fit the same space); nothing to hand over without a sub-branch
-    if (M <= kChunkedMaxM) return small_m_workspace_bytes(d->K, d->r);
+    // up to 64 tokens go through the few-token kernel 16 at a time, all in one launch, every 16 tokens with hand-over
+    // words of their own (one or two left over go through the GEMV afterwards, whose words fit the first set);
+    // nothing to hand over without a sub-branch
+    if (M <= kDecodeMaxM) return small_m_workspace_bytes(d->K, d->r);
+    if (M <= kChunkedMaxM && sets_beat_gemm(M, d->N, d->K))
+        return (size_t)((M + kDecodeMaxM - 1) / kDecodeMaxM) * small_m_workspace_bytes(d->K, d->r);
     return prefill_workspace_bytes(M, d->N, d->K, d->r);      // holds the re-ordered activations even when r == 0
 }
 
@@ -163,23 +182,31 @@ static hipError_t launch_prefill(const LinearArgs &a, hipStream_t s)
 
 // One or two tokens: streaming GEMV, one pass per token, with the down-projection inside the launch.
 // 3..16 tokens: one pass over the packed words against a matrix-core tile of tokens.  17..64 tokens:
-// the same, 16 tokens at a time (the prefill GEMM has too few tiles to fill the GPU there: 103 us
-// against 4 x 11 us for a 4096 x 4096 layer at 64 tokens).  More: the prefill GEMM.
+// the same, 16 tokens at a time, the sets of 16 side by side in ONE launch as if they were layers of a group
+// (the prefill GEMM has too few tiles to fill the GPU there), unless the layer is so large that reading its packed words
+// three or four times costs more than the GEMM's long start.  More: the prefill GEMM.
 hipError_t launch_one(const LinearArgs &a, hipStream_t s)
 {
     if (a.M <= kPerTokenMaxM) return launch_gemv_decode(&a, 1, s);
     if (a.M <= kDecodeMaxM) return launch_gemv_small_m(&a, 1, s);
-    if (a.M <= kChunkedMaxM) {
-        hipError_t e = hipSuccess;
-        for (int m0 = 0; m0 < a.M && e == hipSuccess; m0 += kDecodeMaxM) {
+    if (a.M <= kChunkedMaxM && sets_beat_gemm(a.M, a.N, a.K)) {
+        static_assert(kChunkedMaxM <= kMaxSmallGroup * kDecodeMaxM, "the sets of 16 tokens must fit one grouped launch");
+        LinearArgs set[kMaxSmallGroup], rest = a;
+        const size_t ws_each = small_m_workspace_bytes(a.K, a.r);
+        int n = 0;
+        rest.M = 0;
+        for (int m0 = 0; m0 < a.M; m0 += kDecodeMaxM) {
             LinearArgs c = a;
             c.M = std::min(kDecodeMaxM, a.M - m0);
             c.x = a.x + (size_t)m0 * a.K;
             c.y = a.y + (size_t)m0 * a.N;
-            // the chunks reuse the workspace one after the other on the stream (every launch marks its words with its own
-            // tag, whichever kernel wrote there before); one or two tokens left over go through the GEMV, which is cheaper
-            e = c.M <= kPerTokenMaxM ? launch_gemv_decode(&c, 1, s) : launch_gemv_small_m(&c, 1, s);
+            if (c.M <= kPerTokenMaxM) { rest = c; continue; }   // one or two tokens left over: the GEMV is cheaper
+            c.workspace = a.workspace ? (char *)a.workspace + (size_t)n * ws_each : nullptr;
+            set[n++] = c;
         }
+        hipError_t e = launch_gemv_small_m(set, n, s);
+        // (the GEMV runs behind the grouped launch on the stream and marks its words with its own tag, whoever wrote there before)
+        if (e == hipSuccess && rest.M > 0) e = launch_gemv_decode(&rest, 1, s);
         return e;
     }
     return launch_prefill(a, s);

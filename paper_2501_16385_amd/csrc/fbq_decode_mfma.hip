@@ -665,21 +665,26 @@ static int slice_length(int K)
     return std::max(1024, ceil_div(ceil_div(K, kMaxSlices), 32 * kPrepWaves) * (32 * kPrepWaves));
 }
 
-// Layers may share the launch when they read the same activations and need the same kernel
-// instance; a branch-free layer never joins layers with a sub-branch.
+// What the kernel itself needs of the layers of one launch: the same instance (a branch-free layer never joins layers
+// with a sub-branch).  Activations, token count, outputs and workspace are per layer.
+static bool same_instance(const LinearArgs &a, const LinearArgs &b)
+{
+    return a.K == b.K && a.bits == b.bits && (a.r > 0) == (b.r > 0);
+}
+
+// Layers of a grouped call share the launch when they also read the same activations.
 bool small_m_group_compatible(const LinearArgs &a, const LinearArgs &b)
 {
-    return a.x == b.x && a.K == b.K && a.M == b.M && a.bits == b.bits && (a.r > 0) == (b.r > 0);
+    return a.x == b.x && a.M == b.M && same_instance(a, b);
 }
 
 hipError_t launch_gemv_small_m(const LinearArgs *layers, int n_layers, hipStream_t stream)
 {
     if (n_layers < 1 || n_layers > kMaxSmallGroup) return hipErrorInvalidValue;
     const LinearArgs &first = layers[0];
-    if (first.M < 1 || first.M > kTokens) return hipErrorInvalidValue;
     int total_tiles = 0;
     for (int i = 0; i < n_layers; ++i) {
-        if (!small_m_group_compatible(first, layers[i])) return hipErrorInvalidValue;
+        if (layers[i].M < 1 || layers[i].M > kTokens || !same_instance(first, layers[i])) return hipErrorInvalidValue;
         total_tiles += ceil_div(layers[i].N, 16);
     }
     int preparing = 0;

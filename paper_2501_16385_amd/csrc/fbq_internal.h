@@ -17,7 +17,7 @@ constexpr int kChunk = 64 * kLaneCodes;   // codes one wave-wide load covers (20
 constexpr int kMaxRank = 256;
 constexpr int kMaxK = 16 * kChunk;      // 32768: the decode kernel keeps a wave's activations in registers
 constexpr int kDecodeMaxM = 16;
-constexpr int kChunkedMaxM = 64;     // up to here the few-token kernel, 16 tokens at a time, beats the prefill GEMM
+constexpr int kChunkedMaxM = 64;     // up to here the few-token kernel, 16 tokens at a time, can beat the prefill GEMM
 constexpr int kPerTokenMaxM = 2;     // up to here the GEMV streams the weights once per token; above, the matrix-core tile wins
 constexpr int kMaxTSlices = 4;       // K slices of the decode down-projection: kMaxK / (4 passes * 2048)
 constexpr int kMaxGroup = 8;         // layers one grouped decode launch can serve

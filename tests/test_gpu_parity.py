@@ -173,7 +173,9 @@ def test_large_layer_sweep_sampled_rows(bits, N, K):
     rows = np.sort(rng.choice(N, 96, replace=False))
     want = orc.linear(x, orc.pack(codes[rows], bits), s[rows], z[rows], A, np.ascontiguousarray(B[:, rows]), bits, spec.group)
     dev = fbq.upload_layer(fbq.pack(fbq.Desc(N, K, 128, bits), codes, s, z, A, B))
-    for M in (1, 16, 256):
+    # (33 and 48 tokens: sets of 16 side by side in one few-token launch, plus one token through the GEMV - or, for the
+    # largest of these layers, the prefill GEMM, which is then the cheaper way)
+    for M in (1, 16, 33, 48, 256):
         got = gpu_y(dev, np.ascontiguousarray(x[:M]))
         assert got.shape == (M, N) and np.all(np.isfinite(got))
         assert_matches_oracle(got[:, rows], want[:M], f"M={M}", tol=Y_TOL)

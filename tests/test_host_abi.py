@@ -29,7 +29,8 @@ def test_sizes_and_status_strings():
     assert fbq.workspace_bytes(d, 1) > 0 and fbq.workspace_bytes(fbq.Desc(4096, 4096, 0, 4), 1) == 0
     assert fbq.workspace_bytes(d, 16) >= 16 * 64 * 4
     assert fbq.workspace_bytes(fbq.Desc(4096, 4096, 0, 4), 100) >= 128 * 4096 * 2   # prefill keeps a copy of x
-    assert fbq.workspace_bytes(d, 40) == fbq.workspace_bytes(d, 9)                    # 17..64 tokens: the few-token kernel, 16 at a time
+    assert fbq.workspace_bytes(d, 40) == 3 * fbq.workspace_bytes(d, 9)                # 17..64 tokens: the few-token kernel, every 16 tokens with words of their own
+    assert fbq.workspace_bytes(d, 64) == 4 * fbq.workspace_bytes(d, 16) and fbq.workspace_bytes(d, 17) == 2 * fbq.workspace_bytes(d, 16)
     assert fbq.workspace_bytes(d, 9) >= 4 * 16 * d.r * 8                               # tagged partial sums of t, one set per K slice
     assert fbq.workspace_bytes(fbq.Desc(4096, 4096, 0, 4), 9) == 0                      # nothing to hand over without a sub-branch
     assert fbq.workspace_bytes(d, 2) == 2 * fbq.workspace_bytes(d, 1)        # one set of tagged words per token
