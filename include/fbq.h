@@ -81,7 +81,7 @@ size_t fbq_packed_bytes(const fbq_desc *d);
  * K slice and summed, once for every 16 tokens or part of them (0 when r == 0) - unless the layer is so large that
  * 17..64 tokens take the path of M > 64.  M > 64: the activations
  * re-ordered for the matrix cores (M rounded up to 128 rows of K fp16), t as two fp16 halves and its
- * partial sums, and, where the launch splits K over blocks, fp32 partial outputs (up to 4 x M x N);
+ * partial sums, and, where the launch splits K over blocks, fp32 partial outputs (up to 8 x M x N);
  * not 0 even when r == 0.  0 for an invalid descriptor or M < 1. */
 size_t fbq_workspace_bytes(const fbq_desc *d, int M);
 
@@ -113,7 +113,7 @@ fbq_status fbq_pack(const fbq_desc *d, const uint8_t *codes, const uint16_t *sca
  * tokens left over go through the GEMV; a layer so large that reading it two to four times costs more takes the path
  * of M > 64 instead).  M > 64 runs the fp16 MFMA GEMM after a pass that
  * re-orders x and a separate down-projection; a layer with too few output tiles to fill the GPU has
- * its K range split over up to 4 blocks per tile, summed in fp32 by a last small launch.
+ * its K range split over up to 8 blocks per tile, summed in fp32 by a last small launch.
  *   x         device [M, K] fp16             qweight, scales, zeros, At, Bt: device, layout above
  *   y         device [M, N] fp16, overwritten
  *   workspace device, >= fbq_workspace_bytes(d, M) bytes (may be NULL when that is 0).  Zero-fill it
