@@ -382,6 +382,8 @@ PREFILL_CASES = [
     (300, 1408, 24, 100),             # a rank that is not a multiple of 64: the up-projection's operands straight from memory
     (257, 256, 8, 70),
     (520, 1280, 96, 200),
+    (1000, 2048, 0, 50),              # four sets of tokens in one few-token launch (16 + 16 + 16 + 2 through the GEMV), branch-free
+    (130, 2304, 40, 61),              # 16 + 16 + 16 + 13, wide-ish rank
 ]
 
 
