@@ -819,8 +819,9 @@ static size_t thl_bytes(int M, int r) { return ((size_t)M * 2 * r * sizeof(uint1
 static size_t down_partial_bytes(int M, int K, int r) { return ((size_t)down_slices(M, K) * M * r * sizeof(float) + 255) & ~(size_t)255; }
 
 // K is split over blocks only where 64-row tiles give at most half as many tiles as there are CUs (256 assumed: the
-// rule must not depend on the device, the workspace is sized without one): up to eight ways, never below eight
-// super-steps per group of waves.  Such a layer (256 tokens into a few thousand outputs over a long K) would leave
+// rule must not depend on the device, the workspace is sized without one): up to eight ways, never below four
+// super-steps per group of waves (with eight as the limit, 4096 x 4096 at 65 to 256 tokens ran on half as many blocks
+// and took 37 - 42 us instead of 33 - 37).  Such a layer (256 tokens into a few thousand outputs over a long K) would leave
 // most of the GPU idle otherwise; everywhere else the two groups of a block are all the split there is and nothing
 // but y is written.  M * N must be a multiple of 4 for the summing launch.
 constexpr int kMaxKSplit = 8;
@@ -829,7 +830,7 @@ static int ksplit_of(int M, int N, int K)
     const long tiles = (long)ceil_div(N, kBN) * ceil_div(M, 64);
     if (tiles > 128 || N % 4 != 0 || (K / kBK) % 2 != 0) return 1;
     int split = (int)std::min<long>(kMaxKSplit, 256 / tiles);
-    while (split > 1 && (K / kBK) / (2 * split) < 8) --split;
+    while (split > 1 && (K / kBK) / (2 * split) < 4) --split;
     return std::max(1, split);
 }
 
