@@ -21,7 +21,7 @@ batch of exactly --steps steps, and mean and minimum are printed beside it.
 set in INT3 at 1, 4, 8 and 16 tokens; the two MLP shapes at 1024 tokens; the large-layer sweep at
 1, 16 and 256 tokens in both bit widths), each with its branch-free twin, and
 `measured_read_peak_GBps` what a kernel that only reads gets out of the memory system at the launch
-sizes of the decode path.  Prints ONE JSON line (the design doc explains every field).
+sizes of the decode path.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -474,7 +474,7 @@ def main():
                          "branch_overhead_byte_floor_pct": round(lsb3.byte_floor(m) * 100, 2)})
         del lsb3
         torch.cuda.empty_cache()
-        # the staged INT4 set at 16 tokens (few-token kernel), for comparison with the round before
+        # the staged INT4 set at 16 tokens (few-token kernel)
         lsb16 = LayerSetBench(torch, fbq, specs, CONFIG, 16, args.copies)
         t16 = lsb16.timed(lsb16.schedule(lsb16.stages, 16), 300, 30, 3)
         b16 = lsb16.bytes_per_step(16)
