@@ -49,7 +49,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--batches", type=int, default=5, help="how often the --steps steps are timed (median, min and mean are reported)")
+    ap.add_argument("--batches", type=int, default=0,
+                    help="how often the --steps steps are timed (median, min and mean are reported); default: 5, more when --steps "
+                         "is small, so that about 2000 steps are timed in all")
     ap.add_argument("--copies", type=int, default=0, help="distinct copies of the layer set (default: > 2 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the other benchmark configurations and kernel families")
@@ -338,7 +340,10 @@ def main():
         sys.exit(3)
     fbq.load()
     torch.cuda.set_device(0)
-    K, W, R = args.steps, args.warmup, max(1, args.batches)
+    # (a batch of a few dozen steps lasts under a millisecond: its median over five batches moves by several per cent from
+    # run to run, over a hundred batches it does not)
+    K, W = args.steps, args.warmup
+    R = args.batches if args.batches > 0 else max(5, min(101, (2000 // max(1, K)) | 1))
 
     # ---------------------------------------------------------------- headline: Llama2-7B decode set, INT4, rank 64, one token
     CONFIG = 1                                               # seeds: position of this workload in the benchmark's list, from 0
