@@ -62,6 +62,11 @@ def load() -> ctypes.CDLL:
     if _lib is None:
         if not os.path.exists(_LIB_PATH):
             raise FileNotFoundError(f"{_LIB_PATH} not built: run `python -m paper_2501_16385_amd.build`")
+        # The library and torch must share ONE HIP runtime: the streams and device pointers this binding hands over are
+        # torch's.  torch's wheel brings its own copy of the runtime; loaded first, it also serves this library, but
+        # when this library came first the process ended up with two runtimes and every launch on a torch stream
+        # failed with a launch error.
+        import torch  # noqa: F401
         lib = ctypes.CDLL(_LIB_PATH)
         vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
         dp = ctypes.POINTER(_CDesc)

@@ -137,3 +137,22 @@ def test_host_pack_writes_the_documented_layout(bits):
     with pytest.raises(fbq.FbqError) as e:
         fbq.pack(d, bad, s, z, A, B)
     assert e.value.code == 2
+
+
+def test_loading_the_library_first_still_leaves_one_hip_runtime():
+    """The binding hands torch's streams and pointers to the library, so both must sit on the same HIP runtime; torch's
+    wheel has a copy of its own.  In a fresh process that touches this package before torch, only one copy may end
+    up mapped (with two, every launch on a torch stream failed)."""
+    import subprocess
+    import sys
+    code = (
+        "import paper_2501_16385_amd as fbq\n"
+        "fbq.load()\n"
+        "import torch\n"
+        "paths = {line.split()[-1] for line in open('/proc/self/maps') if 'libamdhip64' in line}\n"
+        "print(len(paths), sorted(paths))\n"
+        "assert len(paths) == 1, paths\n"
+    )
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0, res.stdout + res.stderr
