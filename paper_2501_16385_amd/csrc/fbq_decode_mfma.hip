@@ -429,8 +429,8 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
     // pass needs is requested up front.  Every offset that depends on the group is part of the
     // bounds-checked per-lane offset of its buffer load: groups past the end of K read activation
     // operands and sums beyond their buffers, i.e. zeros without a memory access, and add nothing
-    // (their weights and scales are whatever follows in the row, or zero behind the last row: finite
-    // either way).
+    // (their weights are whatever follows in the row, or zero behind the last row: finite either way;
+    // their scales and zeros are replaced by zero).
     const int passes = (p.G + kPassGroups - 1) / kPassGroups;
     for (int pass = 0; pass < passes; ++pass) {
         const int g0 = pass * kPassGroups + wave * kWaveGroups;
@@ -517,7 +517,11 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
                 float4_t D = zero4;
 #pragma unroll
                 for (int t = 0; t < 4; ++t) D = mfma(xa[gi][t], b[t], D);
-                const float s = (float)half_at(sc[ti], gi + odd[ti]), z = (float)half_at(zp[ti], gi + odd[ti]);
+                // (a group past the end of K: what was read in its place is the next row's, or - behind the last row,
+                // where the number of scales is odd - the two bytes that follow the array, which may hold anything,
+                // a NaN included; its sums are zero, and so must its scale and zero be)
+                const bool there = g0 + gi < p.G;           // wave-uniform
+                const float s = there ? (float)half_at(sc[ti], gi + odd[ti]) : 0.0f, z = there ? (float)half_at(zp[ti], gi + odd[ti]) : 0.0f;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) acc[ti][v] = fmaf(s, D[v] - fmaf(z, X[gi][v], XS[gi][v]), acc[ti][v]);
             }

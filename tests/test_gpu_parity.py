@@ -432,3 +432,37 @@ def test_prefill_benchmark_shapes_sampled_rows():
                           spec.bits, spec.group)
         assert_matches_oracle(got[:, rows], want, spec.name, tol=Y_TOL)
         assert np.all(np.isfinite(got))
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+@pytest.mark.parametrize("N,K,r,M", [(33, 1408, 8, 6), (633, 1408, 64, 3), (257, 128, 8, 16), (33, 1408, 8, 1), (633, 1408, 64, 40),
+                                     (257, 384, 8, 70)])
+def test_nothing_behind_an_array_reaches_the_result(bits, N, K, r, M):
+    """Every array of the layer sits inside a larger buffer filled with an fp16 NaN pattern.  A kernel that lets a value
+    from beyond an array into its arithmetic - even multiplied by zero - shows it as a NaN in y.  (N x K/128 odd: the
+    scale and zero arrays end in the middle of a dword, and a few-token launch once took the half behind them for the
+    scale of a group past the end of K.)"""
+    import torch
+    import paper_2501_16385_amd as fbq
+    spec = spec_of(N, K, r, bits)
+    L = make_oracle_layer(spec, config=23)
+    x = fbq_synth.make_x(spec, M, 23, 0)
+    want = oracle_y(L, x)
+    dev = to_device_layer(L)
+
+    def embedded(t):
+        if t is None:
+            return None
+        flat = t.contiguous().view(torch.uint8).reshape(-1)
+        pad = 4096
+        big = torch.full((flat.numel() + 2 * pad,), 0x7D, dtype=torch.uint8, device=t.device)
+        big[pad:pad + flat.numel()] = flat
+        return big[pad:pad + flat.numel()].view(t.dtype).view(t.shape)
+
+    framed = fbq.DeviceLayer(dev.desc, embedded(dev.qweight), embedded(dev.scales), embedded(dev.zeros), embedded(dev.At), embedded(dev.Bt))
+    xd = embedded(torch.from_numpy(x.view(np.int16)).cuda()).view(torch.float16)
+    y = fbq.linear(framed, xd)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    assert np.all(np.isfinite(got)), f"{int((~np.isfinite(got)).sum())} outputs are not finite"
+    assert_matches_oracle(got, want, f"{N}x{K} r={r} M={M}", tol=Y_TOL)
