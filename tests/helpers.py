@@ -47,6 +47,24 @@ def to_device_layer(L: OracleLayer):
     return fbq.upload_layer(fbq.pack(d, L.codes, L.scales, L.zeros, L.A, L.B))
 
 
+def framed_in_nan(t):
+    """The same device tensor inside a larger buffer filled with an fp16 NaN pattern (0x7D7D), 16-byte aligned: whatever
+    a kernel reads from beyond the tensor and lets into its arithmetic - even multiplied by zero - shows as a NaN."""
+    import torch
+    if t is None:
+        return None
+    flat = t.contiguous().view(torch.uint8).reshape(-1)
+    pad = 4096
+    big = torch.full((flat.numel() + 2 * pad,), 0x7D, dtype=torch.uint8, device=t.device)
+    big[pad:pad + flat.numel()] = flat
+    return big[pad:pad + flat.numel()].view(t.dtype).view(t.shape)
+
+
+def framed_layer(dev_layer):
+    import paper_2501_16385_amd as fbq
+    return fbq.DeviceLayer(dev_layer.desc, *(framed_in_nan(t) for t in (dev_layer.qweight, dev_layer.scales, dev_layer.zeros, dev_layer.At, dev_layer.Bt)))
+
+
 GUARD = 256            # elements (y) / bytes (workspace) of sentinel on either side of a buffer the library writes
 Y_SENTINEL = 0x7D7D    # an fp16 NaN: nothing the kernels compute, and visible if an output is never written
 WS_SENTINEL = 0xA5

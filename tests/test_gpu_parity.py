@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import fbq_synth
-from helpers import assert_matches_oracle, gpu_y, make_oracle_layer, oracle_y, rel_l2, to_device_layer
+from helpers import assert_matches_oracle, framed_in_nan, framed_layer, gpu_y, make_oracle_layer, oracle_y, rel_l2, to_device_layer
 from oracle import fbq_oracle as orc
 
 pytestmark = pytest.mark.gpu
@@ -448,21 +448,36 @@ def test_nothing_behind_an_array_reaches_the_result(bits, N, K, r, M):
     L = make_oracle_layer(spec, config=23)
     x = fbq_synth.make_x(spec, M, 23, 0)
     want = oracle_y(L, x)
-    dev = to_device_layer(L)
-
-    def embedded(t):
-        if t is None:
-            return None
-        flat = t.contiguous().view(torch.uint8).reshape(-1)
-        pad = 4096
-        big = torch.full((flat.numel() + 2 * pad,), 0x7D, dtype=torch.uint8, device=t.device)
-        big[pad:pad + flat.numel()] = flat
-        return big[pad:pad + flat.numel()].view(t.dtype).view(t.shape)
-
-    framed = fbq.DeviceLayer(dev.desc, embedded(dev.qweight), embedded(dev.scales), embedded(dev.zeros), embedded(dev.At), embedded(dev.Bt))
-    xd = embedded(torch.from_numpy(x.view(np.int16)).cuda()).view(torch.float16)
+    framed = framed_layer(to_device_layer(L))
+    xd = framed_in_nan(torch.from_numpy(x.view(np.int16)).cuda()).view(torch.float16)
     y = fbq.linear(framed, xd)
     torch.cuda.synchronize()
     got = y.cpu().numpy()
     assert np.all(np.isfinite(got)), f"{int((~np.isfinite(got)).sum())} outputs are not finite"
     assert_matches_oracle(got, want, f"{N}x{K} r={r} M={M}", tol=Y_TOL)
+
+
+def test_random_shapes_framed_in_nan():
+    """Sixty seeded random shapes (both bit widths, 1 to 300 tokens, ragged N, any K and rank the library takes), every
+    array framed in NaN patterns, y between guard bands: finite, within the bar, bit-identical when repeated.  (Two
+    sweeps of this kind, of a few hundred cases each, found the two bytes behind an odd-sized scale array.)"""
+    rng = np.random.Generator(np.random.Philox(4711))
+    token_counts = [1, 2, 3, 5, 9, 15, 16, 17, 18, 19, 31, 32, 33, 35, 47, 48, 50, 63, 64, 65, 66, 96, 100, 128, 129, 200, 256, 300]
+    for case in range(60):
+        bits = int(rng.choice([3, 4]))
+        K = 128 * int(rng.integers(1, 41)) if rng.random() > 0.15 else 128 * int(rng.integers(41, 120))
+        N = int(rng.integers(1, 1400)) if rng.random() > 0.3 else 8 * int(rng.integers(1, 200))
+        N = max(1, min(N, 2_000_000 // K))
+        r = int(rng.choice([0, 8, 16, 24, 32, 40, 64, 96, 128, 192, 256]))
+        M = int(rng.choice(token_counts))
+        what = f"case {case}: {N}x{K} r={r} M={M} INT{bits}"
+        print(what, flush=True)
+        spec = spec_of(N, K, r, bits)
+        L = make_oracle_layer(spec, config=600 + case)
+        x = fbq_synth.make_x(spec, M, 600 + case, 0)
+        want = oracle_y(L, x)
+        dev = framed_layer(to_device_layer(L))
+        got = gpu_y(dev, x)
+        assert np.all(np.isfinite(got)), what
+        assert rel_l2(got, want) <= Y_TOL, what
+        assert np.array_equal(gpu_y(dev, x), got), what
