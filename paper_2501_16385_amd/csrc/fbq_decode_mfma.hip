@@ -534,7 +534,7 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
             const int j = js * 32 + q * 8;
             // t[token c][j .. j + 7]: eight words {t, launch tag} (four 16-byte device-scope loads), written long ago
             // as a rule.  Should the tags not turn up, the lane computes its eight values itself.
-            float t[8];
+            float t[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};   // (taps past r stay zero also when nothing is ever polled)
             bool ready = false;
             const int off = j < p.r ? (c * p.r + j) * 8 : kNowhere;
             for (int spin = 0; spin < p.spin_limit && !ready; ++spin) {

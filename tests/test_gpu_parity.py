@@ -348,7 +348,8 @@ def test_replayed_graph_follows_new_activations(bits, M):
 
 
 @pytest.mark.parametrize("bits", [4, 3])
-@pytest.mark.parametrize("N,K,r,M", [(300, 1408, 24, 1), (300, 1408, 24, 2), (130, 2304, 40, 5), (96, 1408, 24, 16)])
+@pytest.mark.parametrize("N,K,r,M", [(300, 1408, 24, 1), (300, 1408, 24, 2), (130, 2304, 40, 5), (96, 1408, 24, 16),
+                                     (5859, 2048, 24, 3), (2619, 1408, 8, 48), (500, 1024, 72, 9)])
 def test_fallback_when_the_down_projection_never_arrives(bits, N, K, r, M):
     """Consumers wait a bounded number of polls for the words that carry t and then compute their share
     themselves.  The test hook fbq_test_set_spin_limit(-1) makes them do so at once: every kernel still
@@ -357,7 +358,7 @@ def test_fallback_when_the_down_projection_never_arrives(bits, N, K, r, M):
     import paper_2501_16385_amd as fbq
     spec = spec_of(N, K, r, bits)
     L = make_oracle_layer(spec, config=21)
-    dev = to_device_layer(L)
+    dev = framed_layer(to_device_layer(L))                 # (taps past a rank that is no multiple of 32 must not pick anything up)
     x = fbq_synth.make_x(spec, M, 21, 0)
     before = fbq.load().fbq_test_set_spin_limit(-1)
     try:
