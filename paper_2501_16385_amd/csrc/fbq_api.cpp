@@ -33,6 +33,7 @@ extern "C" fbq_status fbq_check_desc(const fbq_desc *d)
     if (d->r > kMaxRank || d->K > kMaxK) return FBQ_ERR_UNSUPPORTED;
     // the kernels address a layer's buffers with 32-bit byte offsets and keep 2^30 as "nowhere"
     if ((size_t)d->N * row_words(d->K, d->bits) * sizeof(uint32_t) >= ((size_t)1 << 30)) return FBQ_ERR_UNSUPPORTED;
+    if ((size_t)d->N * d->r * sizeof(uint16_t) >= ((size_t)1 << 30)) return FBQ_ERR_UNSUPPORTED;   // (B^T likewise)
     return FBQ_OK;
 }
 
