@@ -50,7 +50,7 @@ typedef enum {
     FBQ_OK = 0,
     FBQ_ERR_NULL = 1,        /* a required pointer is NULL */
     FBQ_ERR_SHAPE = 2,       /* N, K, M < 1; r < 0; K % group; K % 32; r % 8; a code above qmax */
-    FBQ_ERR_UNSUPPORTED = 3, /* bits not in {3, 4}; group != 128; r > 256; K > 32768; packed codes of 1 GiB or more */
+    FBQ_ERR_UNSUPPORTED = 3, /* bits not in {3, 4}; group != 128; r > 256; K > 32768; packed codes, or B, of 1 GiB or more */
     FBQ_ERR_ALIGN = 4,       /* a device pointer is not 16-byte aligned */
     FBQ_ERR_WORKSPACE = 5,   /* workspace smaller than fbq_workspace_bytes() */
     FBQ_ERR_HIP = 6          /* the HIP runtime refused a launch (hipGetLastError) */
