@@ -335,7 +335,8 @@ __device__ __forceinline__ uint32_t small_m_launch_tag()
 // ------------------------------------------------------------------ fused kernel
 
 // BITS: 3 or 4.  T: 16-row tiles per block.  BRANCH: r > 0.
-template <int BITS, int T, bool BRANCH>
+// TAIL: some layer of the launch has an odd number of scales (N G odd): see where scale and zero are taken.
+template <int BITS, int T, bool BRANCH, bool TAIL>
 __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const SmallGroup g)
 {
     constexpr int kPiece = BITS == 4 ? 16 : 12;         // bytes of 32 codes
@@ -510,6 +511,16 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
             zp[ti] = uint3_t{(uint32_t)__builtin_amdgcn_ds_bpermute(from_quad, (int)zp[ti].x), (uint32_t)__builtin_amdgcn_ds_bpermute(from_quad, (int)zp[ti].y),
                              (uint32_t)__builtin_amdgcn_ds_bpermute(from_quad, (int)zp[ti].z)};
             }
+            // Groups past the end of K add nothing as long as what is read in their place is finite: the next row's
+            // scales, or zero beyond the descriptor.  One half is neither: with N G odd the descriptor, whole dwords,
+            // also admits the two bytes behind the array, which may hold anything, a NaN included.  That half is cleared
+            // (any row within a pass's 32 groups of the array's end can have fetched it).
+            if (TAIL && ((p.N * p.G) & 1)) {               // block-uniform; an instance of its own, so that layers with an even number of scales run the code they always ran
+                const int n = min((tile0 + ti) * 16 + c, p.N - 1);
+                const int kk = ((p.N * p.G) >> 1) - ((n * p.G + g0) >> 1);   // which of the lane's three dwords is the array's last
+                sc[ti] = uint3_t{kk == 0 ? sc[ti].x & 0xFFFFu : sc[ti].x, kk == 1 ? sc[ti].y & 0xFFFFu : sc[ti].y, kk == 2 ? sc[ti].z & 0xFFFFu : sc[ti].z};
+                zp[ti] = uint3_t{kk == 0 ? zp[ti].x & 0xFFFFu : zp[ti].x, kk == 1 ? zp[ti].y & 0xFFFFu : zp[ti].y, kk == 2 ? zp[ti].z & 0xFFFFu : zp[ti].z};
+            }
 #pragma unroll
             for (int gi = 0; gi < kWaveGroups; ++gi) {
                 half8_t b[4];
@@ -517,11 +528,7 @@ __global__ __launch_bounds__(64 * kMainWaves) void fbq_small_m_kernel(const Smal
                 float4_t D = zero4;
 #pragma unroll
                 for (int t = 0; t < 4; ++t) D = mfma(xa[gi][t], b[t], D);
-                // (a group past the end of K: what was read in its place is the next row's, or - behind the last row,
-                // where the number of scales is odd - the two bytes that follow the array, which may hold anything,
-                // a NaN included; its sums are zero, and so must its scale and zero be)
-                const bool there = g0 + gi < p.G;           // wave-uniform
-                const float s = there ? (float)half_at(sc[ti], gi + odd[ti]) : 0.0f, z = there ? (float)half_at(zp[ti], gi + odd[ti]) : 0.0f;
+                const float s = (float)half_at(sc[ti], gi + odd[ti]), z = (float)half_at(zp[ti], gi + odd[ti]);
 #pragma unroll
                 for (int v = 0; v < 4; ++v) acc[ti][v] = fmaf(s, D[v] - fmaf(z, X[gi][v], XS[gi][v]), acc[ti][v]);
             }
@@ -607,16 +614,16 @@ static int cu_count()
     return cus;
 }
 
-template <int BITS, int T>
+template <int BITS, int T, bool TAIL>
 static hipError_t launch_tiles(const SmallGroup &g, bool branch, dim3 grid, hipStream_t stream)
 {
     // (the INT3 three- and four-tile instances without the branch come out of the compiler with spills of
     // 160 bytes and more; the ones with the branch spill nothing or 36 bytes, and with r = 0 they do the same work)
     if constexpr (BITS == 3 && T >= 3) {
-        hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true>), grid, dim3(64 * kMainWaves), 0, stream, g);
+        hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true, TAIL>), grid, dim3(64 * kMainWaves), 0, stream, g);
     } else {
-        if (branch) hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true>), grid, dim3(64 * kMainWaves), 0, stream, g);
-        else hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, false>), grid, dim3(64 * kMainWaves), 0, stream, g);
+        if (branch) hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, true, TAIL>), grid, dim3(64 * kMainWaves), 0, stream, g);
+        else hipLaunchKernelGGL((fbq_small_m_kernel<BITS, T, false, TAIL>), grid, dim3(64 * kMainWaves), 0, stream, g);
     }
     return hipGetLastError();
 }
@@ -626,11 +633,17 @@ static hipError_t launch_bits(const SmallGroup &g, int row_blocks, hipStream_t s
 {
     const bool branch = g.layer[0].r > 0;
     const dim3 grid(row_blocks, g.n_layers);
-    switch (g.layer[0].tiles_per_block) {
-    case 1: return launch_tiles<BITS, 1>(g, branch, grid, stream);
-    case 2: return launch_tiles<BITS, 2>(g, branch, grid, stream);
-    case 3: return launch_tiles<BITS, 3>(g, branch, grid, stream);
-    default: return launch_tiles<BITS, 4>(g, branch, grid, stream);
+    bool tail = false;                                  // a layer whose scale array ends in the middle of a dword
+    for (int i = 0; i < g.n_layers; ++i) tail = tail || (((long)g.layer[i].N * g.layer[i].G) & 1);
+    switch (g.layer[0].tiles_per_block * 2 + (tail ? 1 : 0)) {
+    case 2: return launch_tiles<BITS, 1, false>(g, branch, grid, stream);
+    case 3: return launch_tiles<BITS, 1, true>(g, branch, grid, stream);
+    case 4: return launch_tiles<BITS, 2, false>(g, branch, grid, stream);
+    case 5: return launch_tiles<BITS, 2, true>(g, branch, grid, stream);
+    case 6: return launch_tiles<BITS, 3, false>(g, branch, grid, stream);
+    case 7: return launch_tiles<BITS, 3, true>(g, branch, grid, stream);
+    case 8: return launch_tiles<BITS, 4, false>(g, branch, grid, stream);
+    default: return launch_tiles<BITS, 4, true>(g, branch, grid, stream);
     }
 }
 
