@@ -79,7 +79,8 @@ size_t fbq_packed_bytes(const fbq_desc *d);
  * way from the blocks that compute it to the blocks that use it, as tagged 8-byte words, one per token,
  * column of A and K slice (0 when r == 0).  3 <= M <= 64: the same hand-over for 16 token rows, per
  * K slice and summed, once for every 16 tokens or part of them (0 when r == 0) - unless the layer is so large that
- * 17..64 tokens take the path of M > 64.  M > 64: the activations
+ * 17..64 tokens take the path of M > 64.  M > 64: room for those hand-over words (left alone by this path, so
+ * that one workspace can serve calls of every token count), then the activations
  * re-ordered for the matrix cores (M rounded up to 128 rows of K fp16), t as two fp16 halves and its
  * partial sums, and, where the launch splits K over blocks, fp32 partial outputs (up to 8 x M x N);
  * not 0 even when r == 0.  0 for an invalid descriptor or M < 1. */
@@ -218,7 +219,8 @@ fbq_status fbq_quantize_feedback(const fbq_desc *d, const void *W, const void *A
  * stand-alone kernel's output is, and y += t . B, which reads y back and writes it again.  The time it
  * takes beyond the branch-free layer, against what fbq_linear takes beyond it, is the share of the
  * sub-branch's cost that the fusion removes (the paper reports 60 % for its kernels, Sec. 4.3).
- *   workspace: fbq_workspace_bytes(d, M) bytes as for fbq_linear (its first M r fp16 hold t).
+ *   workspace: fbq_workspace_bytes(d, M) bytes as for fbq_linear (its first M r fp16 hold t); one of its own, not
+ *   one that fbq_linear calls also use (those expect to find nothing but their own hand-over words there).
  * Errors: as fbq_linear; FBQ_ERR_UNSUPPORTED for M > 16.  Differs from fbq_linear by the fp16
  * rounding of t (about 2^-11 relative on the sub-branch's share of y).
  */

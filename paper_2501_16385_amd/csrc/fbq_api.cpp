@@ -59,6 +59,15 @@ static bool sets_beat_gemm(int M, int N, int K)
     return cost_sets <= cost_gemm;
 }
 
+// In front of what the prefill path keeps in a workspace: room for the hand-over words of the decode paths, which the
+// prefill path never touches.  A workspace that serves calls of every token count then only ever holds words with a
+// launch's tag, or the zeros it started with, where the decode kernels look for tags - never activations or partial
+// sums that happen to look like one.
+static size_t handover_reserve(int K, int r)
+{
+    return r > 0 ? (size_t)kMaxSmallGroup * small_m_workspace_bytes(K, r) : 0;
+}
+
 extern "C" size_t fbq_workspace_bytes(const fbq_desc *d, int M)
 {
     if (fbq_check_desc(d) != FBQ_OK || M < 1) return 0;
@@ -69,7 +78,7 @@ extern "C" size_t fbq_workspace_bytes(const fbq_desc *d, int M)
     if (M <= kDecodeMaxM) return small_m_workspace_bytes(d->K, d->r);
     if (M <= kChunkedMaxM && sets_beat_gemm(M, d->N, d->K))
         return (size_t)((M + kDecodeMaxM - 1) / kDecodeMaxM) * small_m_workspace_bytes(d->K, d->r);
-    return prefill_workspace_bytes(M, d->N, d->K, d->r);      // holds the re-ordered activations even when r == 0
+    return handover_reserve(d->K, d->r) + prefill_workspace_bytes(M, d->N, d->K, d->r);      // holds the re-ordered activations even when r == 0
 }
 
 // ------------------------------------------------------------------ host-side packing
@@ -174,8 +183,10 @@ fbq_status check_layer(const fbq_desc *d, int M, const void *x, const void *qwei
     return FBQ_OK;
 }
 
-static hipError_t launch_prefill(const LinearArgs &a, hipStream_t s)
+static hipError_t launch_prefill(const LinearArgs &call, hipStream_t s)
 {
+    LinearArgs a = call;
+    a.workspace = (char *)call.workspace + handover_reserve(call.K, call.r);
     hipError_t e = launch_prepass_prefill(a, s);
     if (e == hipSuccess) e = launch_gemm_prefill(a, s);
     return e;

@@ -482,3 +482,29 @@ def test_random_shapes_framed_in_nan():
         assert np.all(np.isfinite(got)), what
         assert rel_l2(got, want) <= Y_TOL, what
         assert np.array_equal(gpu_y(dev, x), got), what
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_one_workspace_for_every_token_count(bits):
+    """A workspace zero-filled once and then used by calls of every token count, in any order: the prefill path must
+    leave the hand-over words of the decode paths alone (they may only ever hold zeros or words with a launch's tag),
+    and every call must give what it gives on a workspace of its own."""
+    import torch
+    import paper_2501_16385_amd as fbq
+    spec = spec_of(520, 1408, 64, bits)
+    L = make_oracle_layer(spec, config=29)
+    dev = to_device_layer(L)
+    counts = [100, 5, 1, 40, 70, 16, 2, 33, 300, 9]
+    ws = torch.zeros(max(fbq.workspace_bytes(dev.desc, M) for M in counts), dtype=torch.uint8, device="cuda")
+    front = 4 * fbq.workspace_bytes(dev.desc, 16)          # the hand-over words of up to four sets of 16 tokens
+    for M in counts:
+        x = fbq_synth.make_x(spec, M, 29, M)
+        xd = torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16)
+        before = ws[:front].clone()
+        y = fbq.linear(dev, xd, workspace=ws)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        assert_matches_oracle(got, oracle_y(L, x), f"M={M} on the shared workspace", tol=Y_TOL)
+        assert np.array_equal(got, gpu_y(dev, x))
+        if fbq.workspace_bytes(dev.desc, M) > front:         # a call that took the prefill path
+            assert torch.equal(ws[:front], before), f"M={M}: the prefill path wrote into the hand-over words"
