@@ -83,7 +83,9 @@ size_t fbq_packed_bytes(const fbq_desc *d);
  * that one workspace can serve calls of every token count), then the activations
  * re-ordered for the matrix cores (M rounded up to 128 rows of K fp16), t as two fp16 halves and its
  * partial sums, and, where the launch splits K over blocks, fp32 partial outputs (up to 8 x M x N);
- * not 0 even when r == 0.  0 for an invalid descriptor or M < 1. */
+ * not 0 even when r == 0.  0 for an invalid descriptor or M < 1.
+ * The size is NOT monotonic in M (fewer tokens can mean more K slices or a K split with partial outputs): a workspace
+ * meant for several token counts takes the largest of their sizes. */
 size_t fbq_workspace_bytes(const fbq_desc *d, int M);
 
 /*
